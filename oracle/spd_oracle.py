@@ -1,0 +1,275 @@
+"""CPU oracle for the Sync-Point-Drop (SPD) decoder block.  TEST INFRASTRUCTURE ONLY.
+
+Only `tests/`, the smoke check and the bench's `cpu_baseline` leg may import this module;
+the product (the HIP library and its binding) never does, and this module imports nothing
+from the product.  It is slow on purpose: plain NumPy in float64, one step per line, in
+the order and notation of the paper, no blocking, fusion or reordering.
+
+What it computes (arXiv 2502.20727):
+
+* Tensor parallelism splits a decoder block over `tp` devices: query/key/value
+  projections by columns (each device owns N/tp whole heads, Sec. 4.2.3 "head
+  scattering": n(A_i) = N / number_of_devices), the attention output projection by rows
+  (Sec. 4.1.2), the MLP likewise.  Device i therefore produces a *partial* attention
+  output Y_i and a partial MLP output Z_i; a TP block all-reduces each of them (two
+  sync points per block, Sec. 3, Fig. 1a) and equals single-device inference.
+* An SPD block (Sec. 4.1.1, Fig. 3a, block without bias) drops the first all-reduce:
+  device i feeds X + Y_i to its MLP, adds Y_i to its MLP partial *before* the remaining
+  all-reduce and adds X *after* it, so the block output is X + sum_i Y_i + sum_i Z_i
+  with Z_i = MLP_i(X + Y_i).
+* Which blocks are SPD blocks is a per-layer boolean (the outcome of Alg. 1); here it is
+  an input: mask[l] = 1 means block l drops its attention sync point.
+
+The paper says "LLaMA2" and nothing more about the block's inside, so the standard
+LLaMA block is taken: pre-norm RMSNorm (eps inside the square root), rotary embedding in
+the rotate-half convention (pair (j, j + d/2), angle pos * base^(-2j/d)) applied to
+queries and keys, causal softmax attention scaled by 1/sqrt(d) with grouped KV heads
+(query head j uses KV head j // (q_heads / kv_heads)), SwiGLU MLP
+(silu(x Wg) * (x Wu)) Wd, silu(x) = x / (1 + exp(-x)).  The second norm of an SPD block
+acts on X + Y_i (that sum is "fed into MLP input").
+
+The all-reduce is a plain sum over ranks (float64 here, so the order is immaterial).
+Parity status: every function below is pinned by tests/test_oracle_pins.py (dense-block
+equality with SPD off, tp = 1 identity, closed forms, an independent scalar brute force).
+The paper prints no worked numeric example of a block output, and its perplexities
+(Table 1) need trained weights and a text corpus: those are parity unpinned.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+F64 = np.float64
+
+
+@dataclass(frozen=True)
+class Shapes:
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int
+    tp: int = 1
+    rms_eps: float = 1e-5
+    rope_base: float = 10000.0
+
+    @property
+    def q(self) -> int:          # query heads per device, n(A_i) = N / number_of_devices
+        assert self.n_q_heads % self.tp == 0
+        return self.n_q_heads // self.tp
+
+    @property
+    def kv(self) -> int:
+        assert self.n_kv_heads % self.tp == 0
+        return self.n_kv_heads // self.tp
+
+    @property
+    def f(self) -> int:
+        assert self.ffn % self.tp == 0
+        return self.ffn // self.tp
+
+
+# --------------------------------------------------------------------------- elementary steps
+
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean_h(x^2) + eps) * g, row by row."""
+    x = np.asarray(x, F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(g, F64)
+
+
+def rope(v: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
+    """Rotate-half rotary embedding.  v: [T, heads, d]; pos: [T] integer positions.
+
+    For j < d/2 the pair (v[j], v[j + d/2]) is rotated by the angle pos * base^(-2j/d).
+    """
+    v = np.asarray(v, F64)
+    T, H, d = v.shape
+    half = d // 2
+    j = np.arange(half, dtype=F64)
+    theta = base ** (-2.0 * j / d)                       # [d/2]
+    ang = np.asarray(pos, F64)[:, None] * theta[None, :]  # [T, d/2]
+    c = np.cos(ang)[:, None, :]
+    s = np.sin(ang)[:, None, :]
+    lo, hi = v[..., :half], v[..., half:]
+    out = np.empty_like(v)
+    out[..., :half] = lo * c - hi * s
+    out[..., half:] = hi * c + lo * s
+    return out
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def token_positions(positions: Sequence[int], batch: int, q_len: int) -> np.ndarray:
+    """Token b*q_len + t of the call sits at position positions[b] + t of sequence b."""
+    positions = np.asarray(positions, dtype=np.int64)
+    assert positions.shape == (batch,)
+    return (positions[:, None] + np.arange(q_len, dtype=np.int64)[None, :]).reshape(-1)
+
+
+class KVCache:
+    """One device's keys and values of one layer: [batch, kv_heads, max_ctx, d] float64."""
+
+    def __init__(self, batch: int, kv_heads: int, max_ctx: int, head_dim: int):
+        self.k = np.zeros((batch, kv_heads, max_ctx, head_dim), F64)
+        self.v = np.zeros((batch, kv_heads, max_ctx, head_dim), F64)
+
+    def fill(self, k: np.ndarray, v: np.ndarray) -> None:
+        """Load positions [0, n) from natural-layout arrays [batch, kv, n, d]."""
+        n = k.shape[2]
+        self.k[:, :, :n, :] = k
+        self.v[:, :, :n, :] = v
+
+    def copy(self) -> "KVCache":
+        c = KVCache.__new__(KVCache)
+        c.k = self.k.copy()
+        c.v = self.v.copy()
+        return c
+
+
+# --------------------------------------------------------------------------- one device's share
+
+def attention_partial(sh: Shapes, X: np.ndarray, W: Dict[str, np.ndarray], cache: KVCache,
+                      positions: Sequence[int], batch: int, q_len: int,
+                      rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """Device i's partial attention output Y_i  [tokens, hidden]  (or only `rows` of it).
+
+    W holds the device's slices: wq [h, q*d], wk/wv [h, kv*d] (column-wise split),
+    wo [q*d, h] (row-wise split), g1 [h].  Keys and values of every token of the call are
+    appended to `cache` at their positions before any query looks at it.
+    """
+    d, q, kv = sh.head_dim, sh.q, sh.kv
+    group = q // kv
+    T = batch * q_len
+    X = np.asarray(X, F64)
+    assert X.shape == (T, sh.hidden)
+    pos = token_positions(positions, batch, q_len)
+
+    n = rmsnorm(X, W["g1"], sh.rms_eps)
+    K = rope((n @ np.asarray(W["wk"], F64)).reshape(T, kv, d), pos, sh.rope_base)
+    V = (n @ np.asarray(W["wv"], F64)).reshape(T, kv, d)
+    for t in range(T):
+        b = t // q_len
+        cache.k[b, :, pos[t], :] = K[t]
+        cache.v[b, :, pos[t], :] = V[t]
+
+    sel = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
+    Q = rope((n[sel] @ np.asarray(W["wq"], F64)).reshape(len(sel), q, d), pos[sel], sh.rope_base)
+
+    A = np.zeros((len(sel), q, d), F64)
+    for i, t in enumerate(sel):
+        b = t // q_len
+        n_keys = int(pos[t]) + 1                       # causal: key position <= query position
+        for j in range(q):
+            kh = j // group                            # grouped KV heads
+            s = cache.k[b, kh, :n_keys, :] @ Q[i, j] / np.sqrt(d)
+            p = np.exp(s - np.max(s))
+            p = p / np.sum(p)
+            A[i, j] = p @ cache.v[b, kh, :n_keys, :]
+    return A.reshape(len(sel), q * d) @ np.asarray(W["wo"], F64)
+
+
+def mlp_partial(sh: Shapes, R: np.ndarray, W: Dict[str, np.ndarray]) -> np.ndarray:
+    """Device i's partial MLP output Z_i = (silu(m Wg_i) * (m Wu_i)) Wd_i with m = RMSNorm(R)."""
+    m = rmsnorm(R, W["g2"], sh.rms_eps)
+    u = silu(m @ np.asarray(W["wg"], F64)) * (m @ np.asarray(W["wu"], F64))
+    return u @ np.asarray(W["wd"], F64)
+
+
+# --------------------------------------------------------------------------- whole blocks
+
+def block_all_ranks(sh: Shapes, X: np.ndarray, shards: List[Dict[str, np.ndarray]],
+                    caches: List[KVCache], positions: Sequence[int], batch: int, q_len: int,
+                    spd: int, detail: Optional[dict] = None):
+    """One decoder block with every device emulated.  Returns (X', number of sync points).
+
+    spd = 0: TP block, two all-reduces (Sec. 3).  spd = 1: SPD block without bias
+    (Sec. 4.1.1): MLP input X + Y_i, Y_i added before the one remaining all-reduce, X after.
+    """
+    X = np.asarray(X, F64)
+    Y = [attention_partial(sh, X, shards[i], caches[i], positions, batch, q_len)
+         for i in range(sh.tp)]
+    if spd:
+        Z = [mlp_partial(sh, X + Y[i], shards[i]) for i in range(sh.tp)]
+        P = [Y[i] + Z[i] for i in range(sh.tp)]          # Y_i goes in before the sync
+        out = X + sum(P)                                 # X after it
+        syncs = 1
+    else:
+        R = X + sum(Y)                                   # sync point after attention
+        Z = [mlp_partial(sh, R, shards[i]) for i in range(sh.tp)]
+        P = Z
+        out = R + sum(Z)                                 # sync point after the MLP
+        syncs = 2
+    if detail is not None:
+        detail.update(Y=Y, Z=Z, P=P)
+    return out, syncs
+
+
+def block_single_rank(sh: Shapes, X: np.ndarray, shard: Dict[str, np.ndarray], cache: KVCache,
+                      positions: Sequence[int], batch: int, q_len: int, spd: int, rank: int,
+                      slots: np.ndarray, rows: Optional[np.ndarray] = None,
+                      detail: Optional[dict] = None) -> np.ndarray:
+    """The same block seen from one device: the other devices' partial sums are inputs.
+
+    `slots` [tp, tokens, hidden] float64 holds what the peers deliver at a sync point;
+    slot `rank` is overwritten with this device's own partial (twice in a TP block, whose
+    two sync points reuse the peers' buffers).  Returns X' (rows `rows` only if given).
+    """
+    X = np.asarray(X, F64)
+    sel = np.arange(X.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
+    Y = attention_partial(sh, X, shard, cache, positions, batch, q_len, rows=rows)
+    if spd:
+        Z = mlp_partial(sh, X[sel] + Y, shard)
+        slots[rank, sel] = Y + Z
+        out = X[sel] + np.sum(slots[:, sel], axis=0)
+    else:
+        slots[rank, sel] = Y
+        R = X[sel] + np.sum(slots[:, sel], axis=0)
+        Z = mlp_partial(sh, R, shard)
+        slots[rank, sel] = Z
+        out = R + np.sum(slots[:, sel], axis=0)
+    if detail is not None:
+        detail.update(Y=Y, Z=Z)
+    return out
+
+
+def dense_block(sh: Shapes, X: np.ndarray, dense: Dict[str, np.ndarray], cache: KVCache,
+                positions: Sequence[int], batch: int, q_len: int) -> np.ndarray:
+    """Single-device inference of the block: no sharding at all."""
+    one = Shapes(sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, 1,
+                 sh.rms_eps, sh.rope_base)
+    X = np.asarray(X, F64)
+    R = X + attention_partial(one, X, dense, cache, positions, batch, q_len)
+    return R + mlp_partial(one, R, dense)
+
+
+# --------------------------------------------------------------------------- whole models
+
+def model_all_ranks(sh: Shapes, X: np.ndarray, layers: List[List[Dict[str, np.ndarray]]],
+                    caches: List[List[KVCache]], positions: Sequence[int], batch: int,
+                    q_len: int, mask: Sequence[int]):
+    """Run the blocks in order; mask[l] = 1 makes block l an SPD block.  Returns (X', syncs)."""
+    total = 0
+    for l, shards in enumerate(layers):
+        X, s = block_all_ranks(sh, X, shards, caches[l], positions, batch, q_len, int(mask[l]))
+        total += s
+    return X, total
+
+
+def model_single_rank(sh: Shapes, X: np.ndarray, layers: List[Dict[str, np.ndarray]],
+                      caches: List[KVCache], positions: Sequence[int], batch: int, q_len: int,
+                      mask: Sequence[int], rank: int, slots: np.ndarray) -> np.ndarray:
+    for l, shard in enumerate(layers):
+        X = block_single_rank(sh, X, shard, caches[l], positions, batch, q_len, int(mask[l]),
+                              rank, slots)
+    return X
+
+
+def rank_sum(base: Optional[np.ndarray], slots: np.ndarray) -> np.ndarray:
+    """What a kept sync point delivers to every device: base + sum over ranks of the partials."""
+    s = np.sum(np.asarray(slots, F64), axis=0)
+    return s if base is None else np.asarray(base, F64) + s
