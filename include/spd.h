@@ -1,0 +1,214 @@
+/*
+ * spd.h - C ABI of the MI355X (gfx950) Sync-Point-Drop decoder-block library.
+ *
+ * What the library computes (arXiv 2502.20727).  Tensor parallelism splits every decoder
+ * block over `tp_degree` devices: the query/key/value projections by columns (each
+ * device owns n_heads / tp_degree whole heads, Sec. 4.2.3), the attention output
+ * projection and the MLP down projection by rows (Sec. 4.1.2).  Device i produces a
+ * partial attention output Y_i and a partial MLP output Z_i, and a TP block all-reduces
+ * both (two sync points per block, Sec. 3, Fig. 1a).  An SPD block (Sec. 4.1.1, Fig. 3a,
+ * the design without linear-layer bias) drops the first all-reduce: the device feeds
+ * X + Y_i to its MLP, adds Y_i to Z_i before the remaining all-reduce and X after it,
+ * giving X + sum_i Y_i + sum_i Z_i.  A per-layer mask (the outcome of Alg. 1) says which
+ * blocks are SPD blocks.
+ *
+ * This library runs ONE device's share ("rank") of such blocks on one GPU.  A sync point
+ * that is kept is not a collective between GPUs: it is a sum, in HBM, over `tp_degree`
+ * buffers ("slots") of which this rank writes its own and the caller supplies the
+ * others.  With rank = SPD_ALL_RANKS the library runs every rank's share in turn and so
+ * emulates the whole TP group exactly.
+ *
+ * Block internals (the paper only says "LLaMA2"): pre-norm RMSNorm with eps inside the
+ * square root; rotary embedding, rotate-half convention (pair (j, j + d/2) rotated by
+ * pos * rope_base^(-2j/d)), on queries and keys; causal softmax attention with scale
+ * 1/sqrt(head_dim) over a KV cache, grouped KV heads (query head j reads KV head
+ * j / (q_heads / kv_heads)); SwiGLU MLP (silu(x Wg) * (x Wu)) Wd.
+ *
+ * General conventions
+ *  - Plain C, no exceptions cross the boundary.  Every int-returning call returns SPD_OK
+ *    (0) or a negative SPD_E* code; spd_strerror() names it.  All argument checks run on
+ *    the host before anything is enqueued, so a failing call has launched nothing.
+ *  - The caller owns every buffer.  Forward calls allocate nothing, free nothing and never
+ *    synchronise; they only enqueue kernels on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream).  spd_workspace_init() is the only call that copies from
+ *    host memory to the device.
+ *  - "device" pointers must be device memory of the current HIP device; "host" pointers
+ *    are ordinary host memory.  Buffers must be 256-byte aligned.
+ *  - Tokens of a call are ordered [batch][q_len]; token b*q_len + t sits at position
+ *    positions[b] + t of sequence b.  The residual stream (x_in, x_out, slots) is fp32
+ *    for both dtypes.
+ *  - An spd_ctx is immutable after spd_create() and may be shared between threads; use
+ *    one workspace per stream that runs concurrently.
+ */
+#ifndef SPD_H
+#define SPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPD_F32 0   /* weights, KV cache and activations fp32; plain reference-style kernels */
+#define SPD_BF16 1  /* weights, KV cache and inter-kernel activations bf16; fp32 accumulation */
+
+#define SPD_OK 0
+#define SPD_EINVAL (-1)       /* NULL pointer, bad shape, rank, batch, position or mask value */
+#define SPD_EUNSUPPORTED (-2) /* a valid request this build does not implement (see spd_create) */
+#define SPD_EHIP (-3)         /* a HIP call or kernel launch reported an error */
+
+#define SPD_ALL_RANKS (-1)
+#define SPD_MAX_BATCH 64
+
+typedef struct spd_config {
+    int32_t hidden;      /* model width h */
+    int32_t n_q_heads;   /* query heads of the whole model */
+    int32_t n_kv_heads;  /* KV heads of the whole model (== n_q_heads: MHA; fewer: grouped) */
+    int32_t head_dim;    /* d */
+    int32_t ffn;         /* SwiGLU inner width F of the whole model */
+    int32_t n_layers;
+    int32_t tp_degree;   /* must divide n_q_heads, n_kv_heads and ffn */
+    int32_t dtype;       /* SPD_F32 | SPD_BF16 */
+    int32_t max_batch;   /* sequences per call, <= SPD_MAX_BATCH */
+    int32_t max_ctx;     /* KV-cache capacity in positions; a multiple of 32 */
+    int32_t max_tokens;  /* largest batch*q_len of a single call */
+    float rms_eps;       /* 1e-5 for LLaMA2 */
+    float rope_base;     /* 10000 for LLaMA2 */
+} spd_config;
+
+typedef struct spd_ctx spd_ctx;
+
+/* Byte sizes the caller allocates.  All are multiples of 256. */
+typedef struct spd_sizes {
+    size_t weight_bytes;    /* one rank's packed shard of one layer */
+    size_t kv_bytes;        /* one rank's KV cache of one layer (max_batch x max_ctx) */
+    size_t workspace_bytes; /* scratch for one stream */
+} spd_sizes;
+
+/* One layer's weights on the host, fp32, in the y = x W convention (rows = inputs).
+ * `ld_*` is the row stride in elements.  For spd_pack_shard() these are the dense
+ * (unsharded) matrices: wq [h, Hq*d], wk/wv [h, Hkv*d], wo [Hq*d, h], wg/wu [h, F],
+ * wd [F, h]; for spd_pack_shard_local() they are one rank's slices.  g1/g2 [h] are the
+ * gains of the two RMSNorms.  With dtype SPD_BF16 every weight must already be exactly
+ * representable in bf16 (the packer copies values, it never rounds). */
+typedef struct spd_layer_weights {
+    const float *wq, *wk, *wv, *wo, *wg, *wu, *wd, *g1, *g2;
+    int64_t ld_q, ld_k, ld_v, ld_o, ld_g, ld_u, ld_d;
+} spd_layer_weights;
+
+/* Optional taps: when a pointer is non-NULL the block copies that intermediate of the
+ * LAST rank it ran, in fp32 natural layout, to the device buffer.  For tests. */
+typedef struct spd_taps {
+    float *q;    /* [tokens, q*d]  rotated queries of the rank's heads */
+    float *attn; /* [tokens, q*d]  attention output before the O projection */
+    float *y;    /* [tokens, h]    partial attention output Y_r */
+    float *u;    /* [tokens, f]    SwiGLU output silu(gate) * up of the rank's FFN slice */
+} spd_taps;
+
+/* ---------------------------------------------------------------- context (host only) */
+
+/* Validates the configuration and builds an immutable context; touches no device.
+ * SPD_EINVAL: NULL, non-positive sizes, odd head_dim, tp_degree not dividing the head
+ * counts or ffn, n_q_heads not a multiple of n_kv_heads, max_batch > SPD_MAX_BATCH,
+ * max_ctx not a multiple of 32.  SPD_EUNSUPPORTED: n_kv_heads < tp_degree (a KV head
+ * shared by several ranks); unknown dtype; for SPD_BF16: hidden or head_dim not a
+ * multiple of 32, ffn / tp_degree not a multiple of 16, more than 16 query heads per
+ * KV head. */
+int spd_create(const spd_config *cfg, spd_ctx **out);
+void spd_destroy(spd_ctx *ctx);
+int spd_get_config(const spd_ctx *ctx, spd_config *out);
+int spd_get_sizes(const spd_ctx *ctx, spd_sizes *out);
+const char *spd_strerror(int code);
+
+/* ---------------------------------------------------------------- rank indexing (host only)
+ * Sec. 4.2.3: the heads (and FFN columns) of device `rank` are a contiguous block of
+ * N / tp_degree of them.  Each call returns the half-open range [*first, *first + *count). */
+int spd_rank_q_heads(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count);
+int spd_rank_kv_heads(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count);
+int spd_rank_ffn_cols(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count);
+
+/* Number of sync points (rank-sums) a model forward with this mask performs: two for a
+ * block that keeps its attention sync point (mask 0), one for an SPD block (mask 1),
+ * Sec. 3.  mask: host, [n_layers], each 0 or 1.  Returns the count or a negative code. */
+int64_t spd_sync_count(const spd_ctx *ctx, const uint8_t *mask);
+
+/* ---------------------------------------------------------------- packing (host only)
+ * Slices rank `rank`'s heads / FFN columns out of the dense layer and lays them out the
+ * way the kernels stream them (bit-exact copies of the values, zero padding only).
+ * `packed_host` receives weight_bytes bytes; the caller then copies them to the device. */
+int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host);
+/* Same, from matrices that already are one rank's slices. */
+int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *shard, void *packed_host);
+/* Inverse of spd_pack_shard_local(): writes the rank's slices back in natural layout
+ * (pointers in `out` are written through despite the const in the struct). */
+int spd_unpack_shard(const spd_ctx *ctx, const void *packed_host, const spd_layer_weights *out);
+
+/* KV cache <-> natural layout.  k, v: host fp32 [batch, kv_heads_per_rank, n_pos, d],
+ * positions 0 .. n_pos-1 of each sequence (keys already rotated).  `cache_host` is a host
+ * copy of one rank's cache of one layer (kv_bytes bytes); pack leaves other positions as
+ * they are.  batch <= max_batch, n_pos <= max_ctx. */
+int spd_kv_pack(const spd_ctx *ctx, const float *k, const float *v, int32_t batch, int32_t n_pos, void *cache_host);
+int spd_kv_unpack(const spd_ctx *ctx, const void *cache_host, int32_t batch, int32_t n_pos, float *k, float *v);
+
+/* ---------------------------------------------------------------- device calls */
+
+/* Prepares a workspace (device, workspace_bytes): uploads the rotary table and clears the
+ * library's counters.  Call once per workspace before the first forward; synchronises
+ * the stream before returning. */
+int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream);
+
+/* out = base + (slot[0] + slot[1] + ... + slot[n_slots-1]): the partials are summed in
+ * ascending slot order in fp32 and the base is added last (a kept sync point: what an
+ * all-reduce delivers to every device, Sec. 3).  The order is fixed, so results are
+ * bit-reproducible.  base may be NULL (treated as zero), out may alias base.  slots: device, [n_slots][n_elems] fp32
+ * contiguous.  n_slots >= 0, n_elems >= 0 (0 is a no-op). */
+int spd_rank_sum(const spd_ctx *ctx, const float *base, const float *slots, int32_t n_slots,
+                 int64_t n_elems, float *out, void *stream);
+
+/* One decoder block for one rank (or all of them).
+ *   layer          index of the block (only used for error messages and taps)
+ *   spd_flag       1: SPD block (attention sync point dropped, Sec. 4.1.1); 0: TP block
+ *   rank           0 .. tp_degree-1, or SPD_ALL_RANKS
+ *   packed_weights device; the rank's packed shard, or all ranks' shards back to back
+ *                  (stride weight_bytes) with SPD_ALL_RANKS
+ *   kv_cache       device; the rank's cache of this layer, or all ranks' caches back to
+ *                  back (stride kv_bytes).  Keys/values of the call's tokens are appended
+ *                  at their positions before attention reads the cache.
+ *   positions      host, [batch]: position of each sequence's first token of this call;
+ *                  positions[b] + q_len <= max_ctx
+ *   x_in           device, fp32 [batch*q_len, hidden]: the block input X, identical on all ranks
+ *   slots          device, fp32 [tp_degree][batch*q_len, hidden]: the partial sums met at a
+ *                  sync point.  With rank = r the library overwrites slot r only (with Y_r
+ *                  and later Z_r in a TP block, with Y_r + Z_r in an SPD block) and reads
+ *                  the other slots as the peers' contributions; with SPD_ALL_RANKS it
+ *                  writes all of them.
+ *   x_out          device, fp32 [batch*q_len, hidden]; may alias x_in
+ *   workspace      device, initialised by spd_workspace_init()
+ *   taps           NULL or optional debug outputs
+ * Errors: SPD_EINVAL for NULL pointers, rank out of range, spd_flag not 0/1, batch or
+ * batch*q_len beyond the configured maxima, a position that would overflow max_ctx. */
+int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank,
+                      const void *packed_weights, void *kv_cache, const int32_t *positions,
+                      int32_t batch, int32_t q_len, const float *x_in, float *slots,
+                      float *x_out, void *workspace, void *stream, const spd_taps *taps);
+
+/* All blocks in order; block l is an SPD block iff spd_mask[l] == 1 (the per-layer outcome
+ * of Alg. 1; every other value than 0 or 1 is SPD_EINVAL).
+ *   spd_mask       host, [n_layers]
+ *   layer_weights  host array [n_layers] of device pointers (as in spd_block_forward)
+ *   layer_kv       host array [n_layers] of device pointers
+ *   slots          one [tp_degree][tokens, hidden] buffer reused by every layer
+ *   n_rank_sums    NULL or host int64 receiving the number of rank-sums enqueued
+ * x_out may alias x_in.  The rank-sum that ends block l is fused with the first norm's
+ * elementwise work of block l+1. */
+int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
+                      const void *const *layer_weights, void *const *layer_kv,
+                      const int32_t *positions, int32_t batch, int32_t q_len,
+                      const float *x_in, float *slots, float *x_out, void *workspace,
+                      void *stream, int64_t *n_rank_sums);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_H */

@@ -135,7 +135,7 @@ class KVCache:
 
 def attention_partial(sh: Shapes, X: np.ndarray, W: Dict[str, np.ndarray], cache: KVCache,
                       positions: Sequence[int], batch: int, q_len: int,
-                      rows: Optional[np.ndarray] = None) -> np.ndarray:
+                      rows: Optional[np.ndarray] = None, detail: Optional[dict] = None) -> np.ndarray:
     """Device i's partial attention output Y_i  [tokens, hidden]  (or only `rows` of it).
 
     W holds the device's slices: wq [h, q*d], wk/wv [h, kv*d] (column-wise split),
@@ -170,13 +170,18 @@ def attention_partial(sh: Shapes, X: np.ndarray, W: Dict[str, np.ndarray], cache
             p = np.exp(s - np.max(s))
             p = p / np.sum(p)
             A[i, j] = p @ cache.v[b, kh, :n_keys, :]
+    if detail is not None:          # intermediates, for tests that look inside the block
+        detail.update(Q=Q.reshape(len(sel), q * d), A=A.reshape(len(sel), q * d))
     return A.reshape(len(sel), q * d) @ np.asarray(W["wo"], F64)
 
 
-def mlp_partial(sh: Shapes, R: np.ndarray, W: Dict[str, np.ndarray]) -> np.ndarray:
+def mlp_partial(sh: Shapes, R: np.ndarray, W: Dict[str, np.ndarray],
+                detail: Optional[dict] = None) -> np.ndarray:
     """Device i's partial MLP output Z_i = (silu(m Wg_i) * (m Wu_i)) Wd_i with m = RMSNorm(R)."""
     m = rmsnorm(R, W["g2"], sh.rms_eps)
     u = silu(m @ np.asarray(W["wg"], F64)) * (m @ np.asarray(W["wu"], F64))
+    if detail is not None:
+        detail.update(U=u)
     return u @ np.asarray(W["wd"], F64)
 
 
@@ -221,17 +226,19 @@ def block_single_rank(sh: Shapes, X: np.ndarray, shard: Dict[str, np.ndarray], c
     """
     X = np.asarray(X, F64)
     sel = np.arange(X.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
-    Y = attention_partial(sh, X, shard, cache, positions, batch, q_len, rows=rows)
+    S = np.array(slots[:, sel], dtype=F64)                 # the partial sums met at a sync point
+    Y = attention_partial(sh, X, shard, cache, positions, batch, q_len, rows=rows, detail=detail)
     if spd:
-        Z = mlp_partial(sh, X[sel] + Y, shard)
-        slots[rank, sel] = Y + Z
-        out = X[sel] + np.sum(slots[:, sel], axis=0)
+        Z = mlp_partial(sh, X[sel] + Y, shard, detail)
+        S[rank] = Y + Z
+        out = X[sel] + np.sum(S, axis=0)
     else:
-        slots[rank, sel] = Y
-        R = X[sel] + np.sum(slots[:, sel], axis=0)
-        Z = mlp_partial(sh, R, shard)
-        slots[rank, sel] = Z
-        out = R + np.sum(slots[:, sel], axis=0)
+        S[rank] = Y
+        R = X[sel] + np.sum(S, axis=0)
+        Z = mlp_partial(sh, R, shard, detail)
+        S[rank] = Z
+        out = R + np.sum(S, axis=0)
+    slots[rank, sel] = S[rank]
     if detail is not None:
         detail.update(Y=Y, Z=Z)
     return out

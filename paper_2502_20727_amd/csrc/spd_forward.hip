@@ -1,0 +1,179 @@
+// Device-facing entry points of the C ABI: argument checks on the host, then the sequence
+// of kernel launches that makes up one rank's share of a TP or SPD decoder block.
+#include <cstring>
+
+#include "spd_internal.h"
+
+namespace {
+
+#define SPD_HIP(x)                          \
+    do {                                    \
+        if ((x) != hipSuccess) return SPD_EHIP; \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
+
+// Everything a forward call must satisfy before anything is launched.
+int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32_t batch, int32_t q_len,
+               const float *x_in, float *slots, float *x_out, void *workspace, spd_call *c, void *stream) {
+    if (!ctx || !positions || !x_in || !slots || !x_out || !workspace) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (rank != SPD_ALL_RANKS && (rank < 0 || rank >= D.tp)) return SPD_EINVAL;
+    if (batch < 0 || q_len < 0 || batch > D.max_batch) return SPD_EINVAL;
+    if ((int64_t)batch * q_len > D.max_tokens) return SPD_EINVAL;
+    if (!aligned16(x_in) || !aligned16(slots) || !aligned16(x_out) || (((uintptr_t)workspace) & 255)) return SPD_EINVAL;
+    c->D = &D;
+    c->s = (hipStream_t)stream;
+    c->batch = batch;
+    c->q_len = q_len;
+    c->M = batch * q_len;
+    c->ws = (char *)workspace;
+    c->taps = nullptr;
+    c->max_pos_end = 0;
+    std::memset(&c->pos, 0, sizeof(c->pos));
+    for (int b = 0; b < batch; ++b) {
+        if (positions[b] < 0 || (int64_t)positions[b] + q_len > D.max_ctx) return SPD_EINVAL;
+        c->pos.pos[b] = positions[b];
+        if (positions[b] + q_len > c->max_pos_end) c->max_pos_end = positions[b] + q_len;
+    }
+    return SPD_OK;
+}
+
+// The part of a block between its input and the rank-sum that ends it.  On return the
+// slots hold the partial sums of the final sync point and *base_out is what they are added
+// to: X for an SPD block ("X is added after the sync operation"), R = X + sum Y for a TP
+// block.  *syncs is incremented by the number of kept attention sync points (0 or 1).
+int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const char *weights, char *kv,
+               const float *x, float *slots, const float **base_out, int64_t *syncs) {
+    const spd_dims &D = ctx->D;
+    const size_t slot_n = (size_t)c.M * D.h;
+    float *ybuf = (float *)(c.ws + D.ws_y), *rbuf = (float *)(c.ws + D.ws_r);
+    const int r0 = rank == SPD_ALL_RANKS ? 0 : rank, r1 = rank == SPD_ALL_RANKS ? D.tp : rank + 1;
+    const bool all = rank == SPD_ALL_RANKS;
+    auto wr = [&](int r) { return weights + (all ? (size_t)r * D.weight_bytes : 0); };
+    auto kr = [&](int r) { return kv + (all ? (size_t)r * D.kv_bytes : 0); };
+
+    if (D.dtype == SPD_BF16) {
+        if (spd) {
+            for (int r = r0; r < r1; ++r) {
+                SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 1, slots + r * slot_n));
+                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 1, slots + r * slot_n));
+            }
+            *base_out = x;
+        } else {
+            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 0, slots + r * slot_n));
+            // kept sync point: R = X + sum_r Y_r, fused with the second norm's elementwise part
+            SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1));
+            *syncs += 1;
+            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n));
+            *base_out = rbuf;
+        }
+        return SPD_OK;
+    }
+    if (spd) {
+        for (int r = r0; r < r1; ++r) {
+            SPD_HIP(spd_f32::attention_half(c, wr(r), kr(r), x, ybuf));
+            SPD_HIP(spd_common::rank_sum(x, ybuf, 1, (int64_t)slot_n, rbuf, c.s));       // local fold X + Y_r
+            SPD_HIP(spd_f32::mlp_half(c, wr(r), rbuf, ybuf, slots + r * slot_n));        // slot = Y_r + Z_r
+        }
+        *base_out = x;
+    } else {
+        for (int r = r0; r < r1; ++r) SPD_HIP(spd_f32::attention_half(c, wr(r), kr(r), x, slots + r * slot_n));
+        SPD_HIP(spd_common::rank_sum(x, slots, D.tp, (int64_t)slot_n, rbuf, c.s));       // kept sync point
+        *syncs += 1;
+        for (int r = r0; r < r1; ++r) SPD_HIP(spd_f32::mlp_half(c, wr(r), rbuf, nullptr, slots + r * slot_n));
+        *base_out = rbuf;
+    }
+    return SPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream) {
+    if (!ctx || !workspace || (((uintptr_t)workspace) & 255)) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    SPD_HIP(hipMemcpyAsync(ws + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
+    SPD_HIP(hipMemcpyAsync(ws + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
+    SPD_HIP(spd_common::fill_zero_u32((uint32_t *)(ws + D.ws_counters), SPD_N_COUNTERS, s));
+    SPD_HIP(hipStreamSynchronize(s));
+    return SPD_OK;
+}
+
+int spd_rank_sum(const spd_ctx *ctx, const float *base, const float *slots, int32_t n_slots, int64_t n_elems,
+                 float *out, void *stream) {
+    if (!ctx || !out || n_slots < 0 || n_elems < 0) return SPD_EINVAL;
+    if (n_slots > 0 && !slots) return SPD_EINVAL;
+    if (n_elems == 0) return SPD_OK;
+    SPD_HIP(spd_common::rank_sum(base, slots, n_slots, n_elems, out, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank, const void *packed_weights,
+                      void *kv_cache, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
+                      float *slots, float *x_out, void *workspace, void *stream, const spd_taps *taps) {
+    spd_call c;
+    const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, workspace, &c, stream);
+    if (rc != SPD_OK) return rc;
+    if (!packed_weights || !kv_cache) return SPD_EINVAL;
+    if (spd_flag != 0 && spd_flag != 1) return SPD_EINVAL;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return SPD_EINVAL;
+    if (c.M == 0) return SPD_OK;
+    const spd_dims &D = ctx->D;
+    c.taps = taps;
+    const char *w = (const char *)packed_weights;
+    if (D.dtype == SPD_BF16) SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)(w + D.w_g1), true, 0));
+    const float *base = nullptr;
+    int64_t syncs = 0;
+    const int rc2 = block_core(ctx, c, spd_flag, rank, w, (char *)kv_cache, x_in, slots, &base, &syncs);
+    if (rc2 != SPD_OK) return rc2;
+    // the sync point that ends every block, SPD or not
+    SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
+    return SPD_OK;
+}
+
+int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
+                      void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
+                      float *slots, float *x_out, void *workspace, void *stream, int64_t *n_rank_sums) {
+    spd_call c;
+    const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, workspace, &c, stream);
+    if (rc != SPD_OK) return rc;
+    if (!spd_mask || !layer_weights || !layer_kv) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    const int L = ctx->cfg.n_layers;
+    for (int l = 0; l < L; ++l) {
+        if (spd_mask[l] > 1) return SPD_EINVAL;
+        if (!layer_weights[l] || !layer_kv[l]) return SPD_EINVAL;
+    }
+    if (n_rank_sums) *n_rank_sums = 0;
+    if (c.M == 0) return SPD_OK;
+    const bool bf = D.dtype == SPD_BF16;
+    int64_t syncs = 0;
+    const float *x = x_in;
+    if (bf)
+        SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)((const char *)layer_weights[0] + D.w_g1),
+                               true, 0));
+    for (int l = 0; l < L; ++l) {
+        const float *base = nullptr;
+        const int rc2 = block_core(ctx, c, spd_mask[l], rank, (const char *)layer_weights[l], (char *)layer_kv[l], x,
+                                   slots, &base, &syncs);
+        if (rc2 != SPD_OK) return rc2;
+        // end-of-block sync point; in the bf16 path it also prepares the next block's first norm
+        if (bf) {
+            const bool more = l + 1 < L;
+            const float *g1 = more ? (const float *)((const char *)layer_weights[l + 1] + D.w_g1) : nullptr;
+            SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0));
+        } else {
+            SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
+        }
+        syncs += 1;
+        x = x_out;
+    }
+    if (n_rank_sums) *n_rank_sums = syncs;
+    return SPD_OK;
+}
+
+}  // extern "C"

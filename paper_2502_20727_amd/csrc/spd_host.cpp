@@ -1,0 +1,401 @@
+// Host side of the SPD library: configuration checks, rank indexing, the sync-point count,
+// and the packers that lay one rank's shard and KV cache out the way the kernels read them.
+// Nothing in this file touches a device.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "spd_internal.h"
+
+namespace {
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// fp32 -> bf16 bit pattern; false if the value is not exactly representable
+inline bool to_bf16_exact(float v, uint16_t *out) {
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    *out = (uint16_t)(u >> 16);
+    return (u & 0xFFFFu) == 0;
+}
+inline float from_bf16(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float v;
+    std::memcpy(&v, &u, 4);
+    return v;
+}
+
+template <class F>
+void parallel_for(int n, F f) {
+    int nt = (int)std::thread::hardware_concurrency();
+    if (nt < 1) nt = 1;
+    if (nt > 16) nt = 16;
+    if (nt > n) nt = n;
+    if (nt <= 1) {
+        for (int i = 0; i < n; ++i) f(i);
+        return;
+    }
+    std::vector<std::thread> th;
+    for (int t = 0; t < nt; ++t)
+        th.emplace_back([=]() {
+            for (int i = t; i < n; i += nt) f(i);
+        });
+    for (auto &t : th) t.join();
+}
+
+void compute_dims(const spd_config &c, spd_dims &D) {
+    std::memset(&D, 0, sizeof(D));
+    D.h = c.hidden;
+    D.q = c.n_q_heads / c.tp_degree;
+    D.kv = c.n_kv_heads / c.tp_degree;
+    D.d = c.head_dim;
+    D.f = c.ffn / c.tp_degree;
+    D.group = D.q / D.kv;
+    D.nqkv = (D.q + 2 * D.kv) * D.d;
+    D.tp = c.tp_degree;
+    D.dtype = c.dtype;
+    D.max_batch = c.max_batch;
+    D.max_ctx = c.max_ctx;
+    D.max_tokens = c.max_tokens;
+    D.eps = c.rms_eps;
+    D.rope_base = c.rope_base;
+    const bool bf = c.dtype == SPD_BF16;
+    D.f_pad = bf ? round_up(D.f, 32) : D.f;
+    D.m_pad = round_up(c.max_tokens, 16);
+    const size_t es = bf ? 2 : 4;
+    const size_t h = D.h, qd = (size_t)D.q * D.d, f = D.f_pad;
+
+    size_t o = 0;
+    D.w_g1 = o; o = spd_align256(o + h * 4);
+    D.w_g2 = o; o = spd_align256(o + h * 4);
+    D.w_qkv = o; o = spd_align256(o + h * (size_t)D.nqkv * es);
+    D.w_o = o; o = spd_align256(o + qd * h * es);
+    D.w_g = o; o = spd_align256(o + h * f * es);
+    D.w_u = o; o = spd_align256(o + h * f * es);     // bf16: second half of the interleaved gate/up block
+    D.w_d = o; o = spd_align256(o + f * h * es);
+    D.weight_bytes = o;
+
+    const size_t kvn = (size_t)D.max_batch * D.kv * D.max_ctx * D.d;
+    D.kv_v = spd_align256(kvn * es);
+    D.kv_bytes = D.kv_v + spd_align256(kvn * es);
+
+    const size_t M = D.m_pad;
+    o = 0;
+    D.ws_cos = o; o = spd_align256(o + (size_t)D.max_ctx * (D.d / 2) * 4);
+    D.ws_sin = o; o = spd_align256(o + (size_t)D.max_ctx * (D.d / 2) * 4);
+    D.ws_counters = o; o = spd_align256(o + (size_t)SPD_N_COUNTERS * 4);
+    D.ws_y = o; o = spd_align256(o + M * h * 4);
+    D.ws_r = o; o = spd_align256(o + M * h * 4);
+    if (bf) {
+        D.ws_xhat = o; o = spd_align256(o + M * h * 2);
+        D.ws_xhat2 = o; o = spd_align256(o + M * h * 2);
+        D.ws_q = o; o = spd_align256(o + M * qd * 2);
+        D.ws_ahat = o; o = spd_align256(o + M * qd * 2);
+        D.ws_ss1 = o; o = spd_align256(o + (h / 32) * M * 4);
+        D.ws_ss2 = o; o = spd_align256(o + (h / 32) * M * 4);
+        D.ws_uhat = o; o = spd_align256(o + M * f * 2);
+        D.ws_apart = o;
+        o = spd_align256(o + (size_t)D.max_batch * D.kv * SPD_MAX_SPLITS * 16 * (D.d + 2) * 4);
+    } else {
+        D.ws_xhat = o; o = spd_align256(o + M * h * 4);            // normalised activations
+        D.ws_qkv = o; o = spd_align256(o + M * (size_t)D.nqkv * 4);
+        D.ws_ahat = o; o = spd_align256(o + M * qd * 4);
+        D.ws_gu = o; o = spd_align256(o + M * 2 * f * 4);
+        D.ws_uhat = o; o = spd_align256(o + M * f * 4);
+    }
+    D.workspace_bytes = o;
+}
+
+// One packed bf16 matrix: n_tiles x k_tiles fragments.  `src(k, tile, r)` returns the fp32
+// value of contraction index k for row r of tile `tile` (0 where padded).
+template <class Src>
+bool pack_frags(uint16_t *dst, int n_tiles, int k_tiles, Src src) {
+    std::vector<int> bad(n_tiles, 0);
+    parallel_for(n_tiles, [&](int nt) {
+        for (int kt = 0; kt < k_tiles; ++kt) {
+            uint16_t *fr = dst + spd_frag_index(nt, kt, k_tiles);
+            for (int c = 0; c < 32; ++c)
+                for (int r = 0; r < 16; ++r)
+                    if (!to_bf16_exact(src(kt * 32 + c, nt, r), &fr[spd_frag_elem(r, c)])) bad[nt] = 1;
+        }
+    });
+    for (int b : bad)
+        if (b) return false;
+    return true;
+}
+
+template <class Dst>
+void unpack_frags(const uint16_t *srcp, int n_tiles, int k_tiles, Dst dst) {
+    parallel_for(n_tiles, [&](int nt) {
+        for (int kt = 0; kt < k_tiles; ++kt) {
+            const uint16_t *fr = srcp + spd_frag_index(nt, kt, k_tiles);
+            for (int c = 0; c < 32; ++c)
+                for (int r = 0; r < 16; ++r) dst(kt * 32 + c, nt, r, from_bf16(fr[spd_frag_elem(r, c)]));
+        }
+    });
+}
+
+bool weights_ok(const spd_layer_weights *w) {
+    return w && w->wq && w->wk && w->wv && w->wo && w->wg && w->wu && w->wd && w->g1 && w->g2;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *spd_strerror(int code) {
+    switch (code) {
+        case SPD_OK: return "ok";
+        case SPD_EINVAL: return "invalid argument";
+        case SPD_EUNSUPPORTED: return "unsupported configuration";
+        case SPD_EHIP: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+int spd_create(const spd_config *cfg, spd_ctx **out) {
+    if (!cfg || !out) return SPD_EINVAL;
+    *out = nullptr;
+    const spd_config &c = *cfg;
+    if (c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.ffn <= 0 ||
+        c.n_layers <= 0 || c.tp_degree <= 0 || c.max_batch <= 0 || c.max_ctx <= 0 || c.max_tokens <= 0)
+        return SPD_EINVAL;
+    if (!(c.rms_eps >= 0.0f) || !(c.rope_base > 0.0f)) return SPD_EINVAL;
+    if (c.head_dim % 2) return SPD_EINVAL;
+    if (c.n_q_heads % c.n_kv_heads) return SPD_EINVAL;
+    if (c.max_batch > SPD_MAX_BATCH || c.max_ctx % 32) return SPD_EINVAL;
+    if (c.max_tokens < c.max_batch) return SPD_EINVAL;
+    if (c.dtype != SPD_F32 && c.dtype != SPD_BF16) return SPD_EUNSUPPORTED;
+    if (c.n_kv_heads < c.tp_degree) return SPD_EUNSUPPORTED;   // a KV head shared by several ranks
+    if (c.n_q_heads % c.tp_degree || c.n_kv_heads % c.tp_degree || c.ffn % c.tp_degree) return SPD_EINVAL;
+    if (c.dtype == SPD_BF16) {
+        if (c.hidden % 32 || c.head_dim % 32 || (c.ffn / c.tp_degree) % 16) return SPD_EUNSUPPORTED;
+        if ((c.n_q_heads / c.n_kv_heads) > 16) return SPD_EUNSUPPORTED;
+        if (c.head_dim > 256) return SPD_EUNSUPPORTED;
+    } else {
+        if (c.head_dim > 256 || c.max_ctx > 8192) return SPD_EUNSUPPORTED;
+    }
+    spd_ctx *ctx = new (std::nothrow) spd_ctx();
+    if (!ctx) return SPD_EINVAL;
+    ctx->cfg = c;
+    compute_dims(c, ctx->D);
+    const int half = c.head_dim / 2;
+    ctx->rope_cos.resize((size_t)c.max_ctx * half);
+    ctx->rope_sin.resize((size_t)c.max_ctx * half);
+    for (int j = 0; j < half; ++j) {
+        const double theta = std::pow((double)c.rope_base, -2.0 * (double)j / (double)c.head_dim);
+        for (int p = 0; p < c.max_ctx; ++p) {
+            const double a = (double)p * theta;
+            ctx->rope_cos[(size_t)p * half + j] = (float)std::cos(a);
+            ctx->rope_sin[(size_t)p * half + j] = (float)std::sin(a);
+        }
+    }
+    *out = ctx;
+    return SPD_OK;
+}
+
+void spd_destroy(spd_ctx *ctx) { delete ctx; }
+
+int spd_get_config(const spd_ctx *ctx, spd_config *out) {
+    if (!ctx || !out) return SPD_EINVAL;
+    *out = ctx->cfg;
+    return SPD_OK;
+}
+
+int spd_get_sizes(const spd_ctx *ctx, spd_sizes *out) {
+    if (!ctx || !out) return SPD_EINVAL;
+    out->weight_bytes = ctx->D.weight_bytes;
+    out->kv_bytes = ctx->D.kv_bytes;
+    out->workspace_bytes = ctx->D.workspace_bytes;
+    return SPD_OK;
+}
+
+static int rank_range(const spd_ctx *ctx, int32_t rank, int per_rank, int32_t *first, int32_t *count) {
+    if (!ctx || !first || !count) return SPD_EINVAL;
+    if (rank < 0 || rank >= ctx->D.tp) return SPD_EINVAL;
+    *first = rank * per_rank;
+    *count = per_rank;
+    return SPD_OK;
+}
+int spd_rank_q_heads(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count) {
+    return rank_range(ctx, rank, ctx ? ctx->D.q : 0, first, count);
+}
+int spd_rank_kv_heads(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count) {
+    return rank_range(ctx, rank, ctx ? ctx->D.kv : 0, first, count);
+}
+int spd_rank_ffn_cols(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t *count) {
+    return rank_range(ctx, rank, ctx ? ctx->D.f : 0, first, count);
+}
+
+int64_t spd_sync_count(const spd_ctx *ctx, const uint8_t *mask) {
+    if (!ctx || !mask) return SPD_EINVAL;
+    int64_t n = 0;
+    for (int l = 0; l < ctx->cfg.n_layers; ++l) {
+        if (mask[l] > 1) return SPD_EINVAL;
+        n += mask[l] ? 1 : 2;
+    }
+    return n;
+}
+
+int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *packed_host) {
+    if (!ctx || !weights_ok(w) || !packed_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    char *base = (char *)packed_host;
+    std::memset(base, 0, D.weight_bytes);
+    std::memcpy(base + D.w_g1, w->g1, (size_t)D.h * 4);
+    std::memcpy(base + D.w_g2, w->g2, (size_t)D.h * 4);
+    const int h = D.h, d = D.d, q = D.q, kv = D.kv, f = D.f, qd = q * d, kvd = kv * d;
+    if (D.dtype == SPD_F32) {
+        float *wqkv = (float *)(base + D.w_qkv);
+        for (int k = 0; k < h; ++k) {
+            std::memcpy(wqkv + (size_t)k * D.nqkv, w->wq + (size_t)k * w->ld_q, (size_t)qd * 4);
+            std::memcpy(wqkv + (size_t)k * D.nqkv + qd, w->wk + (size_t)k * w->ld_k, (size_t)kvd * 4);
+            std::memcpy(wqkv + (size_t)k * D.nqkv + qd + kvd, w->wv + (size_t)k * w->ld_v, (size_t)kvd * 4);
+            std::memcpy((float *)(base + D.w_g) + (size_t)k * f, w->wg + (size_t)k * w->ld_g, (size_t)f * 4);
+            std::memcpy((float *)(base + D.w_u) + (size_t)k * f, w->wu + (size_t)k * w->ld_u, (size_t)f * 4);
+        }
+        for (int k = 0; k < qd; ++k)
+            std::memcpy((float *)(base + D.w_o) + (size_t)k * h, w->wo + (size_t)k * w->ld_o, (size_t)h * 4);
+        for (int k = 0; k < f; ++k)
+            std::memcpy((float *)(base + D.w_d) + (size_t)k * h, w->wd + (size_t)k * w->ld_d, (size_t)h * 4);
+        return SPD_OK;
+    }
+    bool ok = true;
+    // QKV: contraction = hidden, tiles in the rotary-interleaved order
+    ok &= pack_frags((uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, [&](int k, int nt, int r) {
+        const int c = spd_qkv_tile_col0(nt, q, kv, d) + r;
+        if (c < qd) return w->wq[(size_t)k * w->ld_q + c];
+        if (c < qd + kvd) return w->wk[(size_t)k * w->ld_k + (c - qd)];
+        return w->wv[(size_t)k * w->ld_v + (c - qd - kvd)];
+    });
+    // O: contraction = the rank's q*d attention features
+    ok &= pack_frags((uint16_t *)(base + D.w_o), h / 16, qd / 32,
+                     [&](int k, int nt, int r) { return w->wo[(size_t)k * w->ld_o + nt * 16 + r]; });
+    // gate/up: even tiles gate, odd tiles up, same 16 columns; columns >= f are zero padding
+    ok &= pack_frags((uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, [&](int k, int nt, int r) {
+        const int c = (nt >> 1) * 16 + r;
+        if (c >= f) return 0.0f;
+        return (nt & 1) ? w->wu[(size_t)k * w->ld_u + c] : w->wg[(size_t)k * w->ld_g + c];
+    });
+    // down: contraction = the rank's FFN slice (zero rows where padded)
+    ok &= pack_frags((uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r) {
+        return k < f ? w->wd[(size_t)k * w->ld_d + nt * 16 + r] : 0.0f;
+    });
+    return ok ? SPD_OK : SPD_EINVAL;   // a weight that is not a bf16 value
+}
+
+int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host) {
+    if (!ctx || !weights_ok(dense) || !packed_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (rank < 0 || rank >= D.tp) return SPD_EINVAL;
+    spd_layer_weights s = *dense;
+    s.wq += (size_t)rank * D.q * D.d;                      // column-wise split: the rank's heads
+    s.wk += (size_t)rank * D.kv * D.d;
+    s.wv += (size_t)rank * D.kv * D.d;
+    s.wo += (size_t)rank * D.q * D.d * (size_t)dense->ld_o;   // row-wise split
+    s.wg += (size_t)rank * D.f;
+    s.wu += (size_t)rank * D.f;
+    s.wd += (size_t)rank * D.f * (size_t)dense->ld_d;
+    return spd_pack_shard_local(ctx, &s, packed_host);
+}
+
+int spd_unpack_shard(const spd_ctx *ctx, const void *packed_host, const spd_layer_weights *o) {
+    if (!ctx || !weights_ok(o) || !packed_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    const char *base = (const char *)packed_host;
+    const int h = D.h, d = D.d, q = D.q, kv = D.kv, f = D.f, qd = q * d, kvd = kv * d;
+    float *wq = (float *)o->wq, *wk = (float *)o->wk, *wv = (float *)o->wv, *wo = (float *)o->wo;
+    float *wg = (float *)o->wg, *wu = (float *)o->wu, *wd = (float *)o->wd;
+    std::memcpy((float *)o->g1, base + D.w_g1, (size_t)h * 4);
+    std::memcpy((float *)o->g2, base + D.w_g2, (size_t)h * 4);
+    if (D.dtype == SPD_F32) {
+        const float *wqkv = (const float *)(base + D.w_qkv);
+        for (int k = 0; k < h; ++k) {
+            std::memcpy(wq + (size_t)k * o->ld_q, wqkv + (size_t)k * D.nqkv, (size_t)qd * 4);
+            std::memcpy(wk + (size_t)k * o->ld_k, wqkv + (size_t)k * D.nqkv + qd, (size_t)kvd * 4);
+            std::memcpy(wv + (size_t)k * o->ld_v, wqkv + (size_t)k * D.nqkv + qd + kvd, (size_t)kvd * 4);
+            std::memcpy(wg + (size_t)k * o->ld_g, (const float *)(base + D.w_g) + (size_t)k * f, (size_t)f * 4);
+            std::memcpy(wu + (size_t)k * o->ld_u, (const float *)(base + D.w_u) + (size_t)k * f, (size_t)f * 4);
+        }
+        for (int k = 0; k < qd; ++k)
+            std::memcpy(wo + (size_t)k * o->ld_o, (const float *)(base + D.w_o) + (size_t)k * h, (size_t)h * 4);
+        for (int k = 0; k < f; ++k)
+            std::memcpy(wd + (size_t)k * o->ld_d, (const float *)(base + D.w_d) + (size_t)k * h, (size_t)h * 4);
+        return SPD_OK;
+    }
+    unpack_frags((const uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, [&](int k, int nt, int r, float v) {
+        const int c = spd_qkv_tile_col0(nt, q, kv, d) + r;
+        if (c < qd) wq[(size_t)k * o->ld_q + c] = v;
+        else if (c < qd + kvd) wk[(size_t)k * o->ld_k + (c - qd)] = v;
+        else wv[(size_t)k * o->ld_v + (c - qd - kvd)] = v;
+    });
+    unpack_frags((const uint16_t *)(base + D.w_o), h / 16, qd / 32,
+                 [&](int k, int nt, int r, float v) { wo[(size_t)k * o->ld_o + nt * 16 + r] = v; });
+    unpack_frags((const uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, [&](int k, int nt, int r, float v) {
+        const int c = (nt >> 1) * 16 + r;
+        if (c >= f) return;
+        if (nt & 1) wu[(size_t)k * o->ld_u + c] = v;
+        else wg[(size_t)k * o->ld_g + c] = v;
+    });
+    unpack_frags((const uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r, float v) {
+        if (k < f) wd[(size_t)k * o->ld_d + nt * 16 + r] = v;
+    });
+    return SPD_OK;
+}
+
+int spd_kv_pack(const spd_ctx *ctx, const float *k, const float *v, int32_t batch, int32_t n_pos, void *cache_host) {
+    if (!ctx || !k || !v || !cache_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (batch < 0 || batch > D.max_batch || n_pos < 0 || n_pos > D.max_ctx) return SPD_EINVAL;
+    const int d = D.d;
+    const size_t per_head = (size_t)D.max_ctx * d;
+    std::vector<int> bad(batch * D.kv, 0);
+    parallel_for(batch * D.kv, [&](int bh) {
+        const float *ks = k + (size_t)bh * n_pos * d, *vs = v + (size_t)bh * n_pos * d;
+        if (D.dtype == SPD_F32) {
+            float *kd = (float *)cache_host + (size_t)bh * per_head;
+            float *vd = (float *)((char *)cache_host + D.kv_v) + (size_t)bh * per_head;
+            std::memcpy(kd, ks, (size_t)n_pos * d * 4);
+            std::memcpy(vd, vs, (size_t)n_pos * d * 4);
+            return;
+        }
+        uint16_t *kd = (uint16_t *)cache_host + (size_t)bh * per_head;
+        uint16_t *vd = (uint16_t *)((char *)cache_host + D.kv_v) + (size_t)bh * per_head;
+        for (int p = 0; p < n_pos; ++p)
+            for (int c = 0; c < d; ++c) {
+                if (!to_bf16_exact(ks[(size_t)p * d + c], &kd[spd_kcache_off(p, c, d)])) bad[bh] = 1;
+                if (!to_bf16_exact(vs[(size_t)p * d + c], &vd[spd_vcache_off(p, c, d)])) bad[bh] = 1;
+            }
+    });
+    for (int b : bad)
+        if (b) return SPD_EINVAL;
+    return SPD_OK;
+}
+
+int spd_kv_unpack(const spd_ctx *ctx, const void *cache_host, int32_t batch, int32_t n_pos, float *k, float *v) {
+    if (!ctx || !k || !v || !cache_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (batch < 0 || batch > D.max_batch || n_pos < 0 || n_pos > D.max_ctx) return SPD_EINVAL;
+    const int d = D.d;
+    const size_t per_head = (size_t)D.max_ctx * d;
+    parallel_for(batch * D.kv, [&](int bh) {
+        float *ks = k + (size_t)bh * n_pos * d, *vs = v + (size_t)bh * n_pos * d;
+        if (D.dtype == SPD_F32) {
+            std::memcpy(ks, (const float *)cache_host + (size_t)bh * per_head, (size_t)n_pos * d * 4);
+            std::memcpy(vs, (const float *)((const char *)cache_host + D.kv_v) + (size_t)bh * per_head,
+                        (size_t)n_pos * d * 4);
+            return;
+        }
+        const uint16_t *kd = (const uint16_t *)cache_host + (size_t)bh * per_head;
+        const uint16_t *vd = (const uint16_t *)((const char *)cache_host + D.kv_v) + (size_t)bh * per_head;
+        for (int p = 0; p < n_pos; ++p)
+            for (int c = 0; c < d; ++c) {
+                ks[(size_t)p * d + c] = from_bf16(kd[spd_kcache_off(p, c, d)]);
+                vs[(size_t)p * d + c] = from_bf16(vd[spd_vcache_off(p, c, d)]);
+            }
+    });
+    return SPD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,132 @@
+// Internal declarations shared by the host side and the kernels of the SPD library:
+// derived per-rank dimensions, the packed memory layouts, and the launcher prototypes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "spd.h"
+
+#define SPD_HD __host__ __device__ __forceinline__
+
+// ------------------------------------------------------------------------------------------
+// Packed layouts of the bf16 path.
+//
+// Every matrix operand of an MFMA 16x16x32 (bf16) is stored as a sequence of 1 KiB
+// "fragments": 16 rows x 32 contraction elements, in the register order of the
+// instruction.  Lane l of a wavefront owns row (l % 16) and the 8 consecutive contraction
+// elements starting at 8 * (l / 16); its 8 bf16 values are contiguous (16 bytes), and the
+// 64 lanes follow each other, so one fragment is one fully coalesced 1 KiB load.
+//
+// A weight matrix W [K, N] (y = x W) is cut into n-tiles of 16 output columns and k-tiles
+// of 32 inputs; fragment (nt, kt) sits at ((nt * KT) + kt) * 512 elements, row = column
+// n0(nt) + l % 16 of W, contraction element = input kt*32 + 8*(l/16) + j.  Row-major
+// activations [M, K] use the same scheme with m-tiles in place of n-tiles.
+// ------------------------------------------------------------------------------------------
+
+constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
+constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
+constexpr int SPD_N_COUNTERS = 8192;
+
+SPD_HD size_t spd_frag_index(int tile, int ktile, int n_ktiles) {
+    return ((size_t)tile * (size_t)n_ktiles + (size_t)ktile) * SPD_FRAG_ELEMS;
+}
+// element offset inside a fragment of (row r in 0..15, contraction index c in 0..31)
+SPD_HD int spd_frag_elem(int r, int c) { return ((r + 16 * (c >> 3)) << 3) + (c & 7); }
+
+// QKV n-tiles: the rank's columns are [Q heads | K heads | V heads].  Inside every rotary
+// head (Q and K) the d/16 tiles are interleaved so that packed tiles 2i and 2i+1 hold the
+// rotary partners: columns [16 i, 16 i + 16) and the same range shifted by d/2.
+SPD_HD int spd_qkv_tile_col0(int pt, int q, int kv, int d) {
+    const int tph = d >> 4;
+    const int head = pt / tph, w = pt % tph;
+    if (head < q + kv) return head * d + (((w >> 1) + (w & 1) * (tph >> 1)) << 4);
+    return head * d + (w << 4);
+}
+
+// KV cache, bf16 path, per (sequence, KV head): max_ctx * d elements for K, same for V.
+// K: blocks of 16 positions; block = d/32 fragments with row = position, contraction = d.
+SPD_HD size_t spd_kcache_off(int pos, int dcol, int d) {
+    return (size_t)(pos >> 4) * (size_t)(16 * d) + (size_t)(dcol >> 5) * SPD_FRAG_ELEMS +
+           (size_t)spd_frag_elem(pos & 15, dcol & 31);
+}
+// V: blocks of 32 positions; block = d/16 fragments with row = d index, contraction =
+// position.  The 32 positions of a block are permuted so that the probabilities, as they
+// come out of two 16-key score tiles (4 consecutive keys per lane and tile), already are
+// the partner operand: contraction slot (g, j) holds key 4g + j (j < 4) or 16 + 4g + j - 4.
+SPD_HD size_t spd_vcache_off(int pos, int dcol, int d) {
+    const int kl = pos & 31, hi = kl >> 4, r = kl & 15;
+    const int g = r >> 2, j = (r & 3) + 4 * hi;
+    return (size_t)(pos >> 5) * (size_t)(32 * d) + (size_t)(dcol >> 4) * SPD_FRAG_ELEMS +
+           (size_t)(((dcol & 15) + 16 * g) << 3) + (size_t)j;
+}
+
+// ------------------------------------------------------------------------------------------
+// Derived dimensions of one rank's share, and byte offsets of everything the library lays out.
+// ------------------------------------------------------------------------------------------
+struct spd_dims {
+    int h, q, kv, d, f, f_pad, group, nqkv, tp, dtype;
+    int max_batch, max_ctx, max_tokens, m_pad;
+    float eps, rope_base;
+    // packed shard (bytes from its start)
+    size_t w_g1, w_g2, w_qkv, w_o, w_g, w_u, w_d, weight_bytes;   // w_u: f32 path only (bf16: gate/up interleaved at w_g)
+    // KV cache (bytes)
+    size_t kv_v, kv_bytes;
+    // workspace (bytes)
+    size_t ws_cos, ws_sin, ws_counters, ws_xhat, ws_xhat2, ws_q, ws_ahat, ws_y, ws_r, ws_ss1, ws_ss2, ws_uhat,
+        ws_apart, ws_qkv, ws_gu, workspace_bytes;
+};
+
+struct spd_ctx {
+    spd_config cfg;
+    spd_dims D;
+    std::vector<float> rope_cos, rope_sin;   // [max_ctx][d/2], built in double on the host
+};
+
+struct spd_positions {
+    int32_t pos[SPD_MAX_BATCH];
+};
+
+inline size_t spd_align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// ------------------------------------------------------------------------------------------
+// Launchers (defined next to their kernels).  All enqueue on `s` and return a hipError_t.
+// ------------------------------------------------------------------------------------------
+struct spd_call {
+    const spd_dims *D;
+    hipStream_t s;
+    int batch, q_len, M;
+    spd_positions pos;
+    int max_pos_end;          // max over sequences of positions[b] + q_len
+    char *ws;                 // workspace
+    const spd_taps *taps;
+};
+
+namespace spd_common {
+hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s);
+hipError_t fill_zero_u32(uint32_t *p, size_t n, hipStream_t s);
+hipError_t copy2d(const float *src, int lds, float *dst, int ldd, int rows, int cols, hipStream_t s);
+}
+
+namespace spd_f32 {
+// attention half of a rank's share: X -> Y_r (into ybuf or the slot), fp32 path
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, float *y_out);
+// MLP half: r_in -> Z_r, out[m][n] = (add ? add[m][n] : 0) + Z_r
+hipError_t mlp_half(const spd_call &c, const char *w, const float *r_in, const float *add, float *out);
+}
+
+namespace spd_bf16 {
+// out = base + sum slots (optional), xhat = bf16(out * g) packed (optional), partial sums of squares
+// which = 0: the block's first norm (xhat, ss1); which = 1: its second norm (xhat2, ss2)
+hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_slots, float *out,
+                const float *gain, bool want_xhat, int which);
+// QKV + rotary + cache append + attention + O projection.
+//   spd = 1: ybuf <- Y_r, xhat2 <- bf16((X + Y_r) g2) and its partial sums of squares
+//   spd = 0: slot <- Y_r
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot);
+// gate/up + SwiGLU + down.  spd = 1: slot <- ybuf + Z_r; spd = 0: slot <- Z_r
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot);
+}

@@ -1,0 +1,387 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  bf16 path: max abs error 2e-2 on the fp32-stored block outputs; fp32 path:
+1e-3 relative; integer logic (sync counts, rank indexing) bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import spd_oracle as O
+from paper_2502_20727_amd import binding as B
+from paper_2502_20727_amd import inputs, workloads
+from paper_2502_20727_amd.workloads import BF16, F32, Workload
+
+from helpers import Case, assert_close, oracle_shapes
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# rank-sum: the kept sync point
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_slots,n,with_base", [(0, 64, True), (1, 7, True), (2, 1024, False), (8, 4099, True),
+                                                 (8, 16 * 8192, True), (3, 1, False)])
+def test_rank_sum(gpu, n_slots, n, with_base):
+    import torch
+    ctx = B.spd_create(B.make_config(workloads.TOY, max_ctx=64))
+    rng = np.random.default_rng(n_slots * 1000 + n)
+    slots = rng.standard_normal((max(n_slots, 1), n)).astype(np.float32)
+    base = rng.standard_normal(n).astype(np.float32) if with_base else None
+    d_slots = torch.from_numpy(slots).to(gpu)
+    d_base = torch.from_numpy(base).to(gpu) if with_base else None
+    out = torch.full((n,), 7.0, dtype=torch.float32, device=gpu)
+    B.spd_rank_sum(ctx, d_base, d_slots, n_slots, n, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    # contract: partials in ascending slot order, base last, all in fp32 -> bit-exact
+    acc = np.zeros(n, np.float32)
+    if n_slots:
+        acc = slots[0].copy()
+        for s in range(1, n_slots):
+            acc = acc + slots[s]
+    want32 = (base + acc) if with_base else acc
+    assert np.array_equal(got, want32.astype(np.float32))
+    want64 = O.rank_sum(base, slots[:n_slots]) if n_slots else (np.asarray(base, np.float64) if with_base else np.zeros(n))
+    assert np.max(np.abs(got - want64)) <= 1e-5 * max(1.0, float(np.max(np.abs(want64))))
+    B.spd_destroy(ctx)
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 0: the fp32 toy model, all ranks emulated, prefill 32 + 8 single-token steps
+# ------------------------------------------------------------------------------------------------
+def test_toy_fp32_prefill_then_decode(gpu):
+    import torch
+    w = workloads.TOY
+    case = Case(w, gpu, ranks=range(w.tp), positions=[0], max_ctx=64, max_tokens=32)
+    X = inputs.hidden_states(w, 40)
+    slots = torch.zeros((w.tp, 32, w.hidden), dtype=torch.float32, device=gpu)
+    out = torch.empty((32, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward(case.dev.ctx, w.mask, B.SPD_ALL_RANKS, case.dev.weights, case.dev.kv, [0], 1, 32,
+                                case.to_dev(X[:32]), slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    want, osyncs = O.model_all_ranks(case.sh, X[:32], case.shards, case.caches, [0], 1, 32, w.mask)
+    assert syncs == osyncs == 3                        # mask [1, 0]: 1 + 2 sync points
+    err = assert_close(out.cpu().numpy(), want, w, "toy prefill")
+    say(f"toy prefill: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
+    for t in range(32, 40):                            # teacher-forced single-token steps
+        o1 = torch.empty((1, w.hidden), dtype=torch.float32, device=gpu)
+        B.spd_model_forward(case.dev.ctx, w.mask, B.SPD_ALL_RANKS, case.dev.weights, case.dev.kv, [t], 1, 1,
+                            case.to_dev(X[t:t + 1]), slots, o1, case.dev.workspace)
+        torch.cuda.synchronize()
+        want, _ = O.model_all_ranks(case.sh, X[t:t + 1], case.shards, case.caches, [t], 1, 1, w.mask)
+        assert_close(o1.cpu().numpy(), want, w, f"toy decode step {t}")
+    case.close()
+
+
+def _block_with_taps(case, li, flag, rank_arg, x_dev, slots, batch, q_len, positions):
+    import torch
+    w = case.w
+    M = batch * q_len
+    qd = w.q_per_rank * w.head_dim
+    taps = dict(q=torch.zeros((M, qd), dtype=torch.float32, device=x_dev.device),
+                attn=torch.zeros((M, qd), dtype=torch.float32, device=x_dev.device),
+                y=torch.zeros((M, w.hidden), dtype=torch.float32, device=x_dev.device),
+                u=torch.zeros((M, w.ffn_per_rank), dtype=torch.float32, device=x_dev.device))
+    out = torch.empty((M, w.hidden), dtype=torch.float32, device=x_dev.device)
+    B.spd_block_forward(case.dev.ctx, li, flag, rank_arg, case.dev.weights[li], case.dev.kv[li], positions, batch,
+                        q_len, x_dev, slots, out, case.dev.workspace, taps=taps)
+    torch.cuda.synchronize()
+    return out, {k: v.cpu().numpy() for k, v in taps.items()}
+
+
+def _check_taps(taps, det, w, what):
+    # bf16-stored intermediates carry one rounding of their own: half an ulp (2^-9 relative) on top
+    for name, key in (("q", "Q"), ("attn", "A"), ("y", "Y"), ("u", "U")):
+        want = det[key]
+        scale = 1.0 + float(np.max(np.abs(want))) * (2.0 ** -8) / 2e-2 if w.dtype == BF16 else 1.0
+        assert_close(taps[name], want, w, f"{what} tap {name}", scale=scale)
+
+
+def test_toy_fp32_block_intermediates(gpu):
+    import torch
+    w = workloads.TOY
+    for flag in (1, 0):
+        case = Case(w, gpu, ranks=range(w.tp), positions=[0], max_ctx=64, max_tokens=32)
+        X = inputs.hidden_states(w, 32)
+        slots = torch.zeros((w.tp, 32, w.hidden), dtype=torch.float32, device=gpu)
+        out, taps = _block_with_taps(case, 0, flag, B.SPD_ALL_RANKS, case.to_dev(X), slots, 1, 32, [0])
+        det = {}
+        want, _ = O.block_all_ranks(case.sh, X, case.shards[0], case.caches[0], [0], 1, 32, flag, det)
+        assert_close(out.cpu().numpy(), want, w, f"toy block flag={flag}")
+        # the taps belong to the last rank run
+        d2 = {}
+        c2 = O.KVCache(1, w.kv_per_rank, 64, w.head_dim)
+        r = w.tp - 1
+        Y = O.attention_partial(case.sh, X, case.shards[0][r], c2, [0], 1, 32, detail=d2)
+        R = X + (Y if flag else sum(det["Y"]))
+        O.mlp_partial(case.sh, R, case.shards[0][r], d2)
+        d2["Y"] = Y
+        _check_taps(taps, d2, w, f"toy flag={flag}")
+        # slots hold what meets at the final sync point
+        got_slots = slots.cpu().numpy()
+        for i in range(w.tp):
+            assert_close(got_slots[i], det["P"][i], w, f"toy slot {i} flag={flag}")
+        case.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# bf16 path, small shapes, all ranks: several tiles, ragged tails, ragged positions
+# ------------------------------------------------------------------------------------------------
+SMALL = Workload(name="small-bf16", hidden=256, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=832, n_layers=2,
+                 tp=4, dtype=BF16, seed=11, batch=3, q_len=1, ctx=64, mask=(1, 0))
+SMALL_MHA = Workload(name="small-bf16-mha", hidden=128, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=256,
+                     n_layers=1, tp=2, dtype=BF16, seed=12, batch=2, q_len=1, ctx=64, mask=(1,))
+
+
+@pytest.mark.parametrize("w", [SMALL, SMALL_MHA], ids=lambda w: w.name)
+@pytest.mark.parametrize("batch,q_len,positions", [
+    (3, 1, [0, 17, 40]),          # decode, ragged contexts, one sequence with a single key
+    (2, 7, [0, 5]),               # 14 tokens: a partial m-tile
+    (3, 11, [3, 0, 20]),          # 33 tokens: three m-tiles with a ragged tail
+    (1, 40, [8]),                 # one long chunk crossing several key blocks
+], ids=["decode", "chunk14", "chunk33", "chunk40"])
+@pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
+def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
+    import torch
+    M = batch * q_len
+    case = Case(w, gpu, ranks=range(w.tp), positions=positions, max_ctx=64, max_tokens=48)
+    X = inputs.hidden_states(w, M)
+    slots = torch.zeros((w.tp, M, w.hidden), dtype=torch.float32, device=gpu)
+    say(f"case {w.name} batch={batch} q_len={q_len} pos={positions} flag={flag}")
+    out, taps = _block_with_taps(case, 0, flag, B.SPD_ALL_RANKS, case.to_dev(X), slots, batch, q_len, positions)
+    det = {}
+    want, _ = O.block_all_ranks(case.sh, X, case.shards[0], case.caches[0], positions, batch, q_len, flag, det)
+    r = w.tp - 1
+    d2 = {}
+    c2 = O.KVCache(batch, w.kv_per_rank, 64, w.head_dim)
+    c2.k[...] = 0
+    # the last rank's intermediates: recompute them with a cache holding the same prefill
+    if max(positions) > 0:
+        k, v = inputs.kv_prefill(w, 0, r, batch, max(positions))
+        for b, p in enumerate(positions):
+            k[b, :, p:, :] = 0.0
+            v[b, :, p:, :] = 0.0
+        c2.fill(k, v)
+    Y = O.attention_partial(case.sh, X, case.shards[0][r], c2, positions, batch, q_len, detail=d2)
+    O.mlp_partial(case.sh, X + (Y if flag else sum(det["Y"])), case.shards[0][r], d2)
+    d2["Y"] = Y
+    _check_taps(taps, d2, w, "small")
+    err = assert_close(out.cpu().numpy(), want, w, "small block output")
+    say(f"  block output max err {err:.2e} (max |oracle| {np.max(np.abs(want)):.2f})")
+    # the appended keys / values: bf16 copies of the oracle's
+    for i, rr in enumerate(case.ranks):
+        n_pos = max(positions) + q_len
+        k, v = case.dev.read_kv(0, i, batch, n_pos)
+        for b, p in enumerate(positions):
+            ko, vo = case.caches[0][i].k[b, :, p:p + q_len], case.caches[0][i].v[b, :, p:p + q_len]
+            assert np.max(np.abs(k[b, :, p:p + q_len] - ko)) <= 2.0 ** -8 * np.max(np.abs(ko)) + 1e-3
+            assert np.max(np.abs(v[b, :, p:p + q_len] - vo)) <= 2.0 ** -8 * np.max(np.abs(vo)) + 1e-3
+    case.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# bf16 path, one rank of eight with peer slots as inputs, several layers, mixed mask
+# ------------------------------------------------------------------------------------------------
+MID = Workload(name="mid-bf16", hidden=1024, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=11008, n_layers=4,
+               tp=8, dtype=BF16, seed=13, batch=5, q_len=1, ctx=256, mask=(1, 0, 1, 1))
+
+
+@pytest.mark.parametrize("batch,q_len,positions", [(5, 1, [255, 100, 0, 31, 64]), (2, 24, [0, 100])],
+                         ids=["decode", "chunk"])
+def test_bf16_single_rank_model(gpu, batch, q_len, positions):
+    import torch
+    w, rank = MID, 3
+    M = batch * q_len
+    case = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=256, max_tokens=48)
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    # per layer: oracle fed the GPU's layer input
+    x = case.to_dev(X)
+    slots = case.to_dev(peers)
+    worst = 0.0
+    for l in range(w.n_layers):
+        x_host = x.cpu().numpy()
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, l, w.mask[l], rank, case.dev.weights[l], case.dev.kv[l], positions, batch,
+                            q_len, x, slots, out, case.dev.workspace)
+        torch.cuda.synchronize()
+        o_slots = peers.astype(np.float64)
+        want = O.block_single_rank(case.sh, x_host, case.shards[l][0], case.caches[l][0], positions, batch, q_len,
+                                   w.mask[l], rank, o_slots)
+        worst = max(worst, assert_close(out.cpu().numpy(), want, w, f"mid layer {l}"))
+        # the slot this rank wrote must be what the oracle's rank contributes to the last sync point
+        assert_close(slots[rank].cpu().numpy(), o_slots[rank], w, f"mid slot layer {l}")
+        # peers untouched, bit for bit
+        for i in range(w.tp):
+            if i != rank:
+                assert np.array_equal(slots[i].cpu().numpy(), peers[i])
+        x = out
+    say(f"mid {q_len=}: worst per-layer err {worst:.2e}")
+    chain = x.cpu().numpy()
+
+    # end to end through spd_model_forward on fresh caches: same kernels, same order -> same bits
+    case2 = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=256, max_tokens=48)
+    slots2 = case2.to_dev(peers)
+    out2 = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward(case2.dev.ctx, w.mask, rank, case2.dev.weights, case2.dev.kv, positions, batch, q_len,
+                                case2.to_dev(X), slots2, out2, case2.dev.workspace)
+    torch.cuda.synchronize()
+    assert syncs == B.spd_sync_count(case2.dev.ctx, w.mask) == 5
+    assert np.array_equal(out2.cpu().numpy(), chain)
+    want = O.model_single_rank(case2.sh, X, [s[0] for s in case2.shards], [c[0] for c in case2.caches], positions,
+                               batch, q_len, w.mask, rank, peers.astype(np.float64))
+    err = float(np.max(np.abs(chain - want)))
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    say(f"mid end-to-end over {w.n_layers} layers: max err {err:.2e}, output rms {rms:.2f}")
+    assert err <= 2e-2 * w.n_layers * max(1.0, rms)
+    # run twice: bit-identical (fixed summation orders, no float atomics)
+    case3 = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=256, max_tokens=48)
+    out3 = torch.empty_like(out2)
+    B.spd_model_forward(case3.dev.ctx, w.mask, rank, case3.dev.weights, case3.dev.kv, positions, batch, q_len,
+                        case3.to_dev(X), case3.to_dev(peers), out3, case3.dev.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(out3.cpu().numpy(), chain)
+    for c in (case, case2, case3):
+        c.close()
+
+
+def test_bf16_prefill_then_decode_matches_longer_prefill(gpu):
+    """KV-cache consistency on the device: 20 tokens at once == 12 at once + 8 one by one."""
+    import torch
+    w = SMALL
+    X = inputs.hidden_states(w, 20)
+    full = Case(w, gpu, ranks=range(w.tp), positions=[0], max_ctx=64, max_tokens=32)
+    slots = torch.zeros((w.tp, 20, w.hidden), dtype=torch.float32, device=gpu)
+    o_full = torch.empty((20, w.hidden), dtype=torch.float32, device=gpu)
+    B.spd_model_forward(full.dev.ctx, w.mask, B.SPD_ALL_RANKS, full.dev.weights, full.dev.kv, [0], 1, 20,
+                        full.to_dev(X), slots, o_full, full.dev.workspace)
+    step = Case(w, gpu, ranks=range(w.tp), positions=[0], max_ctx=64, max_tokens=32)
+    o_head = torch.empty((12, w.hidden), dtype=torch.float32, device=gpu)
+    B.spd_model_forward(step.dev.ctx, w.mask, B.SPD_ALL_RANKS, step.dev.weights, step.dev.kv, [0], 1, 12,
+                        step.to_dev(X[:12]), slots, o_head, step.dev.workspace)
+    torch.cuda.synchronize()
+    want, _ = O.model_all_ranks(full.sh, X, full.shards, full.caches, [0], 1, 20, w.mask)
+    assert_close(o_full.cpu().numpy(), want, w, "20-token chunk")
+    assert_close(o_head.cpu().numpy(), want[:12], w, "12-token chunk")
+    for t in range(12, 20):
+        o1 = torch.empty((1, w.hidden), dtype=torch.float32, device=gpu)
+        B.spd_model_forward(step.dev.ctx, w.mask, B.SPD_ALL_RANKS, step.dev.weights, step.dev.kv, [t], 1, 1,
+                            step.to_dev(X[t:t + 1]), slots, o1, step.dev.workspace)
+        torch.cuda.synchronize()
+        assert_close(o1.cpu().numpy()[0], want[t], w, f"step {t}")
+    full.close()
+    step.close()
+
+
+def test_edge_cases(gpu):
+    import torch
+    w = SMALL
+    # maximum position: the last slot of the cache; and maximum batch
+    case = Case(w, gpu, ranks=[1], positions=[63, 0, 63], max_ctx=64, max_tokens=16)
+    X = inputs.hidden_states(w, 3)
+    peers = inputs.peer_slots(w, 3)
+    slots = case.to_dev(peers)
+    out = torch.empty((3, w.hidden), dtype=torch.float32, device=gpu)
+    B.spd_block_forward(case.dev.ctx, 0, 1, 1, case.dev.weights[0], case.dev.kv[0], [63, 0, 63], 3, 1,
+                        case.to_dev(X), slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    want = O.block_single_rank(case.sh, X, case.shards[0][0], case.caches[0][0], [63, 0, 63], 3, 1, 1, 1,
+                               peers.astype(np.float64))
+    assert_close(out.cpu().numpy(), want, w, "max position")
+    # empty call: nothing is launched, the output buffer is left alone
+    out.fill_(5.0)
+    B.spd_block_forward(case.dev.ctx, 0, 1, 1, case.dev.weights[0], case.dev.kv[0], [], 0, 1,
+                        case.to_dev(X), slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    assert float(out.min()) == 5.0
+    # x_out may alias x_in
+    x = case.to_dev(X)
+    case_b = Case(w, gpu, ranks=[1], positions=[63, 0, 63], max_ctx=64, max_tokens=16)
+    B.spd_block_forward(case_b.dev.ctx, 0, 0, 1, case_b.dev.weights[0], case_b.dev.kv[0], [63, 0, 63], 3, 1,
+                        x, case_b.to_dev(peers), x, case_b.dev.workspace)
+    torch.cuda.synchronize()
+    want = O.block_single_rank(case_b.sh, X, case_b.shards[0][0], case_b.caches[0][0], [63, 0, 63], 3, 1, 0, 1,
+                               peers.astype(np.float64))
+    assert_close(x.cpu().numpy(), want, w, "aliased output")
+    case.close()
+    case_b.close()
+    # 64 sequences in one call
+    w64 = Workload(name="b64", hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn=128, n_layers=1, tp=2,
+                   dtype=BF16, seed=14, batch=64, q_len=1, ctx=32, mask=(1,))
+    pos = [(7 * i) % 32 for i in range(64)]
+    c64 = Case(w64, gpu, ranks=range(2), positions=pos, max_ctx=32, max_tokens=64)
+    X = inputs.hidden_states(w64, 64)
+    slots = torch.zeros((2, 64, 128), dtype=torch.float32, device=gpu)
+    out = torch.empty((64, 128), dtype=torch.float32, device=gpu)
+    B.spd_block_forward(c64.dev.ctx, 0, 1, B.SPD_ALL_RANKS, c64.dev.weights[0], c64.dev.kv[0], pos, 64, 1,
+                        c64.to_dev(X), slots, out, c64.dev.workspace)
+    torch.cuda.synchronize()
+    want, _ = O.block_all_ranks(c64.sh, X, c64.shards[0], c64.caches[0], pos, 64, 1, 1)
+    assert_close(out.cpu().numpy(), want, w64, "64 sequences")
+    c64.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# full-size shapes, in the launch configuration the bench times (2 layers each: one SPD, one TP)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["7b-decode", "13b-decode", "70b-decode"])
+def test_full_size_decode_shapes(gpu, name):
+    import torch
+    full = workloads.get(name)
+    w = full.with_layers(2).with_mask((1, 0))
+    layer_ids = [0, full.n_layers - 1]
+    positions = [full.ctx - 1] * full.batch
+    say(f"full-size {name}: batch {full.batch}, ctx {full.ctx}")
+    case = Case(w, gpu, ranks=[0], positions=positions, layer_ids=layer_ids)
+    M = full.batch
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    x = case.to_dev(X)
+    slots = case.to_dev(peers)
+    for l in range(2):
+        x_host = x.cpu().numpy()
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, l, w.mask[l], 0, case.dev.weights[l], case.dev.kv[l], positions, M, 1, x,
+                            slots, out, case.dev.workspace)
+        torch.cuda.synchronize()
+        want = O.block_single_rank(case.sh, x_host, case.shards[l][0], case.caches[l][0], positions, M, 1, w.mask[l],
+                                   0, peers.astype(np.float64))
+        err = assert_close(out.cpu().numpy(), want, w, f"{name} layer {layer_ids[l]} flag {w.mask[l]}")
+        say(f"  layer {layer_ids[l]} flag {w.mask[l]}: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
+        x = out
+    case.close()
+
+
+def test_full_size_prefill_shape_sampled_rows(gpu):
+    """LLaMA2-70B shard, 4 x 2048 tokens: the oracle computes sampled output rows one by one."""
+    import torch
+    full = workloads.LLAMA70B_PREFILL
+    w = full.with_layers(1)
+    M = full.batch * full.q_len
+    rows = np.array([0, 1, 15, 16, 17, 255, 256, 2047, 2048, 2049, 3000, 4095, 4096, 5555, 6143, 6144, 8000, 8191])
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    for flag in (1, 0):
+        say(f"full-size prefill flag={flag}")
+        case = Case(w.with_mask((flag,)), gpu, ranks=[0], positions=[0] * full.batch)
+        x = case.to_dev(X)
+        slots = case.to_dev(peers)
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, 0, flag, 0, case.dev.weights[0], case.dev.kv[0], [0] * full.batch,
+                            full.batch, full.q_len, x, slots, out, case.dev.workspace)
+        torch.cuda.synchronize()
+        got = out[torch.from_numpy(rows).to(gpu)].cpu().numpy()
+        got_slot = slots[0][torch.from_numpy(rows).to(gpu)].cpu().numpy()
+        del x, out
+        want = O.block_single_rank(case.sh, X, case.shards[0][0], case.caches[0][0], [0] * full.batch, full.batch,
+                                   full.q_len, flag, 0, peers, rows=rows)
+        err = assert_close(got, want, w, f"prefill rows flag={flag}")
+        say(f"  sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
+        # properties that hold at any size: peers' slots untouched; finite everywhere
+        assert np.array_equal(slots[5][:64].cpu().numpy(), peers[5][:64])
+        assert bool(torch.isfinite(slots[0]).all())
+        del slots
+        case.close()
+        torch.cuda.empty_cache()

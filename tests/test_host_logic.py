@@ -1,0 +1,253 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/spd.h declares, rejects
+bad arguments before touching a device, indexes ranks and counts sync points bit-exactly,
+and its packers are lossless permutations.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_20727_amd import binding as B
+from paper_2502_20727_amd import inputs, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+SMALL_BF16 = workloads.Workload(name="small-bf16", hidden=128, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=416,
+                                n_layers=3, tp=2, dtype=workloads.BF16, seed=7, batch=2, q_len=4, ctx=64,
+                                mask=(1, 0, 1))
+SMALL_F32 = workloads.Workload(name="small-f32", hidden=48, n_q_heads=6, n_kv_heads=3, head_dim=8, ffn=33,
+                               n_layers=2, tp=3, dtype=workloads.F32, seed=8, batch=2, q_len=3, ctx=32, mask=(1, 0))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "spd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = declared_functions()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names          # the binding covers the header, nothing more, nothing less
+
+
+def test_strerror():
+    assert B.strerror(0) == "ok"
+    for code in (B.SPD_EINVAL, B.SPD_EUNSUPPORTED, B.SPD_EHIP, -99):
+        assert B.strerror(code)
+
+
+def _cfg(**over):
+    base = dict(hidden=128, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=416, n_layers=2, tp_degree=2,
+                dtype=B.SPD_BF16, max_batch=2, max_ctx=64, max_tokens=16, rms_eps=1e-5, rope_base=10000.0)
+    base.update(over)
+    return B.spd_config(**base)
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(hidden=0), B.SPD_EINVAL),
+    (dict(tp_degree=3), B.SPD_EINVAL),                 # does not divide the heads
+    (dict(ffn=417), B.SPD_EINVAL),                     # ffn not divisible by tp
+    (dict(n_q_heads=6), B.SPD_EINVAL),                 # not a multiple of the KV heads
+    (dict(head_dim=63), B.SPD_EINVAL),
+    (dict(max_ctx=48), B.SPD_EINVAL),
+    (dict(max_batch=B.SPD_MAX_BATCH + 1, max_tokens=100), B.SPD_EINVAL),
+    (dict(max_tokens=1), B.SPD_EINVAL),
+    (dict(n_kv_heads=1, n_q_heads=8), B.SPD_EUNSUPPORTED),   # a KV head shared by two ranks
+    (dict(dtype=5), B.SPD_EUNSUPPORTED),
+    (dict(hidden=120), B.SPD_EUNSUPPORTED),            # bf16 path wants multiples of 32
+    (dict(ffn=408), B.SPD_EUNSUPPORTED),               # 204 per rank: not a multiple of 16
+    (dict(n_q_heads=136, n_kv_heads=4, tp_degree=2), B.SPD_EUNSUPPORTED),   # 34 query heads per KV head
+])
+def test_create_rejects(over, code):
+    with pytest.raises(B.SpdError) as e:
+        B.spd_create(_cfg(**over))
+    assert e.value.code == code
+
+
+def test_create_null():
+    out = C.c_void_p()
+    assert B.lib().spd_create(None, C.byref(out)) == B.SPD_EINVAL
+    assert B.lib().spd_create(C.byref(_cfg()), None) == B.SPD_EINVAL
+
+
+def test_config_roundtrip_and_sizes():
+    ctx = B.spd_create(_cfg())
+    c = B.spd_get_config(ctx)
+    assert (c.hidden, c.tp_degree, c.max_ctx) == (128, 2, 64)
+    s = B.spd_get_sizes(ctx)
+    # one rank: 4 query heads, 2 KV heads, 208 -> 224 padded FFN columns
+    weights = 128 * (8 * 64) + (4 * 64) * 128 + 2 * 128 * 224 + 224 * 128
+    assert s.weight_bytes >= 2 * weights and s.weight_bytes % 256 == 0
+    assert s.kv_bytes == 2 * (2 * 2 * 64 * 64 * 2) and s.workspace_bytes % 256 == 0
+    B.spd_destroy(ctx)
+
+
+def test_rank_indexing_is_contiguous_equal_blocks():
+    # Sec. 4.2.3: n(A_i) = N / number_of_devices heads per device
+    w = workloads.LLAMA70B_DECODE
+    ctx = B.spd_create(B.make_config(w))
+    seen_q, seen_kv, seen_f = [], [], []
+    for r in range(w.tp):
+        f, n = B.spd_rank_q_heads(ctx, r); seen_q += list(range(f, f + n)); assert n == 8
+        f, n = B.spd_rank_kv_heads(ctx, r); seen_kv += list(range(f, f + n)); assert n == 1
+        f, n = B.spd_rank_ffn_cols(ctx, r); seen_f += list(range(f, f + n)); assert n == 3584
+    assert seen_q == list(range(64)) and seen_kv == list(range(8)) and seen_f == list(range(28672))
+    for bad in (-1, w.tp):
+        with pytest.raises(B.SpdError):
+            B.spd_rank_q_heads(ctx, bad)
+    B.spd_destroy(ctx)
+
+
+@pytest.mark.parametrize("w", [workloads.TOY, workloads.LLAMA13B_DECODE, workloads.LLAMA70B_DECODE,
+                               workloads.LLAMA70B_PREFILL])
+def test_sync_count(w):
+    # two sync points per TP block, one per SPD block (Sec. 3: SPD at 100 % halves them)
+    ctx = B.spd_create(B.make_config(w, max_ctx=64, max_tokens=64, max_batch=1))
+    L = w.n_layers
+    assert B.spd_sync_count(ctx, w.mask) == L + (L - sum(w.mask))
+    assert B.spd_sync_count(ctx, [1] * L) == L
+    assert B.spd_sync_count(ctx, [0] * L) == 2 * L
+    with pytest.raises(B.SpdError):
+        B.spd_sync_count(ctx, [2] + [0] * (L - 1))
+    B.spd_destroy(ctx)
+
+
+def test_workload_masks():
+    assert workloads.TOY.mask == (1, 0)
+    assert sum(workloads.LLAMA7B_DECODE.mask) == 32
+    m = workloads.LLAMA13B_DECODE.mask
+    assert [l for l in range(40) if m[l] == 0] == list(range(3, 40, 4))
+    m = workloads.LLAMA70B_DECODE.mask
+    assert m[:8] == (0,) * 8 and m[72:] == (0,) * 8 and sum(m) == 64
+
+
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32])
+def test_pack_is_a_lossless_slice(w):
+    ctx = B.spd_create(B.make_config(w))
+    dense = inputs.dense_layer(w, 1)
+    for r in range(w.tp):
+        shard = inputs.layer_shard(w, 1, r)
+        a = B.spd_pack_shard(ctx, r, dense)
+        b = B.spd_pack_shard_local(ctx, shard)
+        assert np.array_equal(a, b)                                   # slicing by rank == the rank's shard
+        back = B.spd_unpack_shard(ctx, a, {k: v.shape for k, v in shard.items()})
+        for k in shard:
+            assert np.array_equal(back[k], shard[k]), k               # bit-exact round trip
+    # different ranks really get different columns
+    assert not np.array_equal(B.spd_pack_shard(ctx, 0, dense), B.spd_pack_shard(ctx, 1, dense))
+    with pytest.raises(B.SpdError):
+        B.spd_pack_shard(ctx, w.tp, dense)
+    B.spd_destroy(ctx)
+
+
+def test_pack_every_value_lands_exactly_once():
+    # a packed bf16 shard is a permutation of the shard's values plus zero padding
+    w = SMALL_BF16
+    ctx = B.spd_create(B.make_config(w))
+    shard = inputs.layer_shard(w, 0, 1)
+    n = 0
+    for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+        a = shard[k]
+        a[...] = (np.arange(n, n + a.size, dtype=np.int64) % 251 + 1).reshape(a.shape).astype(np.float32)
+        n += a.size
+    packed = B.spd_pack_shard_local(ctx, shard)
+    vals = packed[2 * 256 * 2:].view(np.uint16)                       # skip the two fp32 gain vectors
+    as_f32 = (vals.astype(np.uint32) << 16).view(np.float32)
+    got = np.bincount(as_f32.astype(np.int64), minlength=252)
+    want = np.zeros(252, dtype=np.int64)
+    for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+        want += np.bincount(shard[k].astype(np.int64).ravel(), minlength=252)
+    assert np.array_equal(got[1:], want[1:])
+    B.spd_destroy(ctx)
+
+
+def test_pack_rejects_values_that_are_not_bf16():
+    w = SMALL_BF16
+    ctx = B.spd_create(B.make_config(w))
+    shard = inputs.layer_shard(w, 0, 0)
+    shard["wd"][3, 5] = np.float32(1.0 + 2.0 ** -12)
+    with pytest.raises(B.SpdError) as e:
+        B.spd_pack_shard_local(ctx, shard)
+    assert e.value.code == B.SPD_EINVAL
+    B.spd_destroy(ctx)
+
+
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32])
+def test_kv_pack_roundtrip(w):
+    ctx = B.spd_create(B.make_config(w))
+    sizes = B.spd_get_sizes(ctx)
+    k, v = inputs.kv_prefill(w, 0, 1, w.batch, 37 if w.dtype == workloads.BF16 else 20)
+    cache = np.zeros(sizes.kv_bytes, dtype=np.uint8)
+    B.spd_kv_pack(ctx, k, v, cache)
+    k2, v2 = B.spd_kv_unpack(ctx, cache, w.batch, k.shape[2], w.kv_per_rank, w.head_dim)
+    assert np.array_equal(k, k2) and np.array_equal(v, v2)
+    # positions beyond n_pos stay zero
+    k3, v3 = B.spd_kv_unpack(ctx, cache, w.batch, k.shape[2] + 5, w.kv_per_rank, w.head_dim)
+    assert not k3[:, :, k.shape[2]:].any() and not v3[:, :, k.shape[2]:].any()
+    B.spd_destroy(ctx)
+
+
+def test_forward_calls_reject_bad_arguments_before_any_launch():
+    # fake, suitably aligned addresses: every one of these calls must fail on the host
+    w = SMALL_BF16
+    ctx = B.spd_create(B.make_config(w))
+    P = 0x10000
+    ok = dict(ctx=ctx, layer=0, spd_flag=1, rank=0, packed_weights=P, kv_cache=P, positions=[0, 0], batch=2,
+              q_len=4, x_in=P, slots=P, x_out=P, workspace=P, stream=0)
+
+    def call(**over):
+        a = dict(ok); a.update(over)
+        with pytest.raises(B.SpdError) as e:
+            B.spd_block_forward(**a)
+        return e.value.code
+
+    assert call(rank=2) == B.SPD_EINVAL
+    assert call(rank=-2) == B.SPD_EINVAL
+    assert call(spd_flag=2) == B.SPD_EINVAL
+    assert call(layer=3) == B.SPD_EINVAL
+    assert call(batch=3, positions=[0, 0, 0]) == B.SPD_EINVAL          # > max_batch
+    assert call(q_len=5) == B.SPD_EINVAL                               # > max_tokens
+    assert call(positions=[0, 61]) == B.SPD_EINVAL                     # 61 + 4 > max_ctx
+    assert call(positions=[-1, 0]) == B.SPD_EINVAL
+    assert call(x_in=P + 4) == B.SPD_EINVAL                            # misaligned
+    for name in ("packed_weights", "kv_cache", "x_in", "slots", "x_out", "workspace"):
+        assert call(**{name: None}) == B.SPD_EINVAL, name
+
+    okm = dict(ctx=ctx, spd_mask=[1, 0, 1], rank=0, layer_weights=[P] * 3, layer_kv=[P] * 3, positions=[0, 0],
+               batch=2, q_len=4, x_in=P, slots=P, x_out=P, workspace=P, stream=0)
+
+    def callm(**over):
+        a = dict(okm); a.update(over)
+        with pytest.raises(B.SpdError) as e:
+            B.spd_model_forward(**a)
+        return e.value.code
+
+    assert callm(spd_mask=[1, 2, 0]) == B.SPD_EINVAL
+    assert callm(rank=5) == B.SPD_EINVAL
+    assert callm(layer_weights=[P, None, P]) == B.SPD_EINVAL
+    assert callm(positions=[0, 62]) == B.SPD_EINVAL
+    # empty calls are valid no-ops
+    B.spd_block_forward(**dict(ok, batch=0, positions=[]))
+    assert B.spd_model_forward(**dict(okm, q_len=0)) == 0
+    with pytest.raises(B.SpdError):
+        B.spd_rank_sum(ctx, None, None, 2, 16, P, stream=0)
+    B.spd_rank_sum(ctx, None, None, 0, 0, P, stream=0)                 # zero elements: nothing to do
+    B.spd_destroy(ctx)
+
+
+def test_inputs_are_counter_based():
+    w = SMALL_BF16
+    a = inputs.hidden_states(w, 6)
+    b = inputs.hidden_states(w, 2, first_token=3)
+    assert np.array_equal(a[3:5], b)
+    s0, s1 = inputs.layer_shard(w, 0, 0), inputs.layer_shard(w, 0, 1)
+    assert not np.array_equal(s0["wq"], s1["wq"]) and np.array_equal(s0["g1"], s1["g1"])
+    bits = s0["wq"].view(np.uint32)
+    assert not (bits & 0xFFFF).any()                                   # bf16-representable
+    x = inputs.normal((200000,), 1, inputs.T_MISC)
+    assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.01
