@@ -208,6 +208,28 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
                       const float *x_in, float *slots, float *x_out, void *workspace,
                       void *stream, int64_t *n_rank_sums);
 
+/* ---------------------------------------------------------------- stage timing (benchmarks)
+ * The stages of a block as the library launches them.  While timing is enabled for a
+ * stage, every forward call brackets each launch of that stage with a pair of HIP events
+ * on the call's stream (so the call must not be under stream capture).  The events are
+ * process-wide state, created by spd_profile_enable(): not for concurrent use. */
+#define SPD_STAGE_PREP 0    /* rank-sum + first-norm elementwise work */
+#define SPD_STAGE_QKV 1     /* QKV projection + rotary + cache append */
+#define SPD_STAGE_ATTN 2    /* attention over the KV cache (all its kernels) */
+#define SPD_STAGE_O 3       /* O projection + residual fold */
+#define SPD_STAGE_GATEUP 4  /* gate/up projection + SwiGLU */
+#define SPD_STAGE_DOWN 5    /* down projection + partial-sum fold */
+#define SPD_N_STAGES 6
+
+/* Start timing `stage` with room for `max_records` launches (older records are kept until
+ * spd_profile_disable()).  SPD_EINVAL for an unknown stage or max_records <= 0. */
+int spd_profile_enable(int32_t stage, int32_t max_records);
+/* Waits for the recorded events, then returns the number of launches timed and their mean
+ * and minimum duration in microseconds (any pointer may be NULL).  Resets the record count. */
+int spd_profile_read(int32_t *n_records, double *mean_us, double *min_us);
+/* Stops timing and destroys the events. */
+int spd_profile_disable(void);
+
 #ifdef __cplusplus
 }
 #endif

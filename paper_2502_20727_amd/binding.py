@@ -74,8 +74,12 @@ _PROTOS = {
     "spd_model_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.POINTER(C.c_int64)]),
+    "spd_profile_enable": (C.c_int, [C.c_int32, C.c_int32]),
+    "spd_profile_read": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "spd_profile_disable": (C.c_int, []),
 }
 EXPORTS = tuple(_PROTOS)
+STAGES = {"prep": 0, "qkv": 1, "attn": 2, "o": 3, "gateup": 4, "down": 5}
 
 
 def lib():
@@ -272,6 +276,21 @@ def spd_model_forward(ctx: int, spd_mask: Sequence[int], rank: int, layer_weight
                                    _ptr(x_out), _ptr(workspace), _stream_ptr(stream), C.byref(syncs)),
            "spd_model_forward")
     return syncs.value
+
+
+def spd_profile_enable(stage: int, max_records: int) -> None:
+    _check(lib().spd_profile_enable(stage, max_records), "spd_profile_enable")
+
+
+def spd_profile_read():
+    """(launches timed, mean microseconds, min microseconds) since the last read."""
+    n, mean, mn = C.c_int32(), C.c_double(), C.c_double()
+    _check(lib().spd_profile_read(C.byref(n), C.byref(mean), C.byref(mn)), "spd_profile_read")
+    return n.value, mean.value, mn.value
+
+
+def spd_profile_disable() -> None:
+    _check(lib().spd_profile_disable(), "spd_profile_disable")
 
 
 # --------------------------------------------------------------------------- device-memory plumbing

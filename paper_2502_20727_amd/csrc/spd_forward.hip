@@ -1,6 +1,7 @@
 // Device-facing entry points of the C ABI: argument checks on the host, then the sequence
 // of kernel launches that makes up one rank's share of a TP or SPD decoder block.
 #include <cstring>
+#include <vector>
 
 #include "spd_internal.h"
 
@@ -173,6 +174,74 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
         x = x_out;
     }
     if (n_rank_sums) *n_rank_sums = syncs;
+    return SPD_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// stage timing
+// ------------------------------------------------------------------------------------------
+namespace {
+struct ProfileState {
+    int stage = -1;
+    int cap = 0, n = 0;
+    std::vector<hipEvent_t> start, stop;
+} g_prof;
+}  // namespace
+
+namespace spd_profile {
+void begin(int stage, hipStream_t s) {
+    if (stage != g_prof.stage || g_prof.n >= g_prof.cap) return;
+    (void)hipEventRecord(g_prof.start[g_prof.n], s);
+}
+void end(int stage, hipStream_t s) {
+    if (stage != g_prof.stage || g_prof.n >= g_prof.cap) return;
+    (void)hipEventRecord(g_prof.stop[g_prof.n], s);
+    ++g_prof.n;
+}
+}  // namespace spd_profile
+
+extern "C" {
+
+int spd_profile_disable(void) {
+    for (auto e : g_prof.start) (void)hipEventDestroy(e);
+    for (auto e : g_prof.stop) (void)hipEventDestroy(e);
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.stage = -1;
+    g_prof.cap = g_prof.n = 0;
+    return SPD_OK;
+}
+
+int spd_profile_enable(int32_t stage, int32_t max_records) {
+    if (stage < 0 || stage >= SPD_N_STAGES || max_records <= 0) return SPD_EINVAL;
+    spd_profile_disable();
+    g_prof.start.resize(max_records);
+    g_prof.stop.resize(max_records);
+    for (int i = 0; i < max_records; ++i) {
+        SPD_HIP(hipEventCreate(&g_prof.start[i]));
+        SPD_HIP(hipEventCreate(&g_prof.stop[i]));
+    }
+    g_prof.cap = max_records;
+    g_prof.n = 0;
+    g_prof.stage = stage;
+    return SPD_OK;
+}
+
+int spd_profile_read(int32_t *n_records, double *mean_us, double *min_us) {
+    double sum = 0.0, mn = 1e30;
+    for (int i = 0; i < g_prof.n; ++i) {
+        SPD_HIP(hipEventSynchronize(g_prof.stop[i]));
+        float ms = 0.f;
+        SPD_HIP(hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]));
+        sum += (double)ms * 1000.0;
+        if ((double)ms * 1000.0 < mn) mn = (double)ms * 1000.0;
+    }
+    if (n_records) *n_records = g_prof.n;
+    if (mean_us) *mean_us = g_prof.n ? sum / g_prof.n : 0.0;
+    if (min_us) *min_us = g_prof.n ? mn : 0.0;
+    g_prof.n = 0;
     return SPD_OK;
 }
 

@@ -105,6 +105,18 @@ struct spd_call {
     const spd_taps *taps;
 };
 
+// stage timing: brackets a launch with events when spd_profile_enable() selected the stage
+namespace spd_profile {
+void begin(int stage, hipStream_t s);
+void end(int stage, hipStream_t s);
+struct scope {
+    int stage;
+    hipStream_t s;
+    scope(int st, hipStream_t str) : stage(st), s(str) { begin(stage, s); }
+    ~scope() { end(stage, s); }
+};
+}
+
 namespace spd_common {
 hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s);
 hipError_t fill_zero_u32(uint32_t *p, size_t n, hipStream_t s);

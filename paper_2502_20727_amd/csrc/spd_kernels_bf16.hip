@@ -589,6 +589,7 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     __bf16 *xhat = want_xhat ? (__bf16 *)(c.ws + (which ? D.ws_xhat2 : D.ws_xhat)) : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base) out = nullptr;   // nothing to rewrite
+    spd_profile::scope prof(SPD_STAGE_PREP, c.s);
     hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
                        (size_t)c.M * D.h, out, gain, xhat, ss, c.M, D.h, tpw, D.m_pad);
     return hipGetLastError();
@@ -608,9 +609,13 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e1.ss = (const float *)(c.ws + D.ws_ss1);
     e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
     e1.qbuf = qbuf; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
-    SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_qkv), xhat, D.nqkv / 32, D.h / 32, M, e1, c.s));
+    {
+        spd_profile::scope prof(SPD_STAGE_QKV, c.s);
+        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_qkv), xhat, D.nqkv / 32, D.h / 32, M, e1, c.s));
+    }
 
     const int DT = D.d / 16;
+    spd_profile::begin(SPD_STAGE_ATTN, c.s);
     if (c.q_len == 1) {
         const int nblk = (c.max_pos_end + 31) / 32;
         int splits = nblk / 4;
@@ -649,13 +654,17 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
 #undef SPD_PREFILL
         SPD_TRY(hipGetLastError());
     }
+    spd_profile::end(SPD_STAGE_ATTN, c.s);
 
     EpiO e2;
     e2.M = M; e2.h = D.h; e2.spd = spd; e2.m_pad = D.m_pad;
     e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
     e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
     e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
-    SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_o), ahat, D.h / 32, qd / 32, M, e2, c.s));
+    {
+        spd_profile::scope prof(SPD_STAGE_O, c.s);
+        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_o), ahat, D.h / 32, qd / 32, M, e2, c.s));
+    }
 
     if (c.taps) {
         if (c.taps->q) {
@@ -682,12 +691,18 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, int 
     e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.nch = nch2; e1.m_pad = D.m_pad; e1.eps = D.eps;
     e1.ss = (const float *)(c.ws + D.ws_ss2);
     e1.uhat = uhat;
-    SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, M, e1, c.s));
+    {
+        spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
+        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, M, e1, c.s));
+    }
 
     EpiDown e2;
     e2.M = M; e2.h = D.h; e2.spd = spd;
     e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
-    SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_d), uhat, D.h / 32, D.f_pad / 32, M, e2, c.s));
+    {
+        spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
+        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_d), uhat, D.h / 32, D.f_pad / 32, M, e2, c.s));
+    }
 
     if (c.taps && c.taps->u) {
         hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, c.taps->u, M, D.f_pad, D.f);
