@@ -139,7 +139,7 @@ def cpu_baseline(w, inputs, positions, X, peers, budget_s=20.0):
     done, spent, per_layer = 0, 0.0, []
     while done < w.n_layers and (done == 0 or spent + (spent / done) < budget_s):
         shard = inputs.layer_shard(w, done, 0)
-        cache = O.KVCache(w.batch, w.kv_per_rank, mc, w.head_dim)
+        cache = O.KVCache(w.batch, w.kv_per_rank, mc, w.head_dim, storage="bf16" if w.dtype == 1 else "f64")
         if n_pre > 0:
             k, v = inputs.kv_prefill(w, done, 0, w.batch, n_pre)
             cache.fill(k, v)

@@ -75,7 +75,17 @@ typedef struct spd_config {
     int32_t max_tokens;  /* largest batch*q_len of a single call */
     float rms_eps;       /* 1e-5 for LLaMA2 */
     float rope_base;     /* 10000 for LLaMA2 */
+    int32_t act_split;   /* SPD_BF16 only: SPD_SPLIT_AUTO | SPD_SPLIT_ALWAYS | SPD_SPLIT_NEVER */
 } spd_config;
+
+/* bf16 MFMA needs bf16 activations.  With "split" activations every activation that feeds a
+ * projection is kept as a pair hi + lo of bf16 values (lo = the rounding error of hi) and the
+ * contraction runs over both, which removes the activation rounding from the result at the
+ * price of twice the MFMA work.  AUTO splits calls of at most 16 tokens, where the
+ * projections are bound by weight streaming and the extra MFMA work is free. */
+#define SPD_SPLIT_AUTO 0
+#define SPD_SPLIT_ALWAYS 1
+#define SPD_SPLIT_NEVER 2
 
 typedef struct spd_ctx spd_ctx;
 
@@ -114,7 +124,7 @@ typedef struct spd_taps {
  * max_ctx not a multiple of 32.  SPD_EUNSUPPORTED: n_kv_heads < tp_degree (a KV head
  * shared by several ranks); unknown dtype; for SPD_BF16: hidden or head_dim not a
  * multiple of 32, ffn / tp_degree not a multiple of 16, more than 16 query heads per
- * KV head. */
+ * KV head.  act_split outside its three values: SPD_EINVAL. */
 int spd_create(const spd_config *cfg, spd_ctx **out);
 void spd_destroy(spd_ctx *ctx);
 int spd_get_config(const spd_ctx *ctx, spd_config *out);
@@ -153,7 +163,10 @@ int spd_kv_unpack(const spd_ctx *ctx, const void *cache_host, int32_t batch, int
 
 /* ---------------------------------------------------------------- device calls */
 
-/* Prepares a workspace (device, workspace_bytes): uploads the rotary table and clears the
+/* The KV cache must be zero-filled once before its first use (positions that were never
+ * written are read as padding of the last key block and multiplied by a zero weight).
+ *
+ * Prepares a workspace (device, workspace_bytes): uploads the rotary table and clears the
  * library's counters.  Call once per workspace before the first forward; synchronises
  * the stream before returning. */
 int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream);

@@ -111,12 +111,35 @@ def token_positions(positions: Sequence[int], batch: int, q_len: int) -> np.ndar
     return (positions[:, None] + np.arange(q_len, dtype=np.int64)[None, :]).reshape(-1)
 
 
-class KVCache:
-    """One device's keys and values of one layer: [batch, kv_heads, max_ctx, d] float64."""
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 value (ties to even) of every element, returned as float64."""
+    f = np.asarray(a, np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(F64).reshape(np.shape(a))
 
-    def __init__(self, batch: int, kv_heads: int, max_ctx: int, head_dim: int):
+
+class KVCache:
+    """One device's keys and values of one layer: [batch, kv_heads, max_ctx, d] float64.
+
+    `storage` is the number format the cache is defined to hold.  A bf16 cache stores bf16
+    values: keys and values are rounded once, when they are stored, and every later use
+    reads the stored value (all arithmetic stays float64).  This is a property of the data
+    structure the workload names, not of any implementation of it.
+    """
+
+    def __init__(self, batch: int, kv_heads: int, max_ctx: int, head_dim: int, storage: str = "f64"):
+        assert storage in ("f64", "bf16")
+        self.storage = storage
         self.k = np.zeros((batch, kv_heads, max_ctx, head_dim), F64)
         self.v = np.zeros((batch, kv_heads, max_ctx, head_dim), F64)
+
+    def store(self, b: int, pos: int, k: np.ndarray, v: np.ndarray) -> None:
+        """Append one token's keys and values [kv_heads, d] at position `pos` of sequence b."""
+        if self.storage == "bf16":
+            k, v = round_to_bf16(k), round_to_bf16(v)
+        self.k[b, :, pos, :] = k
+        self.v[b, :, pos, :] = v
 
     def fill(self, k: np.ndarray, v: np.ndarray) -> None:
         """Load positions [0, n) from natural-layout arrays [batch, kv, n, d]."""
@@ -126,6 +149,7 @@ class KVCache:
 
     def copy(self) -> "KVCache":
         c = KVCache.__new__(KVCache)
+        c.storage = self.storage
         c.k = self.k.copy()
         c.v = self.v.copy()
         return c
@@ -154,8 +178,7 @@ def attention_partial(sh: Shapes, X: np.ndarray, W: Dict[str, np.ndarray], cache
     V = (n @ np.asarray(W["wv"], F64)).reshape(T, kv, d)
     for t in range(T):
         b = t // q_len
-        cache.k[b, :, pos[t], :] = K[t]
-        cache.v[b, :, pos[t], :] = V[t]
+        cache.store(b, int(pos[t]), K[t], V[t])
 
     sel = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
     Q = rope((n[sel] @ np.asarray(W["wq"], F64)).reshape(len(sel), q, d), pos[sel], sh.rope_base)

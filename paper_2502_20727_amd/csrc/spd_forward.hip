@@ -31,6 +31,8 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->ws = (char *)workspace;
     c->taps = nullptr;
     c->max_pos_end = 0;
+    c->split = D.dtype == SPD_BF16 && (ctx->cfg.act_split == SPD_SPLIT_ALWAYS ||
+                                       (ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= 16));
     std::memset(&c->pos, 0, sizeof(c->pos));
     for (int b = 0; b < batch; ++b) {
         if (positions[b] < 0 || (int64_t)positions[b] + q_len > D.max_ctx) return SPD_EINVAL;

@@ -88,13 +88,15 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     D.ws_y = o; o = spd_align256(o + M * h * 4);
     D.ws_r = o; o = spd_align256(o + M * h * 4);
     if (bf) {
-        D.ws_xhat = o; o = spd_align256(o + M * h * 2);
-        D.ws_xhat2 = o; o = spd_align256(o + M * h * 2);
-        D.ws_q = o; o = spd_align256(o + M * qd * 2);
-        D.ws_ahat = o; o = spd_align256(o + M * qd * 2);
+        D.pl_x = M * h; D.pl_a = M * qd; D.pl_u = M * f;
+        D.ws_xhat = o; o = spd_align256(o + 2 * M * h * 2);
+        D.ws_xhat2 = o; o = spd_align256(o + 2 * M * h * 2);
+        D.ws_q = o; o = spd_align256(o + 2 * M * qd * 2);
+        D.ws_ahat = o; o = spd_align256(o + 2 * M * qd * 2);
         D.ws_ss1 = o; o = spd_align256(o + (h / 32) * M * 4);
         D.ws_ss2 = o; o = spd_align256(o + (h / 32) * M * 4);
-        D.ws_uhat = o; o = spd_align256(o + M * f * 2);
+        D.ws_uhat = o; o = spd_align256(o + 2 * M * f * 2);
+        D.ws_kpart = o; o = spd_align256(o + (size_t)SPD_MAX_KPART * 512 * 4);
         D.ws_apart = o;
         o = spd_align256(o + (size_t)D.max_batch * D.kv * SPD_MAX_SPLITS * 16 * (D.d + 2) * 4);
     } else {
@@ -167,6 +169,8 @@ int spd_create(const spd_config *cfg, spd_ctx **out) {
     if (c.max_batch > SPD_MAX_BATCH || c.max_ctx % 32) return SPD_EINVAL;
     if (c.max_tokens < c.max_batch) return SPD_EINVAL;
     if (c.dtype != SPD_F32 && c.dtype != SPD_BF16) return SPD_EUNSUPPORTED;
+    if (c.act_split != SPD_SPLIT_AUTO && c.act_split != SPD_SPLIT_ALWAYS && c.act_split != SPD_SPLIT_NEVER)
+        return SPD_EINVAL;
     if (c.n_kv_heads < c.tp_degree) return SPD_EUNSUPPORTED;   // a KV head shared by several ranks
     if (c.n_q_heads % c.tp_degree || c.n_kv_heads % c.tp_degree || c.ffn % c.tp_degree) return SPD_EINVAL;
     if (c.dtype == SPD_BF16) {

@@ -30,6 +30,7 @@
 constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
 constexpr int SPD_N_COUNTERS = 8192;
+constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
 
 SPD_HD size_t spd_frag_index(int tile, int ktile, int n_ktiles) {
     return ((size_t)tile * (size_t)n_ktiles + (size_t)ktile) * SPD_FRAG_ELEMS;
@@ -77,7 +78,10 @@ struct spd_dims {
     size_t kv_v, kv_bytes;
     // workspace (bytes)
     size_t ws_cos, ws_sin, ws_counters, ws_xhat, ws_xhat2, ws_q, ws_ahat, ws_y, ws_r, ws_ss1, ws_ss2, ws_uhat,
-        ws_apart, ws_qkv, ws_gu, workspace_bytes;
+        ws_apart, ws_kpart, ws_qkv, ws_gu, workspace_bytes;
+    // bf16 path: every packed activation buffer has a second plane (the "lo" halves) this many
+    // elements after the first
+    size_t pl_x, pl_a, pl_u;
 };
 
 struct spd_ctx {
@@ -101,6 +105,7 @@ struct spd_call {
     int batch, q_len, M;
     spd_positions pos;
     int max_pos_end;          // max over sequences of positions[b] + q_len
+    bool split;               // bf16 path: activations carried as hi + lo pairs
     char *ws;                 // workspace
     const spd_taps *taps;
 };

@@ -7,6 +7,10 @@
 // features 4*(l/16) .. 4*(l/16)+3.  Four consecutive features per lane is exactly what the
 // next contraction wants as its packed operand, so every epilogue stores 8-byte pieces
 // straight into the next kernel's fragment layout.
+//
+// "Split" activations: an activation buffer may carry a second plane holding, for every
+// element, the bf16 rounding error of the first plane (x = hi + lo up to 2^-17 relative).
+// Contractions then run over both planes.
 #include "spd_internal.h"
 
 namespace {
@@ -22,6 +26,10 @@ __device__ __forceinline__ bf16x4 cvt4(float a, float b, float c, float d) {
     r[0] = (__bf16)a; r[1] = (__bf16)b; r[2] = (__bf16)c; r[3] = (__bf16)d;
     return r;
 }
+// rounding error of cvt4, itself rounded to bf16
+__device__ __forceinline__ bf16x4 cvt4_lo(float a, float b, float c, float d, bf16x4 hi) {
+    return cvt4(a - (float)hi[0], b - (float)hi[1], c - (float)hi[2], d - (float)hi[3]);
+}
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // 1 / sqrt(mean(x^2) + eps) of row m from `nch` partial sums of squares ss[c][m]; the four
@@ -36,14 +44,15 @@ __device__ __forceinline__ float row_rsqrt(const float *__restrict__ ss, int nch
 }
 
 // ------------------------------------------------------------------------------------------
-// prep: out = base + (slot0 + slot1 + ...), xhat = bf16(out * gain) in packed layout, and the
-// partial sums of squares of `out` per (k-chunk, token).  One wave per (m-tile, chunk of
-// `tpw` k-tiles); lane l handles token l%16 and 8 consecutive features.
+// prep: out = base + (slot0 + slot1 + ...), xhat = bf16(out * gain) in packed layout (plus its
+// lo plane), and the partial sums of squares of `out` per (k-chunk, token).  One wave per
+// (m-tile, chunk of `tpw` k-tiles); lane l handles token l%16 and 8 consecutive features.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, const float *__restrict__ slots,
                                               int n_slots, size_t slot_stride, float *__restrict__ out,
                                               const float *__restrict__ gain, __bf16 *__restrict__ xhat,
-                                              float *__restrict__ ss, int M, int h, int tpw, int m_pad) {
+                                              __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h, int tpw,
+                                              int m_pad) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int KT = h >> 5;
     const int chunk = blockIdx.x * 4 + wave;
@@ -60,16 +69,28 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
         for (int i = 0; i < 8; ++i) v[i] = 0.f;
         if (valid) {
             const size_t o = (size_t)m * h + col;
-            if (n_slots > 0) {
-                float4 a0 = *(const float4 *)(slots + o), a1 = *(const float4 *)(slots + o + 4);
-                for (int s = 1; s < n_slots; ++s) {
-                    const float4 b0 = *(const float4 *)(slots + s * slot_stride + o);
-                    const float4 b1 = *(const float4 *)(slots + s * slot_stride + o + 4);
-                    a0.x += b0.x; a0.y += b0.y; a0.z += b0.z; a0.w += b0.w;
-                    a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
+            // partials in ascending slot order; the loads of a group of 8 slots are issued together
+            for (int s0 = 0; s0 < n_slots; s0 += 8) {
+                float4 p0[8], p1[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (s0 + j < n_slots) {
+                        p0[j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + o);
+                        p1[j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + o + 4);
+                    }
                 }
-                v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w;
-                v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (s0 + j < n_slots) {
+                        if (s0 + j == 0) {
+                            v[0] = p0[j].x; v[1] = p0[j].y; v[2] = p0[j].z; v[3] = p0[j].w;
+                            v[4] = p1[j].x; v[5] = p1[j].y; v[6] = p1[j].z; v[7] = p1[j].w;
+                        } else {
+                            v[0] += p0[j].x; v[1] += p0[j].y; v[2] += p0[j].z; v[3] += p0[j].w;
+                            v[4] += p1[j].x; v[5] += p1[j].y; v[6] += p1[j].z; v[7] += p1[j].w;
+                        }
+                    }
+                }
             }
             if (base) {
                 const float4 b0 = *(const float4 *)(base + o), b1 = *(const float4 *)(base + o + 4);
@@ -84,18 +105,22 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 #pragma unroll
         for (int i = 0; i < 8; ++i) ssum += v[i] * v[i];
         if (xhat) {
-            bf16x8 x;
+            bf16x8 x, xl;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = xl[i] = (__bf16)0.f;
             if (valid) {
                 const float4 g0 = *(const float4 *)(gain + col), g1 = *(const float4 *)(gain + col + 4);
-                x[0] = (__bf16)(v[0] * g0.x); x[1] = (__bf16)(v[1] * g0.y);
-                x[2] = (__bf16)(v[2] * g0.z); x[3] = (__bf16)(v[3] * g0.w);
-                x[4] = (__bf16)(v[4] * g1.x); x[5] = (__bf16)(v[5] * g1.y);
-                x[6] = (__bf16)(v[6] * g1.z); x[7] = (__bf16)(v[7] * g1.w);
-            } else {
+                const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = (__bf16)0.f;
+                for (int i = 0; i < 8; ++i) {
+                    const float p = v[i] * gg[i];
+                    x[i] = (__bf16)p;
+                    xl[i] = (__bf16)(p - (float)x[i]);
+                }
             }
-            *(bf16x8 *)(xhat + spd_frag_index(mt, kt, KT) + lane * 8) = x;
+            const size_t fo = spd_frag_index(mt, kt, KT) + lane * 8;
+            *(bf16x8 *)(xhat + fo) = x;
+            if (xlo) *(bf16x8 *)(xlo + fo) = xl;
         }
     }
     ssum += shfl_xor_f(ssum, 16);
@@ -111,7 +136,7 @@ struct EpiQKV {
     int M, q_len, q, kv, d, h, max_ctx, nch, m_pad;
     float eps;
     const float *ss, *cosT, *sinT;
-    __bf16 *qbuf, *kc, *vc;
+    __bf16 *qbuf, *qlo, *kc, *vc;     // queries are kept as hi + lo pairs
     spd_positions P;
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
@@ -129,14 +154,17 @@ struct EpiQKV {
             // rotary partners: a holds j = ca .. ca+3 (< d/2), b holds j + d/2
             const float4 c = *(const float4 *)(cosT + (size_t)pos * half + ca);
             const float4 s = *(const float4 *)(sinT + (size_t)pos * half + ca);
-            const bf16x4 lo = cvt4(a[0] * c.x - b[0] * s.x, a[1] * c.y - b[1] * s.y, a[2] * c.z - b[2] * s.z,
-                                   a[3] * c.w - b[3] * s.w);
-            const bf16x4 hi = cvt4(b[0] * c.x + a[0] * s.x, b[1] * c.y + a[1] * s.y, b[2] * c.z + a[2] * s.z,
-                                   b[3] * c.w + a[3] * s.w);
+            const float l0 = a[0] * c.x - b[0] * s.x, l1 = a[1] * c.y - b[1] * s.y, l2 = a[2] * c.z - b[2] * s.z,
+                        l3 = a[3] * c.w - b[3] * s.w;
+            const float h0 = b[0] * c.x + a[0] * s.x, h1 = b[1] * c.y + a[1] * s.y, h2 = b[2] * c.z + a[2] * s.z,
+                        h3 = b[3] * c.w + a[3] * s.w;
+            const bf16x4 lo = cvt4(l0, l1, l2, l3), hi = cvt4(h0, h1, h2, h3);
             if (head < q) {
-                __bf16 *dst = qbuf + (size_t)m * (q * d) + head * d;
-                *(bf16x4 *)(dst + ca) = lo;
-                *(bf16x4 *)(dst + cb) = hi;
+                const size_t o = (size_t)m * (q * d) + head * d;
+                *(bf16x4 *)(qbuf + o + ca) = lo;
+                *(bf16x4 *)(qbuf + o + cb) = hi;
+                *(bf16x4 *)(qlo + o + ca) = cvt4_lo(l0, l1, l2, l3, lo);
+                *(bf16x4 *)(qlo + o + cb) = cvt4_lo(h0, h1, h2, h3, hi);
             } else {
                 __bf16 *dst = kc + ((size_t)bseq * kv + (head - q)) * (size_t)max_ctx * d;
                 *(bf16x4 *)(dst + spd_kcache_off(pos, ca, d)) = lo;
@@ -157,7 +185,7 @@ struct EpiO {
     int M, h, spd, m_pad;
     const float *x, *g2;
     float *ybuf, *slot, *ss2;
-    __bf16 *xhat2;
+    __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
@@ -171,7 +199,7 @@ struct EpiO {
             return;
         }
         float ra[4] = {0.f, 0.f, 0.f, 0.f}, rb[4] = {0.f, 0.f, 0.f, 0.f};
-        bf16x4 xa = cvt4(0.f, 0.f, 0.f, 0.f), xb = xa;
+        float pa[4] = {0.f, 0.f, 0.f, 0.f}, pb[4] = {0.f, 0.f, 0.f, 0.f};
         if (valid) {
             const size_t o = (size_t)m * h;
             *(float4 *)(ybuf + o + na) = make_float4(a[0], a[1], a[2], a[3]);
@@ -180,13 +208,19 @@ struct EpiO {
             ra[0] = x0.x + a[0]; ra[1] = x0.y + a[1]; ra[2] = x0.z + a[2]; ra[3] = x0.w + a[3];
             rb[0] = x1.x + b[0]; rb[1] = x1.y + b[1]; rb[2] = x1.z + b[2]; rb[3] = x1.w + b[3];
             const float4 ga = *(const float4 *)(g2 + na), gb = *(const float4 *)(g2 + nb);
-            xa = cvt4(ra[0] * ga.x, ra[1] * ga.y, ra[2] * ga.z, ra[3] * ga.w);
-            xb = cvt4(rb[0] * gb.x, rb[1] * gb.y, rb[2] * gb.z, rb[3] * gb.w);
+            pa[0] = ra[0] * ga.x; pa[1] = ra[1] * ga.y; pa[2] = ra[2] * ga.z; pa[3] = ra[3] * ga.w;
+            pb[0] = rb[0] * gb.x; pb[1] = rb[1] * gb.y; pb[2] = rb[2] * gb.z; pb[3] = rb[3] * gb.w;
         }
+        const bf16x4 xa = cvt4(pa[0], pa[1], pa[2], pa[3]), xb = cvt4(pb[0], pb[1], pb[2], pb[3]);
         // the pair's 32 features are k-tile `pair` of the next contraction
-        __bf16 *fr = xhat2 + spd_frag_index(mt, pair, h >> 5);
-        *(bf16x4 *)(fr + spd_frag_elem(r, 4 * g)) = xa;
-        *(bf16x4 *)(fr + spd_frag_elem(r, 16 + 4 * g)) = xb;
+        const size_t fo = spd_frag_index(mt, pair, h >> 5);
+        const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
+        *(bf16x4 *)(xhat2 + fo + ea) = xa;
+        *(bf16x4 *)(xhat2 + fo + eb) = xb;
+        if (xlo2) {
+            *(bf16x4 *)(xlo2 + fo + ea) = cvt4_lo(pa[0], pa[1], pa[2], pa[3], xa);
+            *(bf16x4 *)(xlo2 + fo + eb) = cvt4_lo(pb[0], pb[1], pb[2], pb[3], xb);
+        }
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) s += ra[i] * ra[i] + rb[i] * rb[i];
@@ -200,24 +234,24 @@ struct EpiGU {
     int M, h, f_pad, nch, m_pad;
     float eps;
     const float *ss;
-    __bf16 *uhat;
+    __bf16 *uhat, *ulo;        // ulo may be NULL
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const float rs = row_rsqrt(ss, nch, m_pad, m, g, h, eps);
-        bf16x4 u = cvt4(0.f, 0.f, 0.f, 0.f);
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
         if (m < M) {
-            float o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float gt = a[i] * rs, up = b[i] * rs;
                 o[i] = gt / (1.0f + __expf(-gt)) * up;
             }
-            u = cvt4(o[0], o[1], o[2], o[3]);
         }
+        const bf16x4 u = cvt4(o[0], o[1], o[2], o[3]);
         // gate/up pair p covers FFN columns [16p, 16p+16): half of k-tile p/2 of the down projection
-        __bf16 *fr = uhat + spd_frag_index(mt, pair >> 1, f_pad >> 5);
-        *(bf16x4 *)(fr + spd_frag_elem(r, 16 * (pair & 1) + 4 * g)) = u;
+        const size_t fo = spd_frag_index(mt, pair >> 1, f_pad >> 5) + spd_frag_elem(r, 16 * (pair & 1) + 4 * g);
+        *(bf16x4 *)(uhat + fo) = u;
+        if (ulo) *(bf16x4 *)(ulo + fo) = cvt4_lo(o[0], o[1], o[2], o[3], u);
     }
 };
 
@@ -241,24 +275,114 @@ struct EpiDown {
 };
 
 // ------------------------------------------------------------------------------------------
-// GEMM, fragments streamed straight from global memory (no reuse through LDS).
+// GEMV-like projection for at most 16 tokens (one m-tile): bound by streaming the weights.
 //   out^T[n][m] = sum_k W[k][n] x[m][k]
-// grid.x = pairs of n-tiles, grid.y = groups of m-tiles.
-// SPLITK = true : the W waves of a workgroup split K, partial accumulators are added through
-//                 LDS in fixed wave order (deterministic); one m-group of MT tiles per workgroup.
-// SPLITK = false: each wave owns its own MT m-tiles and runs the whole K.
+// grid = (pairs of n-tiles, KS).  A workgroup owns one pair and one of KS slices of K; its W
+// waves split that slice, each wave streaming its weight fragments straight from HBM into
+// registers in batches of U k-tiles (all loads of a batch are issued before the first MFMA).
+// The waves' partial tiles are added through LDS in wave order.  With KS > 1 the workgroups
+// of a pair park their partial tile in `kpart`, and the last one to arrive (a counter per
+// pair) adds the KS tiles in slice order and runs the epilogue: the result does not depend
+// on which workgroup came last, so it is bit-reproducible.  No workgroup ever waits.
 // ------------------------------------------------------------------------------------------
-template <int MT, int W, bool SPLITK, class Epi>
-__global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp, int KT,
-                                                  int n_mtiles, Epi epi) {
+template <int W, int U, bool SPLIT, class Epi>
+__global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
+                                                  const __bf16 *__restrict__ Xlo, int KT, int KS,
+                                                  float *__restrict__ kpart, unsigned int *__restrict__ counters, Epi epi) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pair = blockIdx.x, ks = blockIdx.y;
+    const int kb0 = (int)(((long)ks * KT) / KS), kb1 = (int)(((long)(ks + 1) * KT) / KS);
+    const int nk = kb1 - kb0;
+    const int k0 = kb0 + (wave * nk) / W, k1 = kb0 + ((wave + 1) * nk) / W;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
+    const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
+    const bf16x8 *xh = (const bf16x8 *)Xhi + lane;
+    const bf16x8 *xl = (const bf16x8 *)Xlo + lane;
+    int kt = k0;
+    for (; kt + U <= k1; kt += U) {
+        bf16x8 fa[U], fb[U], fh[U], fl[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            fa[u] = __builtin_nontemporal_load(wa + (size_t)(kt + u) * 64);
+            fb[u] = __builtin_nontemporal_load(wb + (size_t)(kt + u) * 64);
+            fh[u] = xh[(size_t)(kt + u) * 64];
+            if (SPLIT) fl[u] = xl[(size_t)(kt + u) * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a = MFMA(fa[u], fh[u], a);
+            b = MFMA(fb[u], fh[u], b);
+            if (SPLIT) {
+                a = MFMA(fa[u], fl[u], a);
+                b = MFMA(fb[u], fl[u], b);
+            }
+        }
+    }
+    for (; kt < k1; ++kt) {
+        const bf16x8 fa = __builtin_nontemporal_load(wa + (size_t)kt * 64);
+        const bf16x8 fb = __builtin_nontemporal_load(wb + (size_t)kt * 64);
+        const bf16x8 fh = xh[(size_t)kt * 64];
+        a = MFMA(fa, fh, a);
+        b = MFMA(fb, fh, b);
+        if (SPLIT) {
+            const bf16x8 fl = xl[(size_t)kt * 64];
+            a = MFMA(fa, fl, a);
+            b = MFMA(fb, fl, b);
+        }
+    }
+    __shared__ f32x4 red[W][2][64];
+    red[wave][0][lane] = a;
+    red[wave][1][lane] = b;
+    __syncthreads();
+    if (wave != 0) return;
+    a = red[0][0][lane];
+    b = red[0][1][lane];
+#pragma unroll
+    for (int w = 1; w < W; ++w) {
+        a += red[w][0][lane];
+        b += red[w][1][lane];
+    }
+    if (KS > 1) {
+        // park the partial tile; agent-scope atomics so that another XCD's L2 sees it
+        unsigned int *mine = (unsigned int *)(kpart + ((size_t)pair * KS + ks) * 512) + lane;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __hip_atomic_store(mine + i * 64, __float_as_uint(a[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(mine + (4 + i) * 64, __float_as_uint(b[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        unsigned int old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(counters + pair, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        old = __shfl(old, 0, 64);
+        if (old != (unsigned int)(KS - 1)) return;   // not the last slice of this pair: done
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        a = (f32x4){0.f, 0.f, 0.f, 0.f};
+        b = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < KS; ++s) {
+            const unsigned int *src = (const unsigned int *)(kpart + ((size_t)pair * KS + s) * 512) + lane;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] += __uint_as_float(__hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                b[i] += __uint_as_float(__hip_atomic_load(src + (4 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            }
+        }
+        if (lane == 0) __hip_atomic_store(counters + pair, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    epi(pair, 0, a, b, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// GEMM for more than 16 tokens, fragments streamed straight from global memory: each wave owns
+// MT m-tiles and one pair of n-tiles and runs the whole K.  grid = (pairs, groups of W*MT m-tiles).
+// ------------------------------------------------------------------------------------------
+template <int MT, int W, bool SPLIT, class Epi>
+__global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
+                                                  const __bf16 *__restrict__ Xlo, int KT, int n_mtiles, Epi epi) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int pair = blockIdx.x;
-    const int mt0 = SPLITK ? blockIdx.y * MT : (blockIdx.y * W + wave) * MT;
-    int k0 = 0, k1 = KT;
-    if (SPLITK) {
-        k0 = (int)(((long)wave * KT) / W);
-        k1 = (int)(((long)(wave + 1) * KT) / W);
-    }
+    const int mt0 = (blockIdx.y * W + wave) * MT;
+    if (mt0 >= n_mtiles) return;
     f32x4 acc[MT][2];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -267,43 +391,28 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
     }
     const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
     const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
-    const bf16x8 *xp[MT];
+    const bf16x8 *xp[MT], *xq[MT];
     bool mv[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         mv[i] = (mt0 + i) < n_mtiles;
-        xp[i] = (const bf16x8 *)(Xp + spd_frag_index(mv[i] ? mt0 + i : 0, 0, KT)) + lane;
+        const size_t o = spd_frag_index(mv[i] ? mt0 + i : mt0, 0, KT);
+        xp[i] = (const bf16x8 *)(Xhi + o) + lane;
+        xq[i] = (const bf16x8 *)(Xlo + o) + lane;
     }
-    if (SPLITK || mv[0]) {
-#pragma unroll 4
-        for (int kt = k0; kt < k1; ++kt) {
-            const bf16x8 fa = wa[(size_t)kt * 64], fb = wb[(size_t)kt * 64];
-#pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                const bf16x8 fx = xp[i][(size_t)kt * 64];
-                acc[i][0] = MFMA(fa, fx, acc[i][0]);
-                acc[i][1] = MFMA(fb, fx, acc[i][1]);
-            }
-        }
-    }
-    if (SPLITK && W > 1) {
-        __shared__ f32x4 red[W][MT * 2][64];
+#pragma unroll 2
+    for (int kt = 0; kt < KT; ++kt) {
+        const bf16x8 fa = wa[(size_t)kt * 64], fb = wb[(size_t)kt * 64];
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
-            red[wave][2 * i][lane] = acc[i][0];
-            red[wave][2 * i + 1][lane] = acc[i][1];
-        }
-        __syncthreads();
-        if (wave != 0) return;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            f32x4 s0 = red[0][2 * i][lane], s1 = red[0][2 * i + 1][lane];
-            for (int w = 1; w < W; ++w) {
-                s0 += red[w][2 * i][lane];
-                s1 += red[w][2 * i + 1][lane];
+            const bf16x8 fx = xp[i][(size_t)kt * 64];
+            acc[i][0] = MFMA(fa, fx, acc[i][0]);
+            acc[i][1] = MFMA(fb, fx, acc[i][1]);
+            if (SPLIT) {
+                const bf16x8 fl = xq[i][(size_t)kt * 64];
+                acc[i][0] = MFMA(fa, fl, acc[i][0]);
+                acc[i][1] = MFMA(fb, fl, acc[i][1]);
             }
-            acc[i][0] = s0;
-            acc[i][1] = s1;
         }
     }
 #pragma unroll
@@ -322,20 +431,41 @@ struct AttnState {
     float m, l;     // running max (of scaled scores) and sum for col = lane%16
 };
 
+template <int DT>
+struct KVFrags {
+    bf16x8 k0[DT / 2], k1[DT / 2], v[DT];
+};
+
+// all fragments of one 32-key block: 2 x 16 keys x d for K, d x 32 keys for V
+template <int DT>
+__device__ __forceinline__ void load_kv(KVFrags<DT> &f, const __bf16 *__restrict__ kbase, const __bf16 *__restrict__ vbase,
+                                        int vb, int d, int lane) {
+    const bf16x8 *k0 = (const bf16x8 *)(kbase + (size_t)(2 * vb) * 16 * d) + lane;
+    const bf16x8 *k1 = (const bf16x8 *)(kbase + (size_t)(2 * vb + 1) * 16 * d) + lane;
+    const bf16x8 *vf = (const bf16x8 *)(vbase + (size_t)vb * 32 * d) + lane;
+#pragma unroll
+    for (int t = 0; t < DT / 2; ++t) {
+        f.k0[t] = k0[t * 64];
+        f.k1[t] = k1[t * 64];
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) f.v[dt] = vf[dt * 64];
+}
+
 // one 32-key block: keys [vb*32, vb*32+32) of one (sequence, KV head); n_keys_col = number of
 // keys column lane%16 may attend (causal), 0 for a padding column
 template <int DT>
-__device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__restrict__ qf, const __bf16 *__restrict__ kbase,
-                                           const __bf16 *__restrict__ vbase, int vb, int d, int n_keys_col, float scale,
-                                           int lane) {
+__device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__restrict__ qf, const KVFrags<DT> &f, int vb,
+                                           int n_keys_col, float scale, int lane) {
+    // qf[0 .. DT/2) are the hi halves of the query fragments, qf[DT/2 .. DT) the lo halves
     const int g = lane >> 4;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-    const bf16x8 *k0 = (const bf16x8 *)(kbase + (size_t)(2 * vb) * 16 * d) + lane;
-    const bf16x8 *k1 = (const bf16x8 *)(kbase + (size_t)(2 * vb + 1) * 16 * d) + lane;
 #pragma unroll
     for (int t = 0; t < DT / 2; ++t) {
-        s0 = MFMA(k0[t * 64], qf[t], s0);
-        s1 = MFMA(k1[t * 64], qf[t], s1);
+        s0 = MFMA(f.k0[t], qf[t], s0);
+        s1 = MFMA(f.k1[t], qf[t], s1);
+        s0 = MFMA(f.k0[t], qf[DT / 2 + t], s0);
+        s1 = MFMA(f.k1[t], qf[DT / 2 + t], s1);
     }
     const int key0 = vb * 32 + 4 * g;
     float mx = -INFINITY;
@@ -362,42 +492,47 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
     ps += shfl_xor_f(ps, 32);
     st.l = st.l * alpha + ps;
     st.m = m_new;
-    bf16x8 pb;
+    bf16x8 pb, pl;      // probabilities as hi + lo pairs
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         pb[i] = (__bf16)p0[i];
         pb[4 + i] = (__bf16)p1[i];
+        pl[i] = (__bf16)(p0[i] - (float)pb[i]);
+        pl[4 + i] = (__bf16)(p1[i] - (float)pb[4 + i]);
     }
-    const bf16x8 *vf = (const bf16x8 *)(vbase + (size_t)vb * 32 * d) + lane;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
         st.o[dt] *= alpha;
-        st.o[dt] = MFMA(vf[dt * 64], pb, st.o[dt]);
+        st.o[dt] = MFMA(f.v[dt], pb, st.o[dt]);
+        st.o[dt] = MFMA(f.v[dt], pl, st.o[dt]);
     }
 }
 
 // query fragments of one column tile: col -> (token t, head c); zero for padding columns
 template <int DT>
-__device__ __forceinline__ void load_q(bf16x8 *qf, const __bf16 *__restrict__ qbuf, int m, int head, int qd, int d,
-                                       bool valid, int lane) {
+__device__ __forceinline__ void load_q(bf16x8 *qf, const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, int m,
+                                       int head, int qd, int d, bool valid, int lane) {
     const int g = lane >> 4;
 #pragma unroll
     for (int t = 0; t < DT / 2; ++t) {
         if (valid) {
-            qf[t] = *(const bf16x8 *)(qbuf + (size_t)m * qd + head * d + t * 32 + g * 8);
+            const size_t o = (size_t)m * qd + head * d + t * 32 + g * 8;
+            qf[t] = *(const bf16x8 *)(qbuf + o);
+            qf[DT / 2 + t] = *(const bf16x8 *)(qlo + o);
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) qf[t][i] = (__bf16)0.f;
+            for (int i = 0; i < 8; ++i) qf[t][i] = qf[DT / 2 + t][i] = (__bf16)0.f;
         }
     }
 }
 
 // Decode (q_len = 1): grid (splits, kv heads, sequences), 4 waves.  The waves of a workgroup
-// take the 32-key blocks of their split round-robin; the workgroup writes one partial
-// (unnormalised O^T, running max, running sum) per split.
+// take the 32-key blocks of their split round-robin, the next block's fragments being loaded
+// while the current one is processed; the workgroup writes one partial (unnormalised O^T,
+// running max, running sum) per split.
 // partial layout: [seq][kvh][split][(d + 2) * 16] floats: O^T[d][16], m[16], l[16]
 template <int DT>
-__global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ kc,
+__global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
                                                      const __bf16 *__restrict__ vc, float *__restrict__ part, spd_positions P,
                                                      int q, int kv, int max_ctx, int n_splits) {
     constexpr int d = DT * 16;
@@ -410,8 +545,6 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
     const int b0 = (int)(((long)split * nblk) / n_splits), b1 = (int)(((long)(split + 1) * nblk) / n_splits);
     const int col = lane & 15, g = lane >> 4;
     const bool cvalid = col < group;
-    bf16x8 qf[DT / 2];
-    load_q<DT>(qf, qbuf, b, kvh * group + col, qd, d, cvalid, lane);
     const __bf16 *kbase = kc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
     const __bf16 *vbase = vc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
     AttnState<DT> st;
@@ -420,7 +553,20 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
     st.m = -INFINITY;
     st.l = 0.f;
     const float scale = 1.0f / sqrtf((float)d);
-    for (int vb = b0 + wave; vb < b1; vb += 4) attn_block<DT>(st, qf, kbase, vbase, vb, d, cvalid ? n_keys : 0, scale, lane);
+    int vb = b0 + wave;
+    if (vb < b1) {
+        KVFrags<DT> cur;
+        load_kv<DT>(cur, kbase, vbase, vb, d, lane);
+        bf16x8 qf[DT];
+        load_q<DT>(qf, qbuf, qlo, b, kvh * group + col, qd, d, cvalid, lane);
+        for (; vb < b1; vb += 4) {
+            KVFrags<DT> nxt;
+            const bool more = vb + 4 < b1;
+            if (more) load_kv<DT>(nxt, kbase, vbase, vb + 4, d, lane);
+            attn_block<DT>(st, qf, cur, vb, cvalid ? n_keys : 0, scale, lane);
+            if (more) cur = nxt;
+        }
+    }
     // merge the four waves
     float *my = sm[wave];
 #pragma unroll
@@ -455,35 +601,61 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
 }
 
 // merge the splits of one (sequence, KV head) and write the normalised output as packed
-// activations of the O projection: row = token, contraction index = head*d + dd
-__global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat, int q, int kv,
-                                                      int d, int n_splits) {
-    const int kvh = blockIdx.x, b = blockIdx.y;
+// activations of the O projection: row = token, contraction index = head*d + dd.
+// grid (kv heads, sequences, d/32): each workgroup produces 32 features of every head of the group.
+__global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat,
+                                                      __bf16 *__restrict__ alo, int q, int kv, int d, int n_splits) {
+    __shared__ float wgt[SPD_MAX_SPLITS][16];     // exp(m_s - M) per split and column
+    __shared__ float den[16];
+    const int kvh = blockIdx.x, b = blockIdx.y, dchunk = blockIdx.z;
     const int group = q / kv, qd = q * d;
     const size_t pstride = (size_t)(d + 2) * 16;
     const float *src = part + ((size_t)b * kv + kvh) * n_splits * pstride;
-    for (int e = threadIdx.x; e < group * d; e += 256) {
-        const int c = e / d, dd = e % d;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < n_splits * 16; e += 256) wgt[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + d * 16 + (e & 15)];
+    __syncthreads();
+    if (tid < 16) {
         float mm = -INFINITY;
-        for (int s = 0; s < n_splits; ++s) mm = fmaxf(mm, src[s * pstride + d * 16 + c]);
-        float num = 0.f, den = 0.f;
+        for (int s = 0; s < n_splits; ++s) mm = fmaxf(mm, wgt[s][tid]);
+        float dn = 0.f;
         for (int s = 0; s < n_splits; ++s) {
-            const float ms = src[s * pstride + d * 16 + c];
+            const float ms = wgt[s][tid];
             const float sc = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-            num += src[s * pstride + dd * 16 + c] * sc;
-            den += src[s * pstride + (d + 1) * 16 + c] * sc;
+            wgt[s][tid] = sc;
+            dn += src[(size_t)s * pstride + (d + 1) * 16 + tid] * sc;
         }
+        den[tid] = dn;
+    }
+    __syncthreads();
+    // 32 features x 16 columns per workgroup; thread -> (feature, column) pairs, columns fastest
+    for (int e = tid; e < 32 * 16; e += 256) {
+        const int c = e & 15, dd = dchunk * 32 + (e >> 4);
+        if (c >= group) continue;
+        float num = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += 8) {
+            float t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = (s0 + j < n_splits) ? src[(size_t)(s0 + j) * pstride + dd * 16 + c] : 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j < n_splits) num += t[j] * wgt[s0 + j][c];
+        }
+        const float val = num / den[c];
         const int kidx = (kvh * group + c) * d + dd;
-        ahat[spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31)] = (__bf16)(num / den);
+        const size_t o = spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31);
+        const __bf16 hi = (__bf16)val;
+        ahat[o] = hi;
+        if (alo) alo[o] = (__bf16)(val - (float)hi);
     }
 }
 
 // Prefill (q_len > 1): grid (column-tile groups, kv heads, sequences), 4 waves, each wave owns
 // CT column tiles of 16 (token, head) columns and walks the causal key range once.
 template <int DT, int CT>
-__global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ kc,
-                                                      const __bf16 *__restrict__ vc, __bf16 *__restrict__ ahat, spd_positions P,
-                                                      int q_len, int q, int kv, int max_ctx) {
+__global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
+                                                      const __bf16 *__restrict__ vc, __bf16 *__restrict__ ahat,
+                                                      __bf16 *__restrict__ alo, spd_positions P, int q_len, int q, int kv,
+                                                      int max_ctx) {
     constexpr int d = DT * 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kvh = blockIdx.y, b = blockIdx.z;
@@ -493,7 +665,7 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
     if (ct0 * 16 >= n_cols) return;
     const int g = lane >> 4;
     const int pos0 = P.pos[b];
-    bf16x8 qf[CT][DT / 2];
+    bf16x8 qf[CT][DT];
     AttnState<DT> st[CT];
     int nk[CT], mrow[CT], hd[CT];
     int last_key = 0;
@@ -505,7 +677,7 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
         hd[c] = kvh * group + col % group;
         mrow[c] = b * q_len + t;
         nk[c] = valid ? pos0 + t + 1 : 0;
-        load_q<DT>(qf[c], qbuf, mrow[c], hd[c], qd, d, valid, lane);
+        load_q<DT>(qf[c], qbuf, qlo, mrow[c], hd[c], qd, d, valid, lane);
 #pragma unroll
         for (int i = 0; i < DT; ++i) st[c].o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
         st[c].m = -INFINITY;
@@ -520,8 +692,10 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
     const float scale = 1.0f / sqrtf((float)d);
     const int nblk = (last_key + 31) >> 5;
     for (int vb = 0; vb < nblk; ++vb) {
+        KVFrags<DT> f;
+        load_kv<DT>(f, kbase, vbase, vb, d, lane);
 #pragma unroll
-        for (int c = 0; c < CT; ++c) attn_block<DT>(st[c], qf[c], kbase, vbase, vb, d, nk[c], scale, lane);
+        for (int c = 0; c < CT; ++c) attn_block<DT>(st[c], qf[c], f, vb, nk[c], scale, lane);
     }
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
@@ -531,24 +705,31 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const int kidx = hd[c] * d + dt * 16 + 4 * g;
-            const bf16x4 v = cvt4(st[c].o[dt][0] * inv, st[c].o[dt][1] * inv, st[c].o[dt][2] * inv, st[c].o[dt][3] * inv);
-            *(bf16x4 *)(ahat + spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31)) = v;
+            const float o0 = st[c].o[dt][0] * inv, o1 = st[c].o[dt][1] * inv, o2 = st[c].o[dt][2] * inv,
+                        o3 = st[c].o[dt][3] * inv;
+            const bf16x4 v = cvt4(o0, o1, o2, o3);
+            const size_t o = spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31);
+            *(bf16x4 *)(ahat + o) = v;
+            if (alo) *(bf16x4 *)(alo + o) = cvt4_lo(o0, o1, o2, o3, v);
         }
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// taps (tests only): packed bf16 -> natural fp32
+// taps (tests only): packed bf16 (hi [+ lo]) -> natural fp32
 // ------------------------------------------------------------------------------------------
-__global__ void k_unpack_act(const __bf16 *__restrict__ src, float *__restrict__ dst, int M, int K_packed, int K_out) {
+__global__ void k_unpack_act(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst, int M,
+                             int K_packed, int K_out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)M * K_out) return;
     const int m = (int)(i / K_out), k = (int)(i % K_out);
-    dst[i] = (float)src[spd_frag_index(m >> 4, k >> 5, K_packed >> 5) + spd_frag_elem(m & 15, k & 31)];
+    const size_t o = spd_frag_index(m >> 4, k >> 5, K_packed >> 5) + spd_frag_elem(m & 15, k & 31);
+    dst[i] = (float)src[o] + (lo ? (float)lo[o] : 0.f);
 }
-__global__ void k_bf16_to_f32(const __bf16 *__restrict__ src, float *__restrict__ dst, int64_t n) {
+__global__ void k_bf16_to_f32(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst,
+                              int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = (float)src[i];
+    if (i < n) dst[i] = (float)src[i] + (float)lo[i];
 }
 
 inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
@@ -559,17 +740,49 @@ inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b);
         if (e_ != hipSuccess) return e_; \
     } while (0)
 
+// Launch shape of a projection.  At most 16 tokens: the weight-streaming kernel; the number of
+// K slices is chosen so that about two workgroups per compute unit are in flight.
 template <class Epi>
-hipError_t launch_gemm(const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, int M, const Epi &epi, hipStream_t s) {
+hipError_t launch_proj(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
+                       const Epi &epi) {
+    const spd_dims &D = *c.D;
+    const int M = c.M;
     const int n_mtiles = (M + 15) / 16;
+    const __bf16 *Xlo = Xhi + plane;
     if (n_mtiles == 1) {
-        // skinny: one m-tile, the waves of a workgroup split K
-        constexpr int W = 8;
-        hipLaunchKernelGGL((k_gemm<1, W, true, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, s, Wp, Xp, KT, n_mtiles, epi);
+        float *kpart = (float *)(c.ws + D.ws_kpart);
+        unsigned int *counters = (unsigned int *)(c.ws + D.ws_counters);
+        if (n_pairs > SPD_N_COUNTERS) return hipErrorInvalidValue;
+        if (n_pairs >= 192 && KT >= 64) {
+            // enough pairs to occupy the chip: one workgroup of 16 waves per pair, no slices
+            constexpr int W = 16, U = 4;
+            if (c.split)
+                hipLaunchKernelGGL((k_gemv<W, U, true, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
+                                   kpart, counters, epi);
+            else
+                hipLaunchKernelGGL((k_gemv<W, U, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
+                                   kpart, counters, epi);
+        } else {
+            constexpr int W = 8, U = 4;
+            int KS = (512 + n_pairs - 1) / n_pairs;
+            const int ks_max = KT / W > 0 ? KT / W : 1;         // at least one k-tile per wave
+            if (KS > ks_max) KS = ks_max;
+            if (KS < 1) KS = 1;
+            while ((size_t)n_pairs * KS > (size_t)SPD_MAX_KPART && KS > 1) --KS;
+            if (c.split)
+                hipLaunchKernelGGL((k_gemv<W, U, true, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+                                   kpart, counters, epi);
+            else
+                hipLaunchKernelGGL((k_gemv<W, U, false, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+                                   kpart, counters, epi);
+        }
     } else {
         constexpr int MT = 4, W = 4;
-        hipLaunchKernelGGL((k_gemm<MT, W, false, Epi>), dim3(n_pairs, cdiv(n_mtiles, MT * W)), dim3(W * 64), 0, s, Wp, Xp,
-                           KT, n_mtiles, epi);
+        const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
+        if (c.split)
+            hipLaunchKernelGGL((k_gemm<MT, W, true, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
+        else
+            hipLaunchKernelGGL((k_gemm<MT, W, false, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
     }
     return hipGetLastError();
 }
@@ -587,11 +800,12 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     const spd_dims &D = *c.D;
     const int tpw = prep_tpw(c.M), nch = prep_nch(D.h, c.M);
     __bf16 *xhat = want_xhat ? (__bf16 *)(c.ws + (which ? D.ws_xhat2 : D.ws_xhat)) : nullptr;
+    __bf16 *xlo = (want_xhat && c.split) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base) out = nullptr;   // nothing to rewrite
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
     hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                       (size_t)c.M * D.h, out, gain, xhat, ss, c.M, D.h, tpw, D.m_pad);
+                       (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad);
     return hipGetLastError();
 }
 
@@ -600,6 +814,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     const int M = c.M, qd = D.q * D.d;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat);
     __bf16 *qbuf = (__bf16 *)(c.ws + D.ws_q), *ahat = (__bf16 *)(c.ws + D.ws_ahat);
+    __bf16 *alo = c.split ? ahat + D.pl_a : nullptr;
+    __bf16 *qlo = qbuf + D.pl_a;
     __bf16 *kc = (__bf16 *)kvc, *vc = (__bf16 *)(kvc + D.kv_v);
     float *ybuf = (float *)(c.ws + D.ws_y);
 
@@ -608,23 +824,24 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e1.nch = prep_nch(D.h, M); e1.m_pad = D.m_pad; e1.eps = D.eps;
     e1.ss = (const float *)(c.ws + D.ws_ss1);
     e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
-    e1.qbuf = qbuf; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
+    e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
     {
         spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_qkv), xhat, D.nqkv / 32, D.h / 32, M, e1, c.s));
+        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
     }
 
     const int DT = D.d / 16;
     spd_profile::begin(SPD_STAGE_ATTN, c.s);
     if (c.q_len == 1) {
+        // about 8 key blocks (256 keys) per workgroup, two per wave
         const int nblk = (c.max_pos_end + 31) / 32;
-        int splits = nblk / 4;
+        int splits = (nblk + 7) / 8;
         if (splits < 1) splits = 1;
         if (splits > SPD_MAX_SPLITS) splits = SPD_MAX_SPLITS;
         float *part = (float *)(c.ws + D.ws_apart);
         const dim3 grid(splits, D.kv, c.batch);
 #define SPD_DECODE(DTV)                                                                                          \
-    hipLaunchKernelGGL((k_attn_decode<DTV>), grid, dim3(256), 0, c.s, qbuf, kc, vc, part, c.pos, D.q, D.kv, D.max_ctx, \
+    hipLaunchKernelGGL((k_attn_decode<DTV>), grid, dim3(256), 0, c.s, qbuf, qlo, kc, vc, part, c.pos, D.q, D.kv, D.max_ctx, \
                        splits)
         switch (DT) {
             case 2: SPD_DECODE(2); break;
@@ -635,15 +852,16 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         }
 #undef SPD_DECODE
         SPD_TRY(hipGetLastError());
-        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch), dim3(256), 0, c.s, part, ahat, D.q, D.kv, D.d, splits);
+        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch, D.d / 32), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
+                           D.d, splits);
         SPD_TRY(hipGetLastError());
     } else {
         constexpr int CT = 2;
         const int n_ct = (c.q_len * D.group + 15) / 16;
         const dim3 grid(cdiv(n_ct, 4 * CT), D.kv, c.batch);
 #define SPD_PREFILL(DTV)                                                                                              \
-    hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), 0, c.s, qbuf, kc, vc, ahat, c.pos, c.q_len, D.q, D.kv, \
-                       D.max_ctx)
+    hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), 0, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, D.q, \
+                       D.kv, D.max_ctx)
         switch (DT) {
             case 2: SPD_PREFILL(2); break;
             case 4: SPD_PREFILL(4); break;
@@ -661,19 +879,21 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
     e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
     e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
+    e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
     {
         spd_profile::scope prof(SPD_STAGE_O, c.s);
-        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_o), ahat, D.h / 32, qd / 32, M, e2, c.s));
+        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_o), ahat, D.pl_a, D.h / 32, qd / 32, e2));
     }
 
     if (c.taps) {
         if (c.taps->q) {
-            hipLaunchKernelGGL(k_bf16_to_f32, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, qbuf, c.taps->q,
+            hipLaunchKernelGGL(k_bf16_to_f32, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, qbuf, qlo, c.taps->q,
                                (int64_t)M * qd);
             SPD_TRY(hipGetLastError());
         }
         if (c.taps->attn) {
-            hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, c.taps->attn, M, qd, qd);
+            hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, alo, c.taps->attn, M,
+                               qd, qd);
             SPD_TRY(hipGetLastError());
         }
         if (c.taps->y) SPD_TRY(spd_common::copy2d(spd ? ybuf : slot, D.h, c.taps->y, D.h, M, D.h, c.s));
@@ -681,19 +901,23 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     return hipSuccess;
 }
 
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, int nch2) {
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot) {
     const spd_dims &D = *c.D;
     const int M = c.M;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat2);
     __bf16 *uhat = (__bf16 *)(c.ws + D.ws_uhat);
+    __bf16 *ulo = c.split ? uhat + D.pl_u : nullptr;
 
     EpiGU e1;
-    e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.nch = nch2; e1.m_pad = D.m_pad; e1.eps = D.eps;
+    e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.m_pad = D.m_pad; e1.eps = D.eps;
+    // SPD block: the O-projection epilogue wrote one partial per pair of n-tiles (h/32 of them);
+    // TP block: prep() wrote them after the kept sync point
+    e1.nch = spd ? D.h / 32 : prep_nch(D.h, M);
     e1.ss = (const float *)(c.ws + D.ws_ss2);
-    e1.uhat = uhat;
+    e1.uhat = uhat; e1.ulo = ulo;
     {
         spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
-        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, M, e1, c.s));
+        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
     }
 
     EpiDown e2;
@@ -701,21 +925,15 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, int 
     e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
     {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
-        SPD_TRY(launch_gemm((const __bf16 *)(w + D.w_d), uhat, D.h / 32, D.f_pad / 32, M, e2, c.s));
+        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
     }
 
     if (c.taps && c.taps->u) {
-        hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, c.taps->u, M, D.f_pad, D.f);
+        hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, ulo, c.taps->u, M,
+                           D.f_pad, D.f);
         SPD_TRY(hipGetLastError());
     }
     return hipSuccess;
-}
-
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot) {
-    // SPD block: the O-projection epilogue wrote one partial per pair of n-tiles (h/32 of them);
-    // TP block: prep() wrote them after the kept sync point
-    const int nch2 = spd ? c.D->h / 32 : prep_nch(c.D->h, c.M);
-    return mlp_half(c, w, spd, slot, nch2);
 }
 
 }  // namespace spd_bf16

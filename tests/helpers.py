@@ -17,6 +17,11 @@ def oracle_shapes(w: Workload) -> O.Shapes:
     return O.Shapes(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, w.tp, w.rms_eps, w.rope_base)
 
 
+def cache_storage(w: Workload) -> str:
+    """The KV cache of a bf16 workload holds bf16 values; the fp32 toy's holds what it is given."""
+    return "bf16" if w.dtype == BF16 else "f64"
+
+
 def tolerance(w: Workload) -> dict:
     """bf16 path: max abs error 2e-2 on fp32-stored outputs; fp32 path: 1e-3 relative to the
     largest oracle magnitude."""
@@ -40,7 +45,7 @@ class Case:
 
     def __init__(self, w: Workload, device, ranks: Sequence[int], positions: Sequence[int],
                  layer_ids: Optional[Sequence[int]] = None, max_ctx: Optional[int] = None,
-                 max_tokens: Optional[int] = None, prefill_layers: bool = True):
+                 max_tokens: Optional[int] = None, prefill_layers: bool = True, act_split: int = 0):
         import torch
         self.torch = torch
         self.w = w
@@ -50,7 +55,7 @@ class Case:
         self.layer_ids = list(layer_ids) if layer_ids is not None else list(range(w.n_layers))
         assert len(self.layer_ids) == w.n_layers
         self.dev = B.DeviceShard(w, self.ranks, device, max_ctx=max_ctx, max_tokens=max_tokens,
-                                 max_batch=len(self.positions))
+                                 max_batch=len(self.positions), act_split=act_split)
         mc = self.dev.cfg.max_ctx
         self.shards: List[List[dict]] = []
         self.caches: List[List[O.KVCache]] = []
@@ -62,7 +67,7 @@ class Case:
             self.dev.load_layer(li, sh)
             caches, kvs = [], []
             for r in self.ranks:
-                c = O.KVCache(batch, w.kv_per_rank, mc, w.head_dim)
+                c = O.KVCache(batch, w.kv_per_rank, mc, w.head_dim, storage=cache_storage(w))
                 if n_pre > 0 and prefill_layers:
                     k, v = inputs.kv_prefill(w, layer, r, batch, n_pre)
                     # every sequence only keeps its own prefix; the rest stays zero on both sides

@@ -9,7 +9,7 @@ from paper_2502_20727_amd import binding as B
 from paper_2502_20727_amd import inputs, workloads
 from paper_2502_20727_amd.workloads import BF16, F32, Workload
 
-from helpers import Case, assert_close, oracle_shapes
+from helpers import Case, assert_close, cache_storage, oracle_shapes
 
 pytestmark = pytest.mark.gpu
 
@@ -155,7 +155,7 @@ def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
     want, _ = O.block_all_ranks(case.sh, X, case.shards[0], case.caches[0], positions, batch, q_len, flag, det)
     r = w.tp - 1
     d2 = {}
-    c2 = O.KVCache(batch, w.kv_per_rank, 64, w.head_dim)
+    c2 = O.KVCache(batch, w.kv_per_rank, 64, w.head_dim, storage=cache_storage(w))
     c2.k[...] = 0
     # the last rank's intermediates: recompute them with a cache holding the same prefill
     if max(positions) > 0:
@@ -176,8 +176,9 @@ def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
         k, v = case.dev.read_kv(0, i, batch, n_pos)
         for b, p in enumerate(positions):
             ko, vo = case.caches[0][i].k[b, :, p:p + q_len], case.caches[0][i].v[b, :, p:p + q_len]
-            assert np.max(np.abs(k[b, :, p:p + q_len] - ko)) <= 2.0 ** -8 * np.max(np.abs(ko)) + 1e-3
-            assert np.max(np.abs(v[b, :, p:p + q_len] - vo)) <= 2.0 ** -8 * np.max(np.abs(vo)) + 1e-3
+            # both sides hold bf16 values; a last-bit disagreement is one ulp (2^-7 relative at most)
+            assert np.max(np.abs(k[b, :, p:p + q_len] - ko)) <= 2.0 ** -7 * np.max(np.abs(ko)) + 1e-3
+            assert np.max(np.abs(v[b, :, p:p + q_len] - vo)) <= 2.0 ** -7 * np.max(np.abs(vo)) + 1e-3
     case.close()
 
 
@@ -354,34 +355,44 @@ def test_full_size_decode_shapes(gpu, name):
     case.close()
 
 
-def test_full_size_prefill_shape_sampled_rows(gpu):
-    """LLaMA2-70B shard, 4 x 2048 tokens: the oracle computes sampled output rows one by one."""
+@pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
+@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
+def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
+    """LLaMA2-70B shard, 4 x 2048 tokens: the oracle computes sampled output rows one by one.
+
+    With split activations the 2e-2 bound holds as it stands.  The default single-pass bf16
+    contraction rounds every activation that feeds a projection to 8 significant bits; with up
+    to 8192 terms per output and outputs that reach |v| ~ 15 (rms ~ 2.9) that rounding alone
+    exceeds 2e-2, so the single-pass bound adds one bf16 unit in the last place at the largest
+    output magnitude: 2e-2 + ulp_bf16(max |oracle|)."""
     import torch
     full = workloads.LLAMA70B_PREFILL
-    w = full.with_layers(1)
+    w = full.with_layers(1).with_mask((flag,))
     M = full.batch * full.q_len
     rows = np.array([0, 1, 15, 16, 17, 255, 256, 2047, 2048, 2049, 3000, 4095, 4096, 5555, 6143, 6144, 8000, 8191])
     X = inputs.hidden_states(w, M)
     peers = inputs.peer_slots(w, M)
-    for flag in (1, 0):
-        say(f"full-size prefill flag={flag}")
-        case = Case(w.with_mask((flag,)), gpu, ranks=[0], positions=[0] * full.batch)
-        x = case.to_dev(X)
-        slots = case.to_dev(peers)
-        out = torch.empty_like(x)
-        B.spd_block_forward(case.dev.ctx, 0, flag, 0, case.dev.weights[0], case.dev.kv[0], [0] * full.batch,
-                            full.batch, full.q_len, x, slots, out, case.dev.workspace)
-        torch.cuda.synchronize()
-        got = out[torch.from_numpy(rows).to(gpu)].cpu().numpy()
-        got_slot = slots[0][torch.from_numpy(rows).to(gpu)].cpu().numpy()
-        del x, out
-        want = O.block_single_rank(case.sh, X, case.shards[0][0], case.caches[0][0], [0] * full.batch, full.batch,
-                                   full.q_len, flag, 0, peers, rows=rows)
-        err = assert_close(got, want, w, f"prefill rows flag={flag}")
-        say(f"  sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
-        # properties that hold at any size: peers' slots untouched; finite everywhere
-        assert np.array_equal(slots[5][:64].cpu().numpy(), peers[5][:64])
-        assert bool(torch.isfinite(slots[0]).all())
-        del slots
-        case.close()
-        torch.cuda.empty_cache()
+    say(f"full-size prefill flag={flag} split={split}")
+    case = Case(w, gpu, ranks=[0], positions=[0] * full.batch, act_split=split)
+    x = case.to_dev(X)
+    slots = case.to_dev(peers)
+    out = torch.empty_like(x)
+    B.spd_block_forward(case.dev.ctx, 0, flag, 0, case.dev.weights[0], case.dev.kv[0], [0] * full.batch,
+                        full.batch, full.q_len, x, slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    got = out[torch.from_numpy(rows).to(gpu)].cpu().numpy()
+    del x, out
+    want = O.block_single_rank(case.sh, X, case.shards[0][0], case.caches[0][0], [0] * full.batch, full.batch,
+                               full.q_len, flag, 0, peers, rows=rows)
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    ulp = 2.0 ** (np.floor(np.log2(np.max(np.abs(want)))) - 7)
+    scale = 1.0 if split == B.SPD_SPLIT_ALWAYS else (2e-2 + ulp) / 2e-2
+    say("  per-row max err:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, np.max(np.abs(got - want), axis=1))))
+    err = assert_close(got, want, w, f"prefill rows flag={flag} split={split}", scale=scale)
+    say(f"  sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}, rms {rms:.2f}")
+    # properties that hold at any size: peers' slots untouched; finite everywhere
+    assert np.array_equal(slots[5][:64].cpu().numpy(), peers[5][:64])
+    assert bool(torch.isfinite(slots[0]).all())
+    del slots
+    case.close()
+    torch.cuda.empty_cache()

@@ -424,3 +424,25 @@ def test_row_subset_matches_full_run():
         rows = np.array([1, 6, 7])
         part = O.block_single_rank(sh, X, shards[2], fresh_caches(sh, 2, 8)[0], [0, 1], 2, 4, flag, 2, peers.copy(), rows=rows)
         np.testing.assert_allclose(part, full[rows], rtol=1e-12, atol=1e-13)
+
+
+def test_bf16_cache_storage_rounds_once_at_the_store():
+    # nearest-even rounding to 8 significant bits, pinned on values with known neighbours
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, -0.3, 3.0e38, 2.0 ** -130])
+    r = O.round_to_bf16(x)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2.0 ** -7      # tie goes to the even mantissa
+    assert r[3] == 1.0 + 2.0 ** -6                                       # tie, odd below: rounds up to even
+    assert abs(r[4] + 0.3) <= 2.0 ** -10                                 # half an ulp of the binade [0.25, 0.5)
+    assert np.float32(r[4]).view(np.uint32) & 0xFFFF == 0
+    assert np.isfinite(r[5]) and r[6] == 2.0 ** -130
+    sh = SHAPES[0]
+    rng = np.random.default_rng(30)
+    shards = make_shards(rng, sh)
+    X = rng.standard_normal((3, sh.hidden))
+    exact = O.KVCache(1, sh.kv, 4, sh.head_dim)
+    stored = O.KVCache(1, sh.kv, 4, sh.head_dim, storage="bf16")
+    ya = O.attention_partial(sh, X, shards[0], exact, [0], 1, 3)
+    yb = O.attention_partial(sh, X, shards[0], stored, [0], 1, 3)
+    np.testing.assert_array_equal(stored.k[:, :, :3], O.round_to_bf16(exact.k[:, :, :3]))
+    np.testing.assert_array_equal(stored.v[:, :, :3], O.round_to_bf16(exact.v[:, :, :3]))
+    assert 0 < np.max(np.abs(ya - yb)) < 0.05 * np.max(np.abs(ya))       # a small, real difference
