@@ -31,8 +31,9 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->ws = (char *)workspace;
     c->taps = nullptr;
     c->max_pos_end = 0;
-    c->split = D.dtype == SPD_BF16 && (ctx->cfg.act_split == SPD_SPLIT_ALWAYS ||
-                                       (ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= 16));
+    c->split_all = D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_ALWAYS;
+    c->split = c->split_all || (D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= 16);
+    c->nch1 = 0;
     std::memset(&c->pos, 0, sizeof(c->pos));
     for (int b = 0; b < batch; ++b) {
         if (positions[b] < 0 || (int64_t)positions[b] + q_len > D.max_ctx) return SPD_EINVAL;
@@ -46,8 +47,12 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
 // slots hold the partial sums of the final sync point and *base_out is what they are added
 // to: X for an SPD block ("X is added after the sync operation"), R = X + sum Y for a TP
 // block.  *syncs is incremented by the number of kept attention sync points (0 or 1).
+// With end_sync_out (one rank, bf16 path, at most 16 tokens) the last kernel of the block also
+// performs that final rank-sum into x_out (and the next block's first-norm preparation when
+// next_g1 is given); *end_done tells the caller whether it did.
 int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const char *weights, char *kv,
-               const float *x, float *slots, const float **base_out, int64_t *syncs) {
+               const float *x, float *slots, const float **base_out, int64_t *syncs, float *x_out,
+               const float *next_g1, bool *end_done) {
     const spd_dims &D = ctx->D;
     const size_t slot_n = (size_t)c.M * D.h;
     float *ybuf = (float *)(c.ws + D.ws_y), *rbuf = (float *)(c.ws + D.ws_r);
@@ -56,11 +61,16 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
     auto wr = [&](int r) { return weights + (all ? (size_t)r * D.weight_bytes : 0); };
     auto kr = [&](int r) { return kv + (all ? (size_t)r * D.kv_bytes : 0); };
 
+    *end_done = false;
     if (D.dtype == SPD_BF16) {
+        spd_bf16::spd_end_sync es;
+        es.slots = slots; es.tp = D.tp; es.rank = r0; es.x_out = x_out; es.next_g1 = next_g1;
+        const spd_bf16::spd_end_sync *fuse = (!all && x_out) ? &es : nullptr;
         if (spd) {
+            es.base = x;
             for (int r = r0; r < r1; ++r) {
                 SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 1, slots + r * slot_n));
-                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 1, slots + r * slot_n));
+                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 1, slots + r * slot_n, fuse, end_done));
             }
             *base_out = x;
         } else {
@@ -68,7 +78,8 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
             // kept sync point: R = X + sum_r Y_r, fused with the second norm's elementwise part
             SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1));
             *syncs += 1;
-            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n));
+            es.base = rbuf;
+            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n, fuse, end_done));
             *base_out = rbuf;
         }
         return SPD_OK;
@@ -128,13 +139,18 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
     const spd_dims &D = ctx->D;
     c.taps = taps;
     const char *w = (const char *)packed_weights;
-    if (D.dtype == SPD_BF16) SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)(w + D.w_g1), true, 0));
+    if (D.dtype == SPD_BF16) {
+        SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)(w + D.w_g1), true, 0));
+        c.nch1 = spd_bf16::prep_chunks(c);
+    }
     const float *base = nullptr;
     int64_t syncs = 0;
-    const int rc2 = block_core(ctx, c, spd_flag, rank, w, (char *)kv_cache, x_in, slots, &base, &syncs);
+    bool end_done = false;
+    const int rc2 = block_core(ctx, c, spd_flag, rank, w, (char *)kv_cache, x_in, slots, &base, &syncs, x_out, nullptr,
+                               &end_done);
     if (rc2 != SPD_OK) return rc2;
     // the sync point that ends every block, SPD or not
-    SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
+    if (!end_done) SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
     return SPD_OK;
 }
 
@@ -156,19 +172,25 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
     const bool bf = D.dtype == SPD_BF16;
     int64_t syncs = 0;
     const float *x = x_in;
-    if (bf)
+    if (bf) {
         SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)((const char *)layer_weights[0] + D.w_g1),
                                true, 0));
+        c.nch1 = spd_bf16::prep_chunks(c);
+    }
     for (int l = 0; l < L; ++l) {
         const float *base = nullptr;
+        const bool more = l + 1 < L;
+        const float *g1 = (bf && more) ? (const float *)((const char *)layer_weights[l + 1] + D.w_g1) : nullptr;
+        bool end_done = false;
         const int rc2 = block_core(ctx, c, spd_mask[l], rank, (const char *)layer_weights[l], (char *)layer_kv[l], x,
-                                   slots, &base, &syncs);
+                                   slots, &base, &syncs, x_out, g1, &end_done);
         if (rc2 != SPD_OK) return rc2;
         // end-of-block sync point; in the bf16 path it also prepares the next block's first norm
-        if (bf) {
-            const bool more = l + 1 < L;
-            const float *g1 = more ? (const float *)((const char *)layer_weights[l + 1] + D.w_g1) : nullptr;
+        if (end_done) {
+            c.nch1 = D.h / 32;                   // the fused epilogue left one partial per pair of n-tiles
+        } else if (bf) {
             SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0));
+            c.nch1 = spd_bf16::prep_chunks(c);
         } else {
             SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
         }

@@ -105,7 +105,9 @@ struct spd_call {
     int batch, q_len, M;
     spd_positions pos;
     int max_pos_end;          // max over sequences of positions[b] + q_len
-    bool split;               // bf16 path: activations carried as hi + lo pairs
+    bool split;               // bf16 path: the MLP's input activations are carried as hi + lo pairs
+    bool split_all;           // ... and so are the attention half's (only when the configuration asks for it)
+    int nch1;                 // number of sum-of-squares partials per token waiting in ss1
     char *ws;                 // workspace
     const spd_taps *taps;
 };
@@ -144,6 +146,19 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
 //   spd = 1: ybuf <- Y_r, xhat2 <- bf16((X + Y_r) g2) and its partial sums of squares
 //   spd = 0: slot <- Y_r
 hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot);
-// gate/up + SwiGLU + down.  spd = 1: slot <- ybuf + Z_r; spd = 0: slot <- Z_r
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot);
+// The sync point that ends a block, for one rank whose peers' partial sums are already in
+// `slots`: x_out = base + (slot_0 + ... + slot_tp-1), optionally followed by the elementwise
+// part of the next block's first norm (gain next_g1, may be NULL).
+struct spd_end_sync {
+    const float *base;        // X (SPD block) or R (TP block)
+    const float *slots;       // [tp][M*h]
+    int tp, rank;
+    float *x_out;
+    const float *next_g1;
+};
+// gate/up + SwiGLU + down.  spd = 1: slot <- ybuf + Z_r; spd = 0: slot <- Z_r.  With `fuse`
+// (calls of at most 16 tokens) the down projection's epilogue also performs the end-of-block
+// sync point; returns through *fused whether it did.
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused);
+int prep_chunks(const spd_call &c);
 }

@@ -32,12 +32,25 @@ __device__ __forceinline__ bf16x4 cvt4_lo(float a, float b, float c, float d, bf
 }
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
+// sum of ss[c][m] over c = start, start + stride, ... < nch, in that order; the loads are issued
+// eight at a time so that their latencies overlap
+__device__ __forceinline__ float sum_ss(const float *__restrict__ ss, int nch, int m_pad, int m, int start, int stride) {
+    float s = 0.f;
+    for (int c0 = start; c0 < nch; c0 += 8 * stride) {
+        float t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = (c0 + j * stride < nch) ? ss[(size_t)(c0 + j * stride) * m_pad + m] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += t[j];
+    }
+    return s;
+}
+
 // 1 / sqrt(mean(x^2) + eps) of row m from `nch` partial sums of squares ss[c][m]; the four
 // lanes that share a token each add a quarter of the partials (fixed order).
 __device__ __forceinline__ float row_rsqrt(const float *__restrict__ ss, int nch, int m_pad, int m, int g, int h,
                                            float eps) {
-    float s = 0.f;
-    for (int c = g; c < nch; c += 4) s += ss[(size_t)c * m_pad + m];
+    float s = sum_ss(ss, nch, m_pad, m, g, 4);
     s += shfl_xor_f(s, 16);
     s += shfl_xor_f(s, 32);
     return 1.0f / sqrtf(s / (float)h + eps);
@@ -132,18 +145,40 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 // Epilogues.  Each receives the accumulators of one (pair of n-tiles, m-tile): a = tile
 // 2*pair, b = tile 2*pair+1; lane l: token m = mt*16 + l%16, features 4*(l/16) + i.
 // ------------------------------------------------------------------------------------------
+// Every epilogue has two parts: pre() issues the loads that do not depend on the accumulators
+// (so that they can be started before the weights are streamed), operator() finishes the tile.
+// kNeedsRs: the tile must be scaled by 1/sqrt(mean(x^2)+eps) of the token, which the caller
+// computes from the partial sums of squares ss[nch][m_pad].
 struct EpiQKV {
+    static constexpr bool kNeedsRs = true;
     int M, q_len, q, kv, d, h, max_ctx, nch, m_pad;
     float eps;
     const float *ss, *cosT, *sinT;
     __bf16 *qbuf, *qlo, *kc, *vc;     // queries are kept as hi + lo pairs
     spd_positions P;
+    struct Pre {
+        float4 c, s;
+    };
 
-    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
+    __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
+        Pre p;
+        p.c = p.s = make_float4(0.f, 0.f, 0.f, 0.f);
         const int m = mt * 16 + (lane & 15), g = lane >> 4;
-        const float rs = row_rsqrt(ss, nch, m_pad, m, g, h, eps);
-        if (m >= M) return;
         const int tph = d >> 4, half = d >> 1;
+        const int head = (2 * pair) / tph;
+        if (m < M && head < q + kv) {
+            const int pos = P.pos[m / q_len] + (m % q_len);
+            const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;
+            p.c = *(const float4 *)(cosT + (size_t)pos * half + ca);
+            p.s = *(const float4 *)(sinT + (size_t)pos * half + ca);
+        }
+        return p;
+    }
+
+    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
+        const int m = mt * 16 + (lane & 15), g = lane >> 4;
+        if (m >= M) return;
+        const int tph = d >> 4;
         const int head = (2 * pair) / tph;
         const int bseq = m / q_len, pos = P.pos[bseq] + (m % q_len);
         const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;       // column inside the head
@@ -152,8 +187,7 @@ struct EpiQKV {
         b *= rs;
         if (head < q + kv) {
             // rotary partners: a holds j = ca .. ca+3 (< d/2), b holds j + d/2
-            const float4 c = *(const float4 *)(cosT + (size_t)pos * half + ca);
-            const float4 s = *(const float4 *)(sinT + (size_t)pos * half + ca);
+            const float4 c = p.c, s = p.s;
             const float l0 = a[0] * c.x - b[0] * s.x, l1 = a[1] * c.y - b[1] * s.y, l2 = a[2] * c.z - b[2] * s.z,
                         l3 = a[3] * c.w - b[3] * s.w;
             const float h0 = b[0] * c.x + a[0] * s.x, h1 = b[1] * c.y + a[1] * s.y, h2 = b[2] * c.z + a[2] * s.z,
@@ -182,12 +216,31 @@ struct EpiQKV {
 };
 
 struct EpiO {
+    static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
     float *ybuf, *slot, *ss2;
     __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
+    struct Pre {
+        float4 x0, x1, ga, gb;
+    };
 
-    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
+    __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
+        Pre p;
+        p.x0 = p.x1 = p.ga = p.gb = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int m = mt * 16 + (lane & 15), g = lane >> 4;
+        const int na = pair * 32 + 4 * g, nb = na + 16;
+        if (spd && m < M) {
+            const size_t o = (size_t)m * h;
+            p.x0 = *(const float4 *)(x + o + na);
+            p.x1 = *(const float4 *)(x + o + nb);
+            p.ga = *(const float4 *)(g2 + na);
+            p.gb = *(const float4 *)(g2 + nb);
+        }
+        return p;
+    }
+
+    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float, const Pre &p) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const int na = pair * 32 + 4 * g, nb = na + 16;
         const bool valid = m < M;
@@ -204,12 +257,10 @@ struct EpiO {
             const size_t o = (size_t)m * h;
             *(float4 *)(ybuf + o + na) = make_float4(a[0], a[1], a[2], a[3]);
             *(float4 *)(ybuf + o + nb) = make_float4(b[0], b[1], b[2], b[3]);
-            const float4 x0 = *(const float4 *)(x + o + na), x1 = *(const float4 *)(x + o + nb);
-            ra[0] = x0.x + a[0]; ra[1] = x0.y + a[1]; ra[2] = x0.z + a[2]; ra[3] = x0.w + a[3];
-            rb[0] = x1.x + b[0]; rb[1] = x1.y + b[1]; rb[2] = x1.z + b[2]; rb[3] = x1.w + b[3];
-            const float4 ga = *(const float4 *)(g2 + na), gb = *(const float4 *)(g2 + nb);
-            pa[0] = ra[0] * ga.x; pa[1] = ra[1] * ga.y; pa[2] = ra[2] * ga.z; pa[3] = ra[3] * ga.w;
-            pb[0] = rb[0] * gb.x; pb[1] = rb[1] * gb.y; pb[2] = rb[2] * gb.z; pb[3] = rb[3] * gb.w;
+            ra[0] = p.x0.x + a[0]; ra[1] = p.x0.y + a[1]; ra[2] = p.x0.z + a[2]; ra[3] = p.x0.w + a[3];
+            rb[0] = p.x1.x + b[0]; rb[1] = p.x1.y + b[1]; rb[2] = p.x1.z + b[2]; rb[3] = p.x1.w + b[3];
+            pa[0] = ra[0] * p.ga.x; pa[1] = ra[1] * p.ga.y; pa[2] = ra[2] * p.ga.z; pa[3] = ra[3] * p.ga.w;
+            pb[0] = rb[0] * p.gb.x; pb[1] = rb[1] * p.gb.y; pb[2] = rb[2] * p.gb.z; pb[3] = rb[3] * p.gb.w;
         }
         const bf16x4 xa = cvt4(pa[0], pa[1], pa[2], pa[3]), xb = cvt4(pb[0], pb[1], pb[2], pb[3]);
         // the pair's 32 features are k-tile `pair` of the next contraction
@@ -231,14 +282,17 @@ struct EpiO {
 };
 
 struct EpiGU {
+    static constexpr bool kNeedsRs = true;
     int M, h, f_pad, nch, m_pad;
     float eps;
     const float *ss;
     __bf16 *uhat, *ulo;        // ulo may be NULL
+    struct Pre {};
 
-    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
+    __device__ __forceinline__ Pre pre(int, int, int) const { return Pre(); }
+
+    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
-        const float rs = row_rsqrt(ss, nch, m_pad, m, g, h, eps);
         float o[4] = {0.f, 0.f, 0.f, 0.f};
         if (m < M) {
 #pragma unroll
@@ -256,21 +310,93 @@ struct EpiGU {
 };
 
 struct EpiDown {
+    static constexpr bool kNeedsRs = false;
     int M, h, spd;
     const float *ybuf;
     float *slot;
+    // optional: the sync point that ends the block, fused (one rank; the peers' partial sums are
+    // inputs).  base == NULL: not fused.
+    const float *base, *slots, *g1;
+    size_t slot_stride;
+    int tp, rank, m_pad;
+    float *x_out, *ss1;
+    __bf16 *xhat, *xlo;        // next block's first-norm activations (xhat NULL: last block)
+    struct Pre {
+        float4 ya, yb;
+    };
 
-    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane) const {
+    __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
+        Pre p;
+        p.ya = p.yb = make_float4(0.f, 0.f, 0.f, 0.f);
         const int m = mt * 16 + (lane & 15), g = lane >> 4;
-        if (m >= M) return;
-        const size_t oa = (size_t)m * h + pair * 32 + 4 * g, ob = oa + 16;
-        if (spd) {   // Y_r joins the partial sum before the sync point (Sec. 4.1.1)
-            const float4 ya = *(const float4 *)(ybuf + oa), yb = *(const float4 *)(ybuf + ob);
-            a[0] += ya.x; a[1] += ya.y; a[2] += ya.z; a[3] += ya.w;
-            b[0] += yb.x; b[1] += yb.y; b[2] += yb.z; b[3] += yb.w;
+        if (spd && m < M) {
+            const size_t oa = (size_t)m * h + pair * 32 + 4 * g;
+            p.ya = *(const float4 *)(ybuf + oa);
+            p.yb = *(const float4 *)(ybuf + oa + 16);
         }
-        *(float4 *)(slot + oa) = make_float4(a[0], a[1], a[2], a[3]);
-        *(float4 *)(slot + ob) = make_float4(b[0], b[1], b[2], b[3]);
+        return p;
+    }
+
+    // out = base + (slot_0 + slot_1 + ...), own partial standing in for slot `rank`: the same
+    // order of additions as the stand-alone rank-sum
+    __device__ __forceinline__ float4 sync_sum(size_t o, float4 own) const {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < tp; s0 += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j < tp && s0 + j != rank) t[j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + o);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (s0 + j >= tp) continue;
+                const float4 v = (s0 + j == rank) ? own : t[j];
+                if (s0 + j == 0) acc = v;
+                else { acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; }
+            }
+        }
+        const float4 bs = *(const float4 *)(base + o);
+        return make_float4(bs.x + acc.x, bs.y + acc.y, bs.z + acc.z, bs.w + acc.w);
+    }
+
+    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float, const Pre &p) const {
+        const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
+        const bool valid = m < M;
+        const size_t oa = (size_t)m * h + pair * 32 + 4 * g, ob = oa + 16;
+        // SPD block: Y_r joins the partial sum before the sync point (Sec. 4.1.1); p.y* are zero otherwise
+        const float4 pa = make_float4(a[0] + p.ya.x, a[1] + p.ya.y, a[2] + p.ya.z, a[3] + p.ya.w);
+        const float4 pb = make_float4(b[0] + p.yb.x, b[1] + p.yb.y, b[2] + p.yb.z, b[3] + p.yb.w);
+        if (valid) {
+            *(float4 *)(slot + oa) = pa;
+            *(float4 *)(slot + ob) = pb;
+        }
+        if (!base) return;
+        float4 xa = make_float4(0.f, 0.f, 0.f, 0.f), xb = xa;
+        if (valid) {
+            xa = sync_sum(oa, pa);
+            xb = sync_sum(ob, pb);
+            *(float4 *)(x_out + oa) = xa;
+            *(float4 *)(x_out + ob) = xb;
+        }
+        if (!xhat) return;
+        float qa[4] = {0.f, 0.f, 0.f, 0.f}, qb[4] = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+            const float4 ga = *(const float4 *)(g1 + pair * 32 + 4 * g), gb = *(const float4 *)(g1 + pair * 32 + 16 + 4 * g);
+            qa[0] = xa.x * ga.x; qa[1] = xa.y * ga.y; qa[2] = xa.z * ga.z; qa[3] = xa.w * ga.w;
+            qb[0] = xb.x * gb.x; qb[1] = xb.y * gb.y; qb[2] = xb.z * gb.z; qb[3] = xb.w * gb.w;
+        }
+        const bf16x4 ha = cvt4(qa[0], qa[1], qa[2], qa[3]), hb = cvt4(qb[0], qb[1], qb[2], qb[3]);
+        const size_t fo = spd_frag_index(mt, pair, h >> 5);
+        const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
+        *(bf16x4 *)(xhat + fo + ea) = ha;
+        *(bf16x4 *)(xhat + fo + eb) = hb;
+        if (xlo) {
+            *(bf16x4 *)(xlo + fo + ea) = cvt4_lo(qa[0], qa[1], qa[2], qa[3], ha);
+            *(bf16x4 *)(xlo + fo + eb) = cvt4_lo(qb[0], qb[1], qb[2], qb[3], hb);
+        }
+        float sq = xa.x * xa.x + xa.y * xa.y + xa.z * xa.z + xa.w * xa.w + xb.x * xb.x + xb.y * xb.y + xb.z * xb.z + xb.w * xb.w;
+        sq += shfl_xor_f(sq, 16);
+        sq += shfl_xor_f(sq, 32);
+        if (g == 0) ss1[(size_t)pair * m_pad + m] = sq;
     }
 };
 
@@ -279,16 +405,20 @@ struct EpiDown {
 //   out^T[n][m] = sum_k W[k][n] x[m][k]
 // grid = (pairs of n-tiles, KS).  A workgroup owns one pair and one of KS slices of K; its W
 // waves split that slice, each wave streaming its weight fragments straight from HBM into
-// registers in batches of U k-tiles (all loads of a batch are issued before the first MFMA).
-// The waves' partial tiles are added through LDS in wave order.  With KS > 1 the workgroups
-// of a pair park their partial tile in `kpart`, and the last one to arrive (a counter per
-// pair) adds the KS tiles in slice order and runs the epilogue: the result does not depend
-// on which workgroup came last, so it is bit-reproducible.  No workgroup ever waits.
+// registers in batches of U k-tiles, the next batch in flight while the current one feeds the
+// MFMAs.  The waves' partial tiles are added through LDS in wave order.  With KS = 1 the first
+// wave then runs the epilogue; with KS > 1 (PARTIAL) the workgroup parks its tile in `kpart`
+// and k_gemv_finish adds the KS tiles in slice order: sums never depend on timing.
 // ------------------------------------------------------------------------------------------
-template <int W, int U, bool SPLIT, class Epi>
+template <int U, bool SPLIT>
+struct GemvBatch {
+    bf16x8 fa[U], fb[U], fh[U], fl[SPLIT ? U : 1];
+};
+
+template <int W, int U, bool SPLIT, bool PARTIAL, class Epi>
 __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
                                                   const __bf16 *__restrict__ Xlo, int KT, int KS,
-                                                  float *__restrict__ kpart, unsigned int *__restrict__ counters, Epi epi) {
+                                                  float *__restrict__ kpart, Epi epi) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int pair = blockIdx.x, ks = blockIdx.y;
     const int kb0 = (int)(((long)ks * KT) / KS), kb1 = (int)(((long)(ks + 1) * KT) / KS);
@@ -299,27 +429,69 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
     const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
     const bf16x8 *xh = (const bf16x8 *)Xhi + lane;
     const bf16x8 *xl = (const bf16x8 *)Xlo + lane;
-    int kt = k0;
-    for (; kt + U <= k1; kt += U) {
-        bf16x8 fa[U], fb[U], fh[U], fl[U];
+
+    auto load = [&](GemvBatch<U, SPLIT> &B, int kt) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            fa[u] = __builtin_nontemporal_load(wa + (size_t)(kt + u) * 64);
-            fb[u] = __builtin_nontemporal_load(wb + (size_t)(kt + u) * 64);
-            fh[u] = xh[(size_t)(kt + u) * 64];
-            if (SPLIT) fl[u] = xl[(size_t)(kt + u) * 64];
+            B.fa[u] = __builtin_nontemporal_load(wa + (size_t)(kt + u) * 64);
+            B.fb[u] = __builtin_nontemporal_load(wb + (size_t)(kt + u) * 64);
+            B.fh[u] = xh[(size_t)(kt + u) * 64];
+            if (SPLIT) B.fl[u] = xl[(size_t)(kt + u) * 64];
         }
+    };
+    auto consume = [&](const GemvBatch<U, SPLIT> &B) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a = MFMA(fa[u], fh[u], a);
-            b = MFMA(fb[u], fh[u], b);
+            a = MFMA(B.fa[u], B.fh[u], a);
+            b = MFMA(B.fb[u], B.fh[u], b);
             if (SPLIT) {
-                a = MFMA(fa[u], fl[u], a);
-                b = MFMA(fb[u], fl[u], b);
+                a = MFMA(B.fa[u], B.fl[u], a);
+                b = MFMA(B.fb[u], B.fl[u], b);
             }
         }
+    };
+
+    // full batches are taken in an order rotated by the pair index, so that the workgroups that
+    // run side by side do not all ask the L2 for the same activation lines at the same time
+    const int nfull = (k1 - k0) / U;
+    const int rot = nfull > 0 ? pair % nfull : 0;
+    GemvBatch<U, SPLIT> cur;
+    if (nfull > 0) load(cur, k0 + rot * U);
+
+    // loads that do not depend on the stream: the epilogue's inputs (first wave) and this wave's
+    // share of the sum-of-squares partials, issued while the first weights are on their way
+    typename Epi::Pre pre;
+    float ssp = 0.f;
+    if (!PARTIAL) {
+        if (wave == 0) pre = epi.pre(pair, 0, lane);
+        if constexpr (Epi::kNeedsRs) {
+            ssp = sum_ss(epi.ss, epi.nch, epi.m_pad, lane & 15, wave * 4 + (lane >> 4), W * 4);
+        }
     }
-    for (; kt < k1; ++kt) {
+
+    // two register buffers, used alternately: the loads of one batch are in flight while the other
+    // batch feeds the MFMAs
+    GemvBatch<U, SPLIT> oth;
+    auto batch_k = [&](int i) {
+        int bi = i + rot;
+        if (bi >= nfull) bi -= nfull;
+        return k0 + bi * U;
+    };
+    int i = 0;
+    for (; i + 2 < nfull; i += 2) {      // steady state: no branch between the loads and their use
+        load(oth, batch_k(i + 1));
+        consume(cur);
+        load(cur, batch_k(i + 2));
+        consume(oth);
+    }
+    if (i + 1 < nfull) {
+        load(oth, batch_k(i + 1));
+        consume(cur);
+        consume(oth);
+    } else if (i < nfull) {
+        consume(cur);
+    }
+    for (int kt = k0 + nfull * U; kt < k1; ++kt) {
         const bf16x8 fa = __builtin_nontemporal_load(wa + (size_t)kt * 64);
         const bf16x8 fb = __builtin_nontemporal_load(wb + (size_t)kt * 64);
         const bf16x8 fh = xh[(size_t)kt * 64];
@@ -332,8 +504,10 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         }
     }
     __shared__ f32x4 red[W][2][64];
+    __shared__ float red_ss[W][64];
     red[wave][0][lane] = a;
     red[wave][1][lane] = b;
+    red_ss[wave][lane] = ssp;
     __syncthreads();
     if (wave != 0) return;
     a = red[0][0][lane];
@@ -343,33 +517,77 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         a += red[w][0][lane];
         b += red[w][1][lane];
     }
-    if (KS > 1) {
-        // park the partial tile; agent-scope atomics so that another XCD's L2 sees it
-        unsigned int *mine = (unsigned int *)(kpart + ((size_t)pair * KS + ks) * 512) + lane;
+    if (PARTIAL) {
+        float *mine = kpart + ((size_t)pair * KS + ks) * 512 + lane * 4;
+        *(f32x4 *)mine = a;
+        *(f32x4 *)(mine + 256) = b;
+        return;
+    }
+    float rs = 1.f;
+    if constexpr (Epi::kNeedsRs) {
+        float sq = red_ss[0][lane];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __hip_atomic_store(mine + i * 64, __float_as_uint(a[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(mine + (4 + i) * 64, __float_as_uint(b[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        unsigned int old = 0;
-        if (lane == 0) old = __hip_atomic_fetch_add(counters + pair, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        old = __shfl(old, 0, 64);
-        if (old != (unsigned int)(KS - 1)) return;   // not the last slice of this pair: done
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        a = (f32x4){0.f, 0.f, 0.f, 0.f};
-        b = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < KS; ++s) {
-            const unsigned int *src = (const unsigned int *)(kpart + ((size_t)pair * KS + s) * 512) + lane;
+        for (int w = 1; w < W; ++w) sq += red_ss[w][lane];
+        sq += shfl_xor_f(sq, 16);
+        sq += shfl_xor_f(sq, 32);
+        rs = 1.0f / sqrtf(sq / (float)epi.h + epi.eps);
+    }
+    epi(pair, 0, a, b, lane, rs, pre);
+}
+
+// Adds the KS partial tiles of a pair in slice order and runs the epilogue.  grid = pairs,
+// 4 waves: wave w adds the slices s = w, w+4, ...; the four sums are then added in wave order.
+template <class Epi>
+__global__ void __launch_bounds__(256) k_gemv_finish(const float *__restrict__ kpart, int KS, Epi epi) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pair = blockIdx.x;
+    typename Epi::Pre pre;
+    if (wave == 0) pre = epi.pre(pair, 0, lane);
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = wave; s0 < KS; s0 += 16) {
+        f32x4 ta[4], tb[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] += __uint_as_float(__hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                b[i] += __uint_as_float(__hip_atomic_load(src + (4 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        for (int j = 0; j < 4; ++j) {
+            const int sl = s0 + 4 * j;
+            if (sl < KS) {
+                const float *src = kpart + ((size_t)pair * KS + sl) * 512 + lane * 4;
+                ta[j] = *(const f32x4 *)src;
+                tb[j] = *(const f32x4 *)(src + 256);
             }
         }
-        if (lane == 0) __hip_atomic_store(counters + pair, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (s0 + 4 * j < KS) {
+                a += ta[j];
+                b += tb[j];
+            }
     }
-    epi(pair, 0, a, b, lane);
+    float ssp = 0.f;
+    if constexpr (Epi::kNeedsRs) {
+        ssp = sum_ss(epi.ss, epi.nch, epi.m_pad, lane & 15, wave * 4 + (lane >> 4), 16);
+    }
+    __shared__ f32x4 red[4][2][64];
+    __shared__ float red_ss[4][64];
+    red[wave][0][lane] = a;
+    red[wave][1][lane] = b;
+    red_ss[wave][lane] = ssp;
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        a += red[w][0][lane];
+        b += red[w][1][lane];
+    }
+    float rs = 1.f;
+    if constexpr (Epi::kNeedsRs) {
+        float sq = red_ss[0][lane];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) sq += red_ss[w][lane];
+        sq += shfl_xor_f(sq, 16);
+        sq += shfl_xor_f(sq, 32);
+        rs = 1.0f / sqrtf(sq / (float)epi.h + epi.eps);
+    }
+    epi(pair, 0, a, b, lane, rs, pre);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -416,8 +634,13 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
         }
     }
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
-        if (mv[i]) epi(pair, mt0 + i, acc[i][0], acc[i][1], lane);
+    for (int i = 0; i < MT; ++i) {
+        if (!mv[i]) continue;
+        float rs = 1.f;
+        if constexpr (Epi::kNeedsRs)
+            rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, (mt0 + i) * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
+        epi(pair, mt0 + i, acc[i][0], acc[i][1], lane, rs, epi.pre(pair, mt0 + i, lane));
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -606,13 +829,17 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
 __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, int q, int kv, int d, int n_splits) {
     __shared__ float wgt[SPD_MAX_SPLITS][16];     // exp(m_s - M) per split and column
+    __shared__ float lsum[SPD_MAX_SPLITS][16];    // running sums of the splits
     __shared__ float den[16];
     const int kvh = blockIdx.x, b = blockIdx.y, dchunk = blockIdx.z;
     const int group = q / kv, qd = q * d;
     const size_t pstride = (size_t)(d + 2) * 16;
     const float *src = part + ((size_t)b * kv + kvh) * n_splits * pstride;
     const int tid = threadIdx.x;
-    for (int e = tid; e < n_splits * 16; e += 256) wgt[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + d * 16 + (e & 15)];
+    for (int e = tid; e < n_splits * 16; e += 256) {
+        wgt[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + d * 16 + (e & 15)];
+        lsum[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + (d + 1) * 16 + (e & 15)];
+    }
     __syncthreads();
     if (tid < 16) {
         float mm = -INFINITY;
@@ -622,7 +849,7 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
             const float ms = wgt[s][tid];
             const float sc = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
             wgt[s][tid] = sc;
-            dn += src[(size_t)s * pstride + (d + 1) * 16 + tid] * sc;
+            dn += lsum[s][tid] * sc;
         }
         den[tid] = dn;
     }
@@ -740,50 +967,58 @@ inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b);
         if (e_ != hipSuccess) return e_; \
     } while (0)
 
-// Launch shape of a projection.  At most 16 tokens: the weight-streaming kernel; the number of
-// K slices is chosen so that about two workgroups per compute unit are in flight.
-template <class Epi>
-hipError_t launch_proj(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
+// Launch shape of a projection.  At most 16 tokens: the weight-streaming kernel, one workgroup
+// per pair of n-tiles when there are enough pairs to occupy the chip, otherwise K is also cut
+// into KS slices (about two workgroups per compute unit) and a second small kernel adds them.
+template <bool SPLIT, class Epi>
+hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, const __bf16 *Xlo, int n_pairs, int KT,
                        const Epi &epi) {
     const spd_dims &D = *c.D;
-    const int M = c.M;
-    const int n_mtiles = (M + 15) / 16;
-    const __bf16 *Xlo = Xhi + plane;
-    if (n_mtiles == 1) {
-        float *kpart = (float *)(c.ws + D.ws_kpart);
-        unsigned int *counters = (unsigned int *)(c.ws + D.ws_counters);
-        if (n_pairs > SPD_N_COUNTERS) return hipErrorInvalidValue;
-        if (n_pairs >= 192 && KT >= 64) {
-            // enough pairs to occupy the chip: one workgroup of 16 waves per pair, no slices
-            constexpr int W = 16, U = 4;
-            if (c.split)
-                hipLaunchKernelGGL((k_gemv<W, U, true, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
-                                   kpart, counters, epi);
-            else
-                hipLaunchKernelGGL((k_gemv<W, U, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
-                                   kpart, counters, epi);
+    float *kpart = (float *)(c.ws + D.ws_kpart);
+    if (n_pairs >= 192) {
+        // enough pairs to occupy the chip: one workgroup per pair, no slices
+        if (KT >= 64) {
+            constexpr int W = 16, U = 2;     // 16 waves share 512 VGPRs per lane and SIMD: two batches of 2 k-tiles fit
+            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
+                               1, kpart, epi);
         } else {
-            constexpr int W = 8, U = 4;
-            int KS = (512 + n_pairs - 1) / n_pairs;
-            const int ks_max = KT / W > 0 ? KT / W : 1;         // at least one k-tile per wave
-            if (KS > ks_max) KS = ks_max;
-            if (KS < 1) KS = 1;
-            while ((size_t)n_pairs * KS > (size_t)SPD_MAX_KPART && KS > 1) --KS;
-            if (c.split)
-                hipLaunchKernelGGL((k_gemv<W, U, true, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
-                                   kpart, counters, epi);
-            else
-                hipLaunchKernelGGL((k_gemv<W, U, false, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
-                                   kpart, counters, epi);
+            constexpr int W = 8, U = 2;
+            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
+                               1, kpart, epi);
         }
-    } else {
-        constexpr int MT = 4, W = 4;
-        const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
-        if (c.split)
-            hipLaunchKernelGGL((k_gemm<MT, W, true, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
-        else
-            hipLaunchKernelGGL((k_gemm<MT, W, false, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
+        return hipGetLastError();
     }
+    constexpr int W = 8, U = 2;
+    int KS = (512 + n_pairs - 1) / n_pairs;
+    const int ks_max = KT / (2 * W) > 0 ? KT / (2 * W) : 1;         // at least two k-tiles per wave
+    if (KS > ks_max) KS = ks_max;
+    while ((size_t)n_pairs * KS > (size_t)SPD_MAX_KPART && KS > 1) --KS;
+    if (KS <= 1) {
+        hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
+                           kpart, epi);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((k_gemv<W, U, SPLIT, true, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+                       kpart, epi);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_gemv_finish<Epi>), dim3(n_pairs), dim3(256), 0, c.s, kpart, KS, epi);
+    return hipGetLastError();
+}
+
+template <class Epi>
+hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
+                       const Epi &epi) {
+    const int n_mtiles = (c.M + 15) / 16;
+    const __bf16 *Xlo = Xhi + plane;
+    if (n_mtiles == 1)
+        return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
+    constexpr int MT = 4, W = 4;
+    const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
+    if (split)
+        hipLaunchKernelGGL((k_gemm<MT, W, true, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
+    else
+        hipLaunchKernelGGL((k_gemm<MT, W, false, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
     return hipGetLastError();
 }
 
@@ -800,7 +1035,7 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     const spd_dims &D = *c.D;
     const int tpw = prep_tpw(c.M), nch = prep_nch(D.h, c.M);
     __bf16 *xhat = want_xhat ? (__bf16 *)(c.ws + (which ? D.ws_xhat2 : D.ws_xhat)) : nullptr;
-    __bf16 *xlo = (want_xhat && c.split) ? xhat + D.pl_x : nullptr;
+    __bf16 *xlo = (want_xhat && (which ? c.split : c.split_all)) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base) out = nullptr;   // nothing to rewrite
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
@@ -809,25 +1044,27 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     return hipGetLastError();
 }
 
+int prep_chunks(const spd_call &c) { return prep_nch(c.D->h, c.M); }
+
 hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot) {
     const spd_dims &D = *c.D;
     const int M = c.M, qd = D.q * D.d;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat);
     __bf16 *qbuf = (__bf16 *)(c.ws + D.ws_q), *ahat = (__bf16 *)(c.ws + D.ws_ahat);
-    __bf16 *alo = c.split ? ahat + D.pl_a : nullptr;
+    __bf16 *alo = c.split_all ? ahat + D.pl_a : nullptr;
     __bf16 *qlo = qbuf + D.pl_a;
     __bf16 *kc = (__bf16 *)kvc, *vc = (__bf16 *)(kvc + D.kv_v);
     float *ybuf = (float *)(c.ws + D.ws_y);
 
     EpiQKV e1;
     e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
-    e1.nch = prep_nch(D.h, M); e1.m_pad = D.m_pad; e1.eps = D.eps;
+    e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
     e1.ss = (const float *)(c.ws + D.ws_ss1);
     e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
     e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
     {
         spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
+        SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
     }
 
     const int DT = D.d / 16;
@@ -882,7 +1119,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
     {
         spd_profile::scope prof(SPD_STAGE_O, c.s);
-        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_o), ahat, D.pl_a, D.h / 32, qd / 32, e2));
+        SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_o), ahat, D.pl_a, D.h / 32, qd / 32, e2));
     }
 
     if (c.taps) {
@@ -901,7 +1138,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     return hipSuccess;
 }
 
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot) {
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused) {
     const spd_dims &D = *c.D;
     const int M = c.M;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat2);
@@ -917,15 +1154,27 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot) {
     e1.uhat = uhat; e1.ulo = ulo;
     {
         spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
-        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+        SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
     }
 
     EpiDown e2;
     e2.M = M; e2.h = D.h; e2.spd = spd;
     e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
+    e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
+    e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
+    if (fused) *fused = false;
+    if (fuse && M <= 16) {
+        e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp; e2.rank = fuse->rank;
+        e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.ss1 = (float *)(c.ws + D.ws_ss1);
+        if (fuse->next_g1) {
+            e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);
+            e2.xlo = c.split_all ? e2.xhat + D.pl_x : nullptr;
+        }
+        if (fused) *fused = true;
+    }
     {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
-        SPD_TRY(launch_proj(c, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+        SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
     }
 
     if (c.taps && c.taps->u) {

@@ -222,7 +222,9 @@ def test_bf16_single_rank_model(gpu, batch, q_len, positions):
     say(f"mid {q_len=}: worst per-layer err {worst:.2e}")
     chain = x.cpu().numpy()
 
-    # end to end through spd_model_forward on fresh caches: same kernels, same order -> same bits
+    # end to end through spd_model_forward on fresh caches.  It fuses each block's closing rank-sum
+    # into the down projection, so the norm statistics are added in another (fixed) order than in
+    # the block-by-block chain: equal up to rounding, not bit for bit
     case2 = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=256, max_tokens=48)
     slots2 = case2.to_dev(peers)
     out2 = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
@@ -230,7 +232,8 @@ def test_bf16_single_rank_model(gpu, batch, q_len, positions):
                                 case2.to_dev(X), slots2, out2, case2.dev.workspace)
     torch.cuda.synchronize()
     assert syncs == B.spd_sync_count(case2.dev.ctx, w.mask) == 5
-    assert np.array_equal(out2.cpu().numpy(), chain)
+    assert np.max(np.abs(out2.cpu().numpy() - chain)) <= 2e-3
+    chain = out2.cpu().numpy()
     want = O.model_single_rank(case2.sh, X, [s[0] for s in case2.shards], [c[0] for c in case2.caches], positions,
                                batch, q_len, w.mask, rank, peers.astype(np.float64))
     err = float(np.max(np.abs(chain - want)))
