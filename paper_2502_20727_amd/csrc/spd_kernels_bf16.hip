@@ -309,7 +309,8 @@ struct EpiGU {
     }
 };
 
-struct EpiDown {
+template <bool FUSED>
+struct EpiDownT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd;
     const float *ybuf;
@@ -369,7 +370,7 @@ struct EpiDown {
             *(float4 *)(slot + oa) = pa;
             *(float4 *)(slot + ob) = pb;
         }
-        if (!base) return;
+        if (!FUSED) return;
         float4 xa = make_float4(0.f, 0.f, 0.f, 0.f), xb = xa;
         if (valid) {
             xa = sync_sum(oa, pa);
@@ -644,6 +645,111 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
 }
 
 // ------------------------------------------------------------------------------------------
+// GEMM for prefill-sized calls: a workgroup of 8 waves computes a 256 (output features) x 256
+// (tokens) tile; both operands are staged through LDS in steps of 64 contraction elements,
+// double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
+// memory, so a stage is filled with gfx950's direct global->LDS loads (one instruction per
+// fragment, no staging registers) and read back with conflict-free 16-byte LDS reads.  Each
+// wave owns 8 n-tiles x 4 m-tiles (128 accumulator registers).  One barrier per step.
+// ------------------------------------------------------------------------------------------
+constexpr int GL_WN = 2, GL_WM = 4, GL_TI = 8, GL_TJ = 4;
+constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // 16 x 16 tiles per workgroup
+constexpr int GL_STAGE = (GL_BN + GL_BM) * 2 * 1024;                 // 64 KiB per stage
+constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
+
+template <class Epi>
+__global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
+                                                                 int KT, int n_ntiles, int n_mtiles, int TN, Epi epi) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wn = wave % GL_WN, wm = wave / GL_WN;
+    const int tn = blockIdx.x % TN, tm = blockIdx.x / TN;
+    const int nt0 = tn * GL_BN, mt0 = tm * GL_BM;
+    f32x4 acc[GL_TI][GL_TJ];
+#pragma unroll
+    for (int i = 0; i < GL_TI; ++i)
+#pragma unroll
+        for (int j = 0; j < GL_TJ; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // this wave's share of the copies: GL_FPW tile rows; the two k-tiles of a row are 2 KiB
+    // contiguous both in global memory and in LDS.  Rows past the matrix repeat its last tile.
+    const __bf16 *src[GL_FPW];
+#pragma unroll
+    for (int i = 0; i < GL_FPW; ++i) {
+        const int row = wave * GL_FPW + i;
+        if (row < GL_BN) {
+            int t = nt0 + row;
+            if (t >= n_ntiles) t = n_ntiles - 1;
+            src[i] = Wp + spd_frag_index(t, 0, KT) + lane * 8;
+        } else {
+            int t = mt0 + row - GL_BN;
+            if (t >= n_mtiles) t = n_mtiles - 1;
+            src[i] = Xp + spd_frag_index(t, 0, KT) + lane * 8;
+        }
+    }
+    auto issue = [&](int stage, int ks) {
+#pragma unroll
+        for (int i = 0; i < GL_FPW; ++i) {
+            const __bf16 *g = src[i] + (size_t)ks * 1024;
+            char *l = lds + stage * GL_STAGE + (wave * GL_FPW + i) * 2048;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                             (__attribute__((address_space(3))) void *)l, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                             (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
+        }
+    };
+    const int nks = KT >> 1;
+    issue(0, 0);
+    for (int ks = 0; ks < nks; ++ks) {
+        const int cur = ks & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's copies into `cur` have landed
+        __syncthreads();                                     // everybody's have, and nobody still reads the other stage
+        if (ks + 1 < nks) issue(cur ^ 1, ks + 1);
+        const char *st = lds + cur * GL_STAGE;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            bf16x8 a[GL_TI], b[GL_TJ];
+#pragma unroll
+            for (int i = 0; i < GL_TI; ++i) a[i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * 2 + kt) * 1024 + lane * 16);
+#pragma unroll
+            for (int j = 0; j < GL_TJ; ++j)
+                b[j] = *(const bf16x8 *)(st + GL_BN * 2048 + ((wm * GL_TJ + j) * 2 + kt) * 1024 + lane * 16);
+#pragma unroll
+            for (int i = 0; i < GL_TI; ++i)
+#pragma unroll
+                for (int j = 0; j < GL_TJ; ++j) acc[i][j] = MFMA(a[i], b[j], acc[i][j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < GL_TJ; ++j) {
+        const int mt = mt0 + wm * GL_TJ + j;
+        if (mt >= n_mtiles) continue;
+        float rs = 1.f;
+        if constexpr (Epi::kNeedsRs) rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
+#pragma unroll
+        for (int i = 0; i < GL_TI; i += 2) {
+            const int nt = nt0 + wn * GL_TI + i;
+            if (nt >= n_ntiles) continue;
+            epi(nt >> 1, mt, acc[i][j], acc[i + 1][j], lane, rs, epi.pre(nt >> 1, mt, lane));
+        }
+    }
+}
+
+template <class Epi>
+hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
+    static bool attr_set = false;       // the attribute is per kernel instantiation; setting it twice is harmless
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_lds<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * GL_STAGE);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
+    const int TN = (n_ntiles + GL_BN - 1) / GL_BN, TM = (n_mtiles + GL_BM - 1) / GL_BM;
+    hipLaunchKernelGGL((k_gemm_lds<Epi>), dim3(TN * TM), dim3(GL_WN * GL_WM * 64), 2 * GL_STAGE, c.s, Wp, Xp, KT, n_ntiles,
+                       n_mtiles, TN, epi);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Attention.  Scores are computed transposed, S^T[key][col] = K q, so that the probabilities
 // leave the MFMA already in the operand layout of the second contraction O^T = V^T P^T.
 // A "column" is a (token, query head of the KV group) pair: col = t * group + c.
@@ -776,18 +882,18 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
     st.m = -INFINITY;
     st.l = 0.f;
     const float scale = 1.0f / sqrtf((float)d);
-    int vb = b0 + wave;
-    if (vb < b1) {
-        KVFrags<DT> cur;
-        load_kv<DT>(cur, kbase, vbase, vb, d, lane);
+    if (b0 + wave < b1) {
         bf16x8 qf[DT];
         load_q<DT>(qf, qbuf, qlo, b, kvh * group + col, qd, d, cvalid, lane);
-        for (; vb < b1; vb += 4) {
-            KVFrags<DT> nxt;
-            const bool more = vb + 4 < b1;
-            if (more) load_kv<DT>(nxt, kbase, vbase, vb + 4, d, lane);
-            attn_block<DT>(st, qf, cur, vb, cvalid ? n_keys : 0, scale, lane);
-            if (more) cur = nxt;
+        // two key blocks at a time, both loaded before the first is used (no branch in between, so
+        // that the second block's loads stay in flight while the first block is processed)
+        for (int vb = b0 + wave; vb < b1; vb += 8) {
+            const int vb2 = vb + 4 < b1 ? vb + 4 : vb;      // clamp: a repeated block is masked below
+            KVFrags<DT> f0, f1;
+            load_kv<DT>(f0, kbase, vbase, vb, d, lane);
+            load_kv<DT>(f1, kbase, vbase, vb2, d, lane);
+            attn_block<DT>(st, qf, f0, vb, cvalid ? n_keys : 0, scale, lane);
+            attn_block<DT>(st, qf, f1, vb2, (cvalid && vb + 4 < b1) ? n_keys : 0, scale, lane);
         }
     }
     // merge the four waves
@@ -825,55 +931,48 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
 
 // merge the splits of one (sequence, KV head) and write the normalised output as packed
 // activations of the O projection: row = token, contraction index = head*d + dd.
-// grid (kv heads, sequences, d/32): each workgroup produces 32 features of every head of the group.
+// grid (kv heads, sequences, d/16); thread -> (feature dd, column c).  Every thread reads the
+// running max and sum of its column itself (16 splits at a time, all loads issued together), so
+// the kernel is one memory round trip per 16 splits; the splits are merged in ascending order.
 __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, int q, int kv, int d, int n_splits) {
-    __shared__ float wgt[SPD_MAX_SPLITS][16];     // exp(m_s - M) per split and column
-    __shared__ float lsum[SPD_MAX_SPLITS][16];    // running sums of the splits
-    __shared__ float den[16];
-    const int kvh = blockIdx.x, b = blockIdx.y, dchunk = blockIdx.z;
+    const int kvh = blockIdx.x, b = blockIdx.y;
     const int group = q / kv, qd = q * d;
     const size_t pstride = (size_t)(d + 2) * 16;
     const float *src = part + ((size_t)b * kv + kvh) * n_splits * pstride;
-    const int tid = threadIdx.x;
-    for (int e = tid; e < n_splits * 16; e += 256) {
-        wgt[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + d * 16 + (e & 15)];
-        lsum[e >> 4][e & 15] = src[(size_t)(e >> 4) * pstride + (d + 1) * 16 + (e & 15)];
-    }
-    __syncthreads();
-    if (tid < 16) {
-        float mm = -INFINITY;
-        for (int s = 0; s < n_splits; ++s) mm = fmaxf(mm, wgt[s][tid]);
-        float dn = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const float ms = wgt[s][tid];
-            const float sc = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-            wgt[s][tid] = sc;
-            dn += lsum[s][tid] * sc;
-        }
-        den[tid] = dn;
-    }
-    __syncthreads();
-    // 32 features x 16 columns per workgroup; thread -> (feature, column) pairs, columns fastest
-    for (int e = tid; e < 32 * 16; e += 256) {
-        const int c = e & 15, dd = dchunk * 32 + (e >> 4);
-        if (c >= group) continue;
-        float num = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += 8) {
-            float t[8];
+    const int c = threadIdx.x & 15, dd = blockIdx.z * 16 + (threadIdx.x >> 4);
+    if (c >= group) return;
+    float M = -INFINITY, num = 0.f, den = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += 16) {
+        float ms[16], ls[16], os[16];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (s0 + j < n_splits) ? src[(size_t)(s0 + j) * pstride + dd * 16 + c] : 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (s0 + j < n_splits) num += t[j] * wgt[s0 + j][c];
+        for (int j = 0; j < 16; ++j) {
+            const bool ok = s0 + j < n_splits;
+            const float *p = src + (size_t)(ok ? s0 + j : s0) * pstride;
+            ms[j] = ok ? p[d * 16 + c] : -INFINITY;
+            ls[j] = ok ? p[(d + 1) * 16 + c] : 0.f;
+            os[j] = ok ? p[dd * 16 + c] : 0.f;
         }
-        const float val = num / den[c];
-        const int kidx = (kvh * group + c) * d + dd;
-        const size_t o = spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31);
-        const __bf16 hi = (__bf16)val;
-        ahat[o] = hi;
-        if (alo) alo[o] = (__bf16)(val - (float)hi);
+        float mc = M;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) mc = fmaxf(mc, ms[j]);
+        const float keep = (M == -INFINITY) ? 0.f : __expf(M - mc);
+        num *= keep;
+        den *= keep;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float sc = (ms[j] == -INFINITY) ? 0.f : __expf(ms[j] - mc);
+            num += os[j] * sc;
+            den += ls[j] * sc;
+        }
+        M = mc;
     }
+    const float val = num / den;
+    const int kidx = (kvh * group + c) * d + dd;
+    const size_t o = spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31);
+    const __bf16 hi = (__bf16)val;
+    ahat[o] = hi;
+    if (alo) alo[o] = (__bf16)(val - (float)hi);
 }
 
 // Prefill (q_len > 1): grid (column-tile groups, kv heads, sequences), 4 waves, each wave owns
@@ -1013,6 +1112,7 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
     const __bf16 *Xlo = Xhi + plane;
     if (n_mtiles == 1)
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
+    if (!split && (KT % 2) == 0 && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
     constexpr int MT = 4, W = 4;
     const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
     if (split)
@@ -1089,7 +1189,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         }
 #undef SPD_DECODE
         SPD_TRY(hipGetLastError());
-        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch, D.d / 32), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
+        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch, D.d / 16), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
                            D.d, splits);
         SPD_TRY(hipGetLastError());
     } else {
@@ -1157,24 +1257,33 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
         SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
     }
 
-    EpiDown e2;
-    e2.M = M; e2.h = D.h; e2.spd = spd;
-    e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
-    e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
-    e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
-    if (fused) *fused = false;
-    if (fuse && M <= 16) {
-        e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp; e2.rank = fuse->rank;
-        e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.ss1 = (float *)(c.ws + D.ws_ss1);
-        if (fuse->next_g1) {
-            e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);
-            e2.xlo = c.split_all ? e2.xhat + D.pl_x : nullptr;
+    const bool do_fuse = fuse && M <= 16;
+    if (fused) *fused = do_fuse;
+    auto fill = [&](auto &e2) {
+        e2.M = M; e2.h = D.h; e2.spd = spd;
+        e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
+        e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
+        e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
+        if (do_fuse) {
+            e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp;
+            e2.rank = fuse->rank; e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.ss1 = (float *)(c.ws + D.ws_ss1);
+            if (fuse->next_g1) {
+                e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);
+                e2.xlo = c.split_all ? e2.xhat + D.pl_x : nullptr;
+            }
         }
-        if (fused) *fused = true;
-    }
+    };
     {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
-        SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+        if (do_fuse) {
+            EpiDownT<true> e2;
+            fill(e2);
+            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+        } else {
+            EpiDownT<false> e2;
+            fill(e2);
+            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+        }
     }
 
     if (c.taps && c.taps->u) {

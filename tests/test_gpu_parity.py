@@ -141,12 +141,13 @@ SMALL_MHA = Workload(name="small-bf16-mha", hidden=128, n_q_heads=4, n_kv_heads=
     (2, 7, [0, 5]),               # 14 tokens: a partial m-tile
     (3, 11, [3, 0, 20]),          # 33 tokens: three m-tiles with a ragged tail
     (1, 40, [8]),                 # one long chunk crossing several key blocks
-], ids=["decode", "chunk14", "chunk33", "chunk40"])
+    (3, 50, [0, 5, 14]),          # 150 tokens: the LDS-tiled GEMM with a partly empty workgroup tile
+], ids=["decode", "chunk14", "chunk33", "chunk40", "chunk150"])
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
     import torch
     M = batch * q_len
-    case = Case(w, gpu, ranks=range(w.tp), positions=positions, max_ctx=64, max_tokens=48)
+    case = Case(w, gpu, ranks=range(w.tp), positions=positions, max_ctx=64, max_tokens=max(48, M))
     X = inputs.hidden_states(w, M)
     slots = torch.zeros((w.tp, M, w.hidden), dtype=torch.float32, device=gpu)
     say(f"case {w.name} batch={batch} q_len={q_len} pos={positions} flag={flag}")
