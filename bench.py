@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 import numpy as np
 
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (summaries and the copy-kernel calibration are under profiles/); None = not measured
+MEASURED_TRAFFIC = {}
+
+
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
@@ -87,15 +92,37 @@ def time_forward(torch, B, shard, w, mask, positions, x, slots, out, steps, warm
 
 
 def stage_time(torch, B, shard, w, mask, positions, x, slots, out, stage, reps):
-    """Mean duration of one stage's launches, HIP events on the launch stream (eager mode)."""
-    B.spd_profile_enable(B.STAGES[stage], reps * w.n_layers * 2)
-    for _ in range(reps):
-        B.spd_model_forward(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots, out,
-                            shard.workspace)
-    torch.cuda.synchronize()
-    n, mean_us, min_us = B.spd_profile_read()
-    B.spd_profile_disable()
-    return n, mean_us, min_us
+    """Average duration of ONE launch of a stage's kernel(s), HIP events on the launch stream.
+
+    The library is told to launch only that stage; one whole-model call then is a train of
+    n_layers launches of the same kernel over every layer's distinct weights (no cache reuse).
+    The train is captured into a HIP graph (no launch gaps) and replayed `reps` times between
+    one pair of events.  Returns (launches, mean microseconds per launch of the stage).
+    """
+    stream = torch.cuda.current_stream()
+    B.spd_profile_only(B.STAGES[stage])
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                B.spd_model_forward(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots,
+                                    out, shard.workspace)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        per_launch_us = e0.elapsed_time(e1) * 1e3 / (reps * w.n_layers)
+    finally:
+        B.spd_profile_only(-1)
+    return reps * w.n_layers, per_launch_us
 
 
 def algorithmic_work(w):
@@ -172,6 +199,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-synced", action="store_true", help="skip the all-sync-points-kept run")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain copy of MIB MiB (spd_rank_sum with one slot, no base) 10 times: the reference "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one tensor-parallel rank on ONE GPU; sync points that are kept are "
@@ -182,6 +212,18 @@ def main():
     from paper_2502_20727_amd import binding as B
     from paper_2502_20727_amd import inputs, workloads
 
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        n = args.calibrate_copy * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        ctx = B.spd_create(B.make_config(workloads.TOY, max_ctx=64))
+        for _ in range(10):
+            B.spd_rank_sum(ctx, None, src, 1, n, dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "bytes_read": n * 4, "bytes_written": n * 4,
+                          "kernel": "k_rank_sum4", "launches": 10}))
+        return
     w = workloads.get(args.workload)
     if args.layers:
         w = w.with_layers(args.layers)
@@ -222,26 +264,27 @@ def main():
             f"all SPD: {extra['us_per_layer_all_spd']:.2f} us/layer")
 
     work = algorithmic_work(w)
-    # dominant kernel: the gate/up projection (55 % of the weights, 55 % of the flops)
-    n, mean_us, min_us = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, "gateup",
-                                    2 if prefill else 5)
+    # dominant kernel: the gate/up projection + SwiGLU (55 % of the weights, 55 % of the flops)
+    reps = 3 if prefill else 10
+    n, mean_us = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, "gateup", reps)
     if prefill:
         roof = dict(bound="mfma", achieved=work["gateup"]["flops"] / (mean_us * 1e-6) / 1e12, peak=2500.0,
                     unit="TFLOP/s")
     else:
         roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=8000.0, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    roof["kernel"] = "gate/up projection + SwiGLU"
+    roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
+    roof["kernel"] = "k_gemm_lds<EpiGU>" if prefill else "k_gemv<16,2,split,EpiGU>"
+    roof["stage"] = "gate/up projection + SwiGLU"
     roof["launches_timed"] = n
     roof["mean_us"] = mean_us
-    roof["min_us"] = min_us
-    stages = {}
+    roof["algorithmic_bytes_per_launch"] = work["gateup"]["bytes"]
+    roof["algorithmic_flops_per_launch"] = work["gateup"]["flops"]
+    stages = {"gateup": round(mean_us, 2)}
     for st in ("prep", "qkv", "attn", "o", "down"):
-        _, m_us, _ = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, st, 2)
+        _, m_us = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, st, max(1, reps // 2))
         stages[st] = round(m_us, 2)
-    stages["gateup"] = round(mean_us, 2)
-    log(f"stage means (us, eager, HIP events): {stages}")
+    log(f"mean us per launch of each stage (single-stage launch trains under a HIP graph): {stages}")
 
     whole = dict(hbm_GBps=work["bytes"] / (us_layer * 1e-6) / 1e9, hbm_frac=work["bytes"] / (us_layer * 1e-6) / 8e12,
                  mfma_TFLOPs=work["flops"] / (us_layer * 1e-6) / 1e12,

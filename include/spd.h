@@ -242,6 +242,12 @@ int spd_profile_enable(int32_t stage, int32_t max_records);
 int spd_profile_read(int32_t *n_records, double *mean_us, double *min_us);
 /* Stops timing and destroys the events. */
 int spd_profile_disable(void);
+/* Benchmark aid: while `stage` is selected (0 .. SPD_N_STAGES-1) forward calls launch ONLY the
+ * kernels of that stage and skip everything else, so that a whole-model call becomes a train
+ * of launches of one kernel over every layer's distinct weights (its inputs are whatever an
+ * earlier full call left in the workspace; the outputs are meaningless).  -1 restores normal
+ * operation.  Process-wide; SPD_EINVAL for other values. */
+int spd_profile_only(int32_t stage);
 
 #ifdef __cplusplus
 }

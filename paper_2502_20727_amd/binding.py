@@ -80,6 +80,7 @@ _PROTOS = {
     "spd_profile_enable": (C.c_int, [C.c_int32, C.c_int32]),
     "spd_profile_read": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_profile_disable": (C.c_int, []),
+    "spd_profile_only": (C.c_int, [C.c_int32]),
 }
 EXPORTS = tuple(_PROTOS)
 STAGES = {"prep": 0, "qkv": 1, "attn": 2, "o": 3, "gateup": 4, "down": 5}
@@ -290,6 +291,10 @@ def spd_profile_read():
     n, mean, mn = C.c_int32(), C.c_double(), C.c_double()
     _check(lib().spd_profile_read(C.byref(n), C.byref(mean), C.byref(mn)), "spd_profile_read")
     return n.value, mean.value, mn.value
+
+
+def spd_profile_only(stage: int) -> None:
+    _check(lib().spd_profile_only(stage), "spd_profile_only")
 
 
 def spd_profile_disable() -> None:

@@ -191,7 +191,7 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
         } else if (bf) {
             SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0));
             c.nch1 = spd_bf16::prep_chunks(c);
-        } else {
+        } else if (spd_profile::enabled(SPD_STAGE_PREP)) {
             SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
         }
         syncs += 1;
@@ -214,7 +214,12 @@ struct ProfileState {
 } g_prof;
 }  // namespace
 
+namespace {
+int g_only_stage = -1;
+}
+
 namespace spd_profile {
+bool enabled(int stage) { return g_only_stage < 0 || g_only_stage == stage; }
 void begin(int stage, hipStream_t s) {
     if (stage != g_prof.stage || g_prof.n >= g_prof.cap) return;
     (void)hipEventRecord(g_prof.start[g_prof.n], s);
@@ -227,6 +232,12 @@ void end(int stage, hipStream_t s) {
 }  // namespace spd_profile
 
 extern "C" {
+
+int spd_profile_only(int32_t stage) {
+    if (stage < -1 || stage >= SPD_N_STAGES) return SPD_EINVAL;
+    g_only_stage = stage;
+    return SPD_OK;
+}
 
 int spd_profile_disable(void) {
     for (auto e : g_prof.start) (void)hipEventDestroy(e);

@@ -114,6 +114,7 @@ struct spd_call {
 
 // stage timing: brackets a launch with events when spd_profile_enable() selected the stage
 namespace spd_profile {
+bool enabled(int stage);      // false while another stage is selected by spd_profile_only()
 void begin(int stage, hipStream_t s);
 void end(int stage, hipStream_t s);
 struct scope {

@@ -650,9 +650,9 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
 // double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
 // memory, so a stage is filled with gfx950's direct global->LDS loads (one instruction per
 // fragment, no staging registers) and read back with conflict-free 16-byte LDS reads.  Each
-// wave owns 8 n-tiles x 4 m-tiles (128 accumulator registers).  One barrier per step.
+// wave owns 4 n-tiles x 8 m-tiles (128 accumulator registers).  One barrier per step.
 // ------------------------------------------------------------------------------------------
-constexpr int GL_WN = 2, GL_WM = 4, GL_TI = 8, GL_TJ = 4;
+constexpr int GL_WN = 4, GL_WM = 2, GL_TI = 4, GL_TJ = 8;
 constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // 16 x 16 tiles per workgroup
 constexpr int GL_STAGE = (GL_BN + GL_BM) * 2 * 1024;                 // 64 KiB per stage
 constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
@@ -705,31 +705,64 @@ __global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *_
         __syncthreads();                                     // everybody's have, and nobody still reads the other stage
         if (ks + 1 < nks) issue(cur ^ 1, ks + 1);
         const char *st = lds + cur * GL_STAGE;
+        // all 24 fragments of the step are requested first, then the 64 MFMAs run in program order
+        // (the scheduling barriers keep the compiler from re-interleaving reads and MFMAs, which
+        // would make it wait for the whole LDS queue before every group of MFMAs)
+        bf16x8 a[2][GL_TI], b[2][GL_TJ];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
-            bf16x8 a[GL_TI], b[GL_TJ];
-#pragma unroll
-            for (int i = 0; i < GL_TI; ++i) a[i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * 2 + kt) * 1024 + lane * 16);
 #pragma unroll
             for (int j = 0; j < GL_TJ; ++j)
-                b[j] = *(const bf16x8 *)(st + GL_BN * 2048 + ((wm * GL_TJ + j) * 2 + kt) * 1024 + lane * 16);
+                b[kt][j] = *(const bf16x8 *)(st + GL_BN * 2048 + ((wm * GL_TJ + j) * 2 + kt) * 1024 + lane * 16);
+#pragma unroll
+            for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * 2 + kt) * 1024 + lane * 16);
+        }
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
-                for (int j = 0; j < GL_TJ; ++j) acc[i][j] = MFMA(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < GL_TJ; ++j) {
+                    acc[i][j] = MFMA(a[kt][i], b[kt][j], acc[i][j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    }
+    // norm factors of all the wave's m-tiles first, so that their loads are in flight together
+    float rs[GL_TJ];
+#pragma unroll
+    for (int j = 0; j < GL_TJ; ++j) {
+        rs[j] = 1.f;
+        if constexpr (Epi::kNeedsRs) {
+            int mt = mt0 + wm * GL_TJ + j;
+            if (mt >= n_mtiles) mt = n_mtiles - 1;
+            rs[j] = sum_ss(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, 4);
+        }
+    }
+    if constexpr (Epi::kNeedsRs) {
+#pragma unroll
+        for (int j = 0; j < GL_TJ; ++j) {
+            float s = rs[j];
+            s += shfl_xor_f(s, 16);
+            s += shfl_xor_f(s, 32);
+            rs[j] = 1.0f / sqrtf(s / (float)epi.h + epi.eps);
         }
     }
 #pragma unroll
     for (int j = 0; j < GL_TJ; ++j) {
         const int mt = mt0 + wm * GL_TJ + j;
         if (mt >= n_mtiles) continue;
-        float rs = 1.f;
-        if constexpr (Epi::kNeedsRs) rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
+        typename Epi::Pre pre[GL_TI / 2];
+#pragma unroll
+        for (int i = 0; i < GL_TI; i += 2) {
+            int nt = nt0 + wn * GL_TI + i;
+            if (nt >= n_ntiles) nt = n_ntiles - 2;
+            pre[i / 2] = epi.pre(nt >> 1, mt, lane);
+        }
 #pragma unroll
         for (int i = 0; i < GL_TI; i += 2) {
             const int nt = nt0 + wn * GL_TI + i;
             if (nt >= n_ntiles) continue;
-            epi(nt >> 1, mt, acc[i][j], acc[i + 1][j], lane, rs, epi.pre(nt >> 1, mt, lane));
+            epi(nt >> 1, mt, acc[i][j], acc[i + 1][j], lane, rs[j], pre[i / 2]);
         }
     }
 }
@@ -1138,6 +1171,7 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     __bf16 *xlo = (want_xhat && (which ? c.split : c.split_all)) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base) out = nullptr;   // nothing to rewrite
+    if (!spd_profile::enabled(SPD_STAGE_PREP)) return hipSuccess;
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
     hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
                        (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad);
@@ -1162,14 +1196,16 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e1.ss = (const float *)(c.ws + D.ws_ss1);
     e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
     e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
-    {
+    if (spd_profile::enabled(SPD_STAGE_QKV)) {
         spd_profile::scope prof(SPD_STAGE_QKV, c.s);
         SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
     }
 
     const int DT = D.d / 16;
     spd_profile::begin(SPD_STAGE_ATTN, c.s);
-    if (c.q_len == 1) {
+    if (!spd_profile::enabled(SPD_STAGE_ATTN)) {
+        // skipped
+    } else if (c.q_len == 1) {
         // about 8 key blocks (256 keys) per workgroup, two per wave
         const int nblk = (c.max_pos_end + 31) / 32;
         int splits = (nblk + 7) / 8;
@@ -1217,7 +1253,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
     e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
     e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
-    {
+    if (spd_profile::enabled(SPD_STAGE_O)) {
         spd_profile::scope prof(SPD_STAGE_O, c.s);
         SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_o), ahat, D.pl_a, D.h / 32, qd / 32, e2));
     }
@@ -1252,7 +1288,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     e1.nch = spd ? D.h / 32 : prep_nch(D.h, M);
     e1.ss = (const float *)(c.ws + D.ws_ss2);
     e1.uhat = uhat; e1.ulo = ulo;
-    {
+    if (spd_profile::enabled(SPD_STAGE_GATEUP)) {
         spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
         SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
     }
@@ -1273,7 +1309,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             }
         }
     };
-    {
+    if (spd_profile::enabled(SPD_STAGE_DOWN)) {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
         if (do_fuse) {
             EpiDownT<true> e2;
