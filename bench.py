@@ -27,8 +27,12 @@ import numpy as np
 
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (summaries and the copy-kernel calibration are under profiles/); None = not measured
-MEASURED_TRAFFIC = {}
+# this script (summaries and the copy-kernel calibration are under profiles/); None = not measured.
+# FETCH_SIZE counts 2 KiB per unit on this device (a 1 GiB copy reads 524300), WRITE_SIZE 1 KiB.
+MEASURED_TRAFFIC = {
+    "llama2-70b-tp8-decode-b16-ctx4096": (59513 * 2 + 224) * 1024,        # 122.1 MB vs 117.9 MB algorithmic
+    "llama2-70b-tp8-prefill-b4x2048": (1078690 * 2 + 57344) * 1024,       # 2.27 GB: tiles re-read past the L2
+}
 
 
 def log(*a):
