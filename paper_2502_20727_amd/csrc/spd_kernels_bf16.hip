@@ -452,12 +452,11 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         }
     };
 
-    // full batches are taken in an order rotated by the pair index, so that the workgroups that
-    // run side by side do not all ask the L2 for the same activation lines at the same time
+    // every wave walks its share of K front to back (measured: any other order, e.g. one rotated
+    // per workgroup to spread the activation reads, costs a fifth of the streaming rate)
     const int nfull = (k1 - k0) / U;
-    const int rot = nfull > 0 ? pair % nfull : 0;
     GemvBatch<U, SPLIT> cur;
-    if (nfull > 0) load(cur, k0 + rot * U);
+    if (nfull > 0) load(cur, k0);
 
     // loads that do not depend on the stream: the epilogue's inputs (first wave) and this wave's
     // share of the sum-of-squares partials, issued while the first weights are on their way
@@ -473,11 +472,7 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
     // two register buffers, used alternately: the loads of one batch are in flight while the other
     // batch feeds the MFMAs
     GemvBatch<U, SPLIT> oth;
-    auto batch_k = [&](int i) {
-        int bi = i + rot;
-        if (bi >= nfull) bi -= nfull;
-        return k0 + bi * U;
-    };
+    auto batch_k = [&](int i) { return k0 + i * U; };
     int i = 0;
     for (; i + 2 < nfull; i += 2) {      // steady state: no branch between the loads and their use
         load(oth, batch_k(i + 1));
