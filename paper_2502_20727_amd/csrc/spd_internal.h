@@ -30,6 +30,7 @@
 constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
 constexpr int SPD_N_COUNTERS = 8192;
+constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
 
 SPD_HD size_t spd_frag_index(int tile, int ktile, int n_ktiles) {

@@ -215,6 +215,54 @@ struct EpiQKV {
     }
 };
 
+// QKV projection of a decode step whose K is cut into slices: norm scale and rotation are linear,
+// so every slice applies them to its own partial sums and parks the result, fp32, in
+// part[slice][token][column] (columns in natural order: head * d + j).  The attention kernel adds
+// the slices in ascending order, rounds, and appends the new key and value to the cache.
+struct EpiQKVPart {
+    static constexpr bool kNeedsRs = true;
+    int M, q, kv, d, h, nqkv, nch, m_pad;
+    float eps;
+    const float *ss, *cosT, *sinT;
+    float *part;
+    spd_positions P;
+    typedef EpiQKV::Pre Pre;
+
+    __device__ __forceinline__ Pre pre(int pair, int, int lane) const {
+        Pre p;
+        p.c = p.s = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int m = lane & 15, g = lane >> 4;
+        const int tph = d >> 4, half = d >> 1;
+        const int head = (2 * pair) / tph;
+        if (m < M && head < q + kv) {
+            const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;
+            p.c = *(const float4 *)(cosT + (size_t)P.pos[m] * half + ca);
+            p.s = *(const float4 *)(sinT + (size_t)P.pos[m] * half + ca);
+        }
+        return p;
+    }
+
+    __device__ __forceinline__ void slice(int pair, int ks, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
+        const int m = lane & 15, g = lane >> 4;
+        if (m >= M) return;
+        const int tph = d >> 4;
+        const int head = (2 * pair) / tph;
+        const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) + 4 * g;
+        const int cb = spd_qkv_tile_col0(2 * pair + 1, q, kv, d) + 4 * g;
+        a *= rs;
+        b *= rs;
+        float4 lo = make_float4(a[0], a[1], a[2], a[3]), hi = make_float4(b[0], b[1], b[2], b[3]);
+        if (head < q + kv) {
+            const float4 c = p.c, s = p.s;
+            lo = make_float4(a[0] * c.x - b[0] * s.x, a[1] * c.y - b[1] * s.y, a[2] * c.z - b[2] * s.z, a[3] * c.w - b[3] * s.w);
+            hi = make_float4(b[0] * c.x + a[0] * s.x, b[1] * c.y + a[1] * s.y, b[2] * c.z + a[2] * s.z, b[3] * c.w + a[3] * s.w);
+        }
+        float *dst = part + ((size_t)ks * 16 + m) * nqkv;
+        *(float4 *)(dst + ca) = lo;
+        *(float4 *)(dst + cb) = hi;
+    }
+};
+
 struct EpiO {
     static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
@@ -409,14 +457,16 @@ struct EpiDownT {
 // registers in batches of U k-tiles, the next batch in flight while the current one feeds the
 // MFMAs.  The waves' partial tiles are added through LDS in wave order.  With KS = 1 the first
 // wave then runs the epilogue; with KS > 1 (PARTIAL) the workgroup parks its tile in `kpart`
-// and k_gemv_finish adds the KS tiles in slice order: sums never depend on timing.
+// and k_gemv_finish adds the KS tiles in slice order: sums never depend on timing.  MODE 2 is
+// for epilogues that are linear in the accumulators: every slice runs Epi::slice() on its own
+// partial sums and the consumer of the result adds the slices.
 // ------------------------------------------------------------------------------------------
 template <int U, bool SPLIT>
 struct GemvBatch {
     bf16x8 fa[U], fb[U], fh[U], fl[SPLIT ? U : 1];
 };
 
-template <int W, int U, bool SPLIT, bool PARTIAL, class Epi>
+template <int W, int U, bool SPLIT, int MODE, class Epi>     // MODE 0: whole K, 1: slices -> kpart, 2: slices -> Epi::slice
 __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
                                                   const __bf16 *__restrict__ Xlo, int KT, int KS,
                                                   float *__restrict__ kpart, Epi epi) {
@@ -462,6 +512,7 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
     // share of the sum-of-squares partials, issued while the first weights are on their way
     typename Epi::Pre pre;
     float ssp = 0.f;
+    constexpr bool PARTIAL = MODE == 1;
     if (!PARTIAL) {
         if (wave == 0) pre = epi.pre(pair, 0, lane);
         if constexpr (Epi::kNeedsRs) {
@@ -528,7 +579,8 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         sq += shfl_xor_f(sq, 32);
         rs = 1.0f / sqrtf(sq / (float)epi.h + epi.eps);
     }
-    epi(pair, 0, a, b, lane, rs, pre);
+    if constexpr (MODE == 2) epi.slice(pair, ks, a, b, lane, rs, pre);
+    else epi(pair, 0, a, b, lane, rs, pre);
 }
 
 // Adds the KS partial tiles of a pair in slice order and runs the epilogue.  grid = pairs,
@@ -888,41 +940,156 @@ __device__ __forceinline__ void load_q(bf16x8 *qf, const __bf16 *__restrict__ qb
 // while the current one is processed; the workgroup writes one partial (unnormalised O^T,
 // running max, running sum) per split.
 // partial layout: [seq][kvh][split][(d + 2) * 16] floats: O^T[d][16], m[16], l[16]
-template <int DT>
-__global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
-                                                     const __bf16 *__restrict__ vc, float *__restrict__ part, spd_positions P,
-                                                     int q, int kv, int max_ctx, int n_splits) {
+//
+// FUSED: the QKV projection ran in K slices and left fp32 partial rows qkvp[slice][token][nqkv]
+// (EpiQKVPart).  Every workgroup adds the slices of its queries (ascending order), keeps them as
+// hi + lo bf16 pairs; the cache then holds the P.pos[b] earlier positions only, and the
+// workgroup of the last split adds the new token: it sums its key and value, rounds them to the
+// cache's bf16, appends them to the cache and attends to them as one more (single-key) block.
+template <int DT, bool FUSED>
+__global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ qbuf_in, const __bf16 *__restrict__ qlo_in,
+                                                     const float *__restrict__ qkvp, int KS, int nqkv, __bf16 *__restrict__ qbuf_out,
+                                                     __bf16 *__restrict__ qlo_out, __bf16 *__restrict__ kc, __bf16 *__restrict__ vc,
+                                                     float *__restrict__ part, spd_positions P, int q, int kv, int max_ctx,
+                                                     int n_splits) {
     constexpr int d = DT * 16;
     __shared__ float sm[4][(DT * 16 + 2) * 16];
+    __shared__ __attribute__((aligned(16))) __bf16 sq[2][16 * d];      // hi / lo queries of the group's heads
+    __shared__ __attribute__((aligned(16))) __bf16 snew[2][d];         // new key, new value
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int group = q / kv, qd = q * d;
-    const int n_keys = P.pos[b] + 1;
+    const int n_keys = FUSED ? P.pos[b] : P.pos[b] + 1;       // keys in the cache
     const int nblk = (n_keys + 31) >> 5;
     const int b0 = (int)(((long)split * nblk) / n_splits), b1 = (int)(((long)(split + 1) * nblk) / n_splits);
     const int col = lane & 15, g = lane >> 4;
     const bool cvalid = col < group;
-    const __bf16 *kbase = kc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
-    const __bf16 *vbase = vc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
+    const bool newtok = FUSED && split == n_splits - 1;
+    __bf16 *kbase = kc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
+    __bf16 *vbase = vc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
     AttnState<DT> st;
 #pragma unroll
     for (int i = 0; i < DT; ++i) st.o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     st.m = -INFINITY;
     st.l = 0.f;
     const float scale = 1.0f / sqrtf((float)d);
-    if (b0 + wave < b1) {
-        bf16x8 qf[DT];
-        load_q<DT>(qf, qbuf, qlo, b, kvh * group + col, qd, d, cvalid, lane);
+    const bool has_blocks = b0 + wave < b1;
+    // FUSED: thread -> items of 4 consecutive columns of the group's queries (group * d / 4 items); in
+    // the workgroup of the last split the first d / 2 threads also take the new key and the new value.
+    // The slices of all items are requested first, then the first two key blocks; the sums are
+    // formed while the key blocks are on their way.  All these loads are unconditional (indices are
+    // clamped instead), so that nothing waits between them.
+    constexpr int NQS = (16 * d / 4 + 255) / 256, MAXKS = SPD_MAX_QKV_SLICES;
+    const int nq4 = group * d / 4, nk4 = d / 4;
+    float4 qs[NQS][MAXKS], ns[MAXKS];
+    if constexpr (FUSED) {
+#pragma unroll
+        for (int sl = 0; sl < NQS; ++sl) {
+            if (256 * sl >= nq4) break;                                   // uniform
+            const int e = min((int)threadIdx.x + 256 * sl, nq4 - 1);
+            const float *src = qkvp + (size_t)b * nqkv + kvh * group * d + 4 * e;
+#pragma unroll
+            for (int j = 0; j < MAXKS; ++j) qs[sl][j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * 16 * nqkv);
+        }
+        if (newtok) {                                                     // uniform
+            const int e = min((int)threadIdx.x, 2 * nk4 - 1);
+            const int colq = e < nk4 ? qd + kvh * d + 4 * e : qd + kv * d + kvh * d + 4 * (e - nk4);
+            const float *src = qkvp + (size_t)b * nqkv + colq;
+#pragma unroll
+            for (int j = 0; j < MAXKS; ++j) ns[j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * 16 * nqkv);
+        }
+    }
+    // (a wave without blocks loads a block it will not use: one code path, no waiting at a join)
+    KVFrags<DT> f0, f1;
+    {
+        const int last = nblk > 0 ? nblk - 1 : 0;          // the cache holds at least one block
+        const int vb = min(b0 + wave, last), vb2 = vb + 4 < b1 ? vb + 4 : vb;
+        load_kv<DT>(f0, kbase, vbase, vb, d, lane);
+        load_kv<DT>(f1, kbase, vbase, vb2, d, lane);
+    }
+    bf16x8 qf[DT];
+    if constexpr (FUSED) {
+        auto add_slices = [&](const float4 *v) {
+            float4 acc = v[0];
+#pragma unroll
+            for (int j = 1; j < MAXKS; ++j) {
+                const float on = j < KS ? 1.f : 0.f;      // a clamped repeat of the last slice counts for nothing
+                acc.x += on * v[j].x; acc.y += on * v[j].y; acc.z += on * v[j].z; acc.w += on * v[j].w;
+            }
+            return acc;
+        };
+#pragma unroll
+        for (int sl = 0; sl < NQS; ++sl) {
+            if (256 * sl >= nq4) break;
+            const int e = threadIdx.x + 256 * sl;
+            const float4 acc = add_slices(qs[sl]);
+            const bf16x4 hi = cvt4(acc.x, acc.y, acc.z, acc.w);
+            const bf16x4 lo = cvt4_lo(acc.x, acc.y, acc.z, acc.w, hi);
+            if (e < nq4) {
+                *(bf16x4 *)(&sq[0][4 * e]) = hi;
+                *(bf16x4 *)(&sq[1][4 * e]) = lo;
+                if (newtok) {        // the rotated queries stay readable in the workspace
+                    *(bf16x4 *)(qbuf_out + (size_t)b * qd + kvh * group * d + 4 * e) = hi;
+                    *(bf16x4 *)(qlo_out + (size_t)b * qd + kvh * group * d + 4 * e) = lo;
+                }
+            }
+        }
+        if (newtok) {
+            const int e = threadIdx.x;
+            const float4 acc = add_slices(ns);
+            const bf16x4 hi = cvt4(acc.x, acc.y, acc.z, acc.w);
+            if (e < nk4) {
+                *(bf16x4 *)(&snew[0][4 * e]) = hi;
+                *(bf16x4 *)(kbase + spd_kcache_off(P.pos[b], 4 * e, d)) = hi;
+            } else if (e < 2 * nk4) {
+                const int dc = 4 * (e - nk4);
+                *(bf16x4 *)(&snew[1][dc]) = hi;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vbase[spd_vcache_off(P.pos[b], dc + i, d)] = hi[i];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < DT / 2; ++t) {
+            if (cvalid) {
+                qf[t] = *(const bf16x8 *)(&sq[0][col * d + t * 32 + g * 8]);
+                qf[DT / 2 + t] = *(const bf16x8 *)(&sq[1][col * d + t * 32 + g * 8]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qf[t][i] = qf[DT / 2 + t][i] = (__bf16)0.f;
+            }
+        }
+    } else {
+        load_q<DT>(qf, qbuf_in, qlo_in, b, kvh * group + col, qd, d, cvalid, lane);
+    }
+    if (has_blocks) {
         // two key blocks at a time, both loaded before the first is used (no branch in between, so
         // that the second block's loads stay in flight while the first block is processed)
         for (int vb = b0 + wave; vb < b1; vb += 8) {
             const int vb2 = vb + 4 < b1 ? vb + 4 : vb;      // clamp: a repeated block is masked below
-            KVFrags<DT> f0, f1;
-            load_kv<DT>(f0, kbase, vbase, vb, d, lane);
-            load_kv<DT>(f1, kbase, vbase, vb2, d, lane);
+            if (vb != b0 + wave) {
+                load_kv<DT>(f0, kbase, vbase, vb, d, lane);
+                load_kv<DT>(f1, kbase, vbase, vb2, d, lane);
+            }
             attn_block<DT>(st, qf, f0, vb, cvalid ? n_keys : 0, scale, lane);
             attn_block<DT>(st, qf, f1, vb2, (cvalid && vb + 4 < b1) ? n_keys : 0, scale, lane);
         }
+    }
+    if (newtok && wave == 0) {
+        // the new token as a block whose only key is key 0: K row 0, V contraction slot 0
+        KVFrags<DT> fn;
+        const bf16x8 zero = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+#pragma unroll
+        for (int t = 0; t < DT / 2; ++t) {
+            fn.k0[t] = col == 0 ? *(const bf16x8 *)(&snew[0][t * 32 + g * 8]) : zero;
+            fn.k1[t] = zero;
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            fn.v[dt] = zero;
+            if (g == 0) fn.v[dt][0] = snew[1][dt * 16 + col];
+        }
+        attn_block<DT>(st, qf, fn, 0, cvalid ? 1 : 0, scale, lane);
     }
     // merge the four waves
     float *my = sm[wave];
@@ -1094,6 +1261,18 @@ inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b);
         if (e_ != hipSuccess) return e_; \
     } while (0)
 
+// Number of K slices of a weight-streaming launch: 1 when there are enough pairs of n-tiles to
+// occupy the chip, otherwise about two workgroups of 8 waves per compute unit.
+constexpr int GEMV_SLICE_W = 8;
+inline int gemv_slices(int n_pairs, int KT) {
+    if (n_pairs >= 192) return 1;
+    int KS = (512 + n_pairs - 1) / n_pairs;
+    const int ks_max = KT / (2 * GEMV_SLICE_W) > 0 ? KT / (2 * GEMV_SLICE_W) : 1;         // at least two k-tiles per wave
+    if (KS > ks_max) KS = ks_max;
+    while ((size_t)n_pairs * KS > (size_t)SPD_MAX_KPART && KS > 1) --KS;
+    return KS;
+}
+
 // Launch shape of a projection.  At most 16 tokens: the weight-streaming kernel, one workgroup
 // per pair of n-tiles when there are enough pairs to occupy the chip, otherwise K is also cut
 // into KS slices (about two workgroups per compute unit) and a second small kernel adds them.
@@ -1106,30 +1285,42 @@ hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, c
         // enough pairs to occupy the chip: one workgroup per pair, no slices
         if (KT >= 64) {
             constexpr int W = 16, U = 2;     // 16 waves share 512 VGPRs per lane and SIMD: two batches of 2 k-tiles fit
-            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
+            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
                                1, kpart, epi);
         } else {
             constexpr int W = 8, U = 2;
-            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
+            hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
                                1, kpart, epi);
         }
         return hipGetLastError();
     }
-    constexpr int W = 8, U = 2;
-    int KS = (512 + n_pairs - 1) / n_pairs;
-    const int ks_max = KT / (2 * W) > 0 ? KT / (2 * W) : 1;         // at least two k-tiles per wave
-    if (KS > ks_max) KS = ks_max;
-    while ((size_t)n_pairs * KS > (size_t)SPD_MAX_KPART && KS > 1) --KS;
+    constexpr int W = GEMV_SLICE_W, U = 2;
+    const int KS = gemv_slices(n_pairs, KT);
     if (KS <= 1) {
-        hipLaunchKernelGGL((k_gemv<W, U, SPLIT, false, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
+        hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
                            kpart, epi);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL((k_gemv<W, U, SPLIT, true, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+    hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 1, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
                        kpart, epi);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((k_gemv_finish<Epi>), dim3(n_pairs), dim3(256), 0, c.s, kpart, KS, epi);
+    return hipGetLastError();
+}
+
+// K-sliced launch for an epilogue that is linear in the accumulators (Epi::slice); no second kernel
+template <class Epi>
+hipError_t launch_gemv_sliced(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs,
+                              int KT, int KS, const Epi &epi) {
+    constexpr int W = GEMV_SLICE_W, U = 2;
+    const __bf16 *Xlo = Xhi + plane;
+    if (split)
+        hipLaunchKernelGGL((k_gemv<W, U, true, 2, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+                           (float *)nullptr, epi);
+    else
+        hipLaunchKernelGGL((k_gemv<W, U, false, 2, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
+                           (float *)nullptr, epi);
     return hipGetLastError();
 }
 
@@ -1185,15 +1376,40 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     __bf16 *kc = (__bf16 *)kvc, *vc = (__bf16 *)(kvc + D.kv_v);
     float *ybuf = (float *)(c.ws + D.ws_y);
 
-    EpiQKV e1;
-    e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
-    e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
-    e1.ss = (const float *)(c.ws + D.ws_ss1);
-    e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
-    e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
-    if (spd_profile::enabled(SPD_STAGE_QKV)) {
-        spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-        SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
+    // a decode step whose QKV projection needs K slices hands the slices to the attention kernel
+    // (no second kernel to add them up); every other shape finishes Q, K and V in the projection
+    int qkv_slices = (c.q_len == 1 && M <= 16) ? gemv_slices(D.nqkv / 32, D.h / 32) : 1;
+    const bool fused_q = qkv_slices > 1;
+    if (fused_q) {      // about 320 workgroups of 8 waves, at most SPD_MAX_QKV_SLICES slices
+        const int want = (320 + D.nqkv / 32 - 1) / (D.nqkv / 32);
+        qkv_slices = want < 2 ? 2 : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
+        if (qkv_slices > D.h / 32 / GEMV_SLICE_W) qkv_slices = D.h / 32 / GEMV_SLICE_W;
+        if (qkv_slices < 2) qkv_slices = 2;
+    }
+    float *qkvp = (float *)(c.ws + D.ws_kpart);
+    if (fused_q) {
+        EpiQKVPart e1;
+        e1.M = M; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
+        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
+        e1.ss = (const float *)(c.ws + D.ws_ss1);
+        e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.part = qkvp; e1.P = c.pos;
+        if (spd_profile::enabled(SPD_STAGE_QKV)) {
+            spd_profile::scope prof(SPD_STAGE_QKV, c.s);
+            SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32,
+                                       qkv_slices, e1));
+        }
+    } else {
+        EpiQKV e1;
+        e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
+        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
+        e1.ss = (const float *)(c.ws + D.ws_ss1);
+        e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
+        if (spd_profile::enabled(SPD_STAGE_QKV)) {
+            spd_profile::scope prof(SPD_STAGE_QKV, c.s);
+            SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
+        }
     }
 
     const int DT = D.d / 16;
@@ -1208,9 +1424,14 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         if (splits > SPD_MAX_SPLITS) splits = SPD_MAX_SPLITS;
         float *part = (float *)(c.ws + D.ws_apart);
         const dim3 grid(splits, D.kv, c.batch);
-#define SPD_DECODE(DTV)                                                                                          \
-    hipLaunchKernelGGL((k_attn_decode<DTV>), grid, dim3(256), 0, c.s, qbuf, qlo, kc, vc, part, c.pos, D.q, D.kv, D.max_ctx, \
-                       splits)
+#define SPD_DECODE(DTV)                                                                                              \
+    if (fused_q)                                                                                                     \
+        hipLaunchKernelGGL((k_attn_decode<DTV, true>), grid, dim3(256), 0, c.s, (const __bf16 *)nullptr,             \
+                           (const __bf16 *)nullptr, qkvp, qkv_slices, D.nqkv, qbuf, qlo, kc, vc, part, c.pos, D.q, D.kv, \
+                           D.max_ctx, splits);                                                                       \
+    else                                                                                                             \
+        hipLaunchKernelGGL((k_attn_decode<DTV, false>), grid, dim3(256), 0, c.s, qbuf, qlo, (const float *)nullptr, 1,   \
+                           D.nqkv, (__bf16 *)nullptr, (__bf16 *)nullptr, kc, vc, part, c.pos, D.q, D.kv, D.max_ctx, splits)
         switch (DT) {
             case 2: SPD_DECODE(2); break;
             case 4: SPD_DECODE(4); break;
