@@ -74,6 +74,22 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     D.w_g = o; o = spd_align256(o + h * f * es);
     D.w_u = o; o = spd_align256(o + h * f * es);     // bf16: second half of the interleaved gate/up block
     D.w_d = o; o = spd_align256(o + f * h * es);
+    // Decode streams the gate/up weights with one workgroup per group of FFN columns.  When the
+    // 16-column tiles of the block above do not fill a whole number of rounds of the chip's 256
+    // compute units, a second copy with narrower groups (c < 16 columns) is kept for decode so
+    // that they do: group p holds, for every k-tile, the c gate rows then the c up rows of the
+    // columns [c p, c p + c), 16 bytes (8 contraction elements) per row and quarter of the k-tile.
+    if (bf) {
+        const int pairs = D.f_pad / 16;
+        const int want = 256 * ((pairs + 255) / 256);
+        const int c = (D.f_pad + want - 1) / want;
+        if (pairs >= 192 && want != pairs && c < 16) {
+            D.gud_cols = c;
+            D.gud_groups = (D.f_pad + c - 1) / c;
+            D.w_gud = o;
+            o = spd_align256(o + (size_t)D.gud_groups * (h / 32) * 2 * 64 * c);
+        }
+    }
     D.weight_bytes = o;
 
     const size_t kvn = (size_t)D.max_batch * D.kv * D.max_ctx * D.d;
@@ -282,6 +298,25 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
         if (c >= f) return 0.0f;
         return (nt & 1) ? w->wu[(size_t)k * w->ld_u + c] : w->wg[(size_t)k * w->ld_g + c];
     });
+    if (D.gud_cols) {
+        const int c = D.gud_cols, KT = h / 32;
+        std::vector<int> bad(D.gud_groups, 0);
+        parallel_for(D.gud_groups, [&](int p) {
+            for (int kt = 0; kt < KT; ++kt)
+                for (int t = 0; t < 2; ++t) {
+                    uint16_t *fr = (uint16_t *)(base + D.w_gud) + (((size_t)p * KT + kt) * 2 + t) * (size_t)(32 * c);
+                    for (int g = 0; g < 4; ++g)
+                        for (int r = 0; r < c; ++r)
+                            for (int j = 0; j < 8; ++j) {
+                                const int col = p * c + r, k = kt * 32 + g * 8 + j;
+                                const float v = col >= f ? 0.0f : (t ? w->wu[(size_t)k * w->ld_u + col] : w->wg[(size_t)k * w->ld_g + col]);
+                                if (!to_bf16_exact(v, &fr[(g * c + r) * 8 + j])) bad[p] = 1;
+                            }
+                }
+        });
+        for (int b : bad)
+            if (b) ok = false;
+    }
     // down: contraction = the rank's FFN slice (zero rows where padded)
     ok &= pack_frags((uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r) {
         return k < f ? w->wd[(size_t)k * w->ld_d + nt * 16 + r] : 0.0f;

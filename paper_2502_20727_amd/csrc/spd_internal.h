@@ -71,6 +71,8 @@ SPD_HD size_t spd_vcache_off(int pos, int dcol, int d) {
 // ------------------------------------------------------------------------------------------
 struct spd_dims {
     int h, q, kv, d, f, f_pad, group, nqkv, tp, dtype;
+    int gud_cols, gud_groups;     // decode-only gate/up copy: FFN columns per workgroup and number of groups (0: none)
+    size_t w_gud;                 // its offset in a layer's packed weights
     int max_batch, max_ctx, max_tokens, m_pad;
     float eps, rope_base;
     // packed shard (bytes from its start)

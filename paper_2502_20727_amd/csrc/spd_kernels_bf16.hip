@@ -332,6 +332,7 @@ struct EpiO {
 struct EpiGU {
     static constexpr bool kNeedsRs = true;
     int M, h, f_pad, nch, m_pad;
+    int cols = 16;             // FFN columns per group: 16, or fewer for the decode-only narrow groups
     float eps;
     const float *ss;
     __bf16 *uhat, *ulo;        // ulo may be NULL
@@ -350,6 +351,20 @@ struct EpiGU {
             }
         }
         const bf16x4 u = cvt4(o[0], o[1], o[2], o[3]);
+        if (cols != 16) {
+            // narrow group: rows 4g .. 4g+3 are FFN columns cols*pair + 4g + i, stored one by one
+            const bf16x4 lo = cvt4_lo(o[0], o[1], o[2], o[3], u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int col = pair * cols + 4 * g + i;
+                if (4 * g + i < cols && col < f_pad) {
+                    const size_t fo = spd_frag_index(mt, col >> 5, f_pad >> 5) + spd_frag_elem(r, col & 31);
+                    uhat[fo] = u[i];
+                    if (ulo) ulo[fo] = lo[i];
+                }
+            }
+            return;
+        }
         // gate/up pair p covers FFN columns [16p, 16p+16): half of k-tile p/2 of the down projection
         const size_t fo = spd_frag_index(mt, pair >> 1, f_pad >> 5) + spd_frag_elem(r, 16 * (pair & 1) + 4 * g);
         *(bf16x4 *)(uhat + fo) = u;
@@ -469,23 +484,37 @@ struct GemvBatch {
 template <int W, int U, bool SPLIT, int MODE, class Epi>     // MODE 0: whole K, 1: slices -> kpart, 2: slices -> Epi::slice
 __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
                                                   const __bf16 *__restrict__ Xlo, int KT, int KS,
-                                                  float *__restrict__ kpart, Epi epi) {
+                                                  float *__restrict__ kpart, int rows, Epi epi) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int pair = blockIdx.x, ks = blockIdx.y;
     const int kb0 = (int)(((long)ks * KT) / KS), kb1 = (int)(((long)(ks + 1) * KT) / KS);
     const int nk = kb1 - kb0;
     const int k0 = kb0 + (wave * nk) / W, k1 = kb0 + ((wave + 1) * nk) / W;
     f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-    const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
-    const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
+    // rows == 16: two n-tiles of 1 KiB fragments.  rows < 16 (narrow groups of the decode-only
+    // gate/up copy): per k-tile `rows` rows of the first tile then `rows` rows of the second, 16
+    // bytes per row and quarter of the k-tile; the lanes of the missing rows repeat the last row
+    // (same cache lines; the epilogue does not store them).
+    const bf16x8 *wa, *wb;
+    size_t kstr;        // distance between k-tiles, in 16-byte units
+    if (rows == 16) {
+        wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
+        wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
+        kstr = 64;
+    } else {
+        const int rr = (lane & 15) < rows ? (lane & 15) : rows - 1;
+        wa = (const bf16x8 *)Wp + (size_t)pair * KT * 8 * rows + (lane >> 4) * rows + rr;
+        wb = wa + 4 * rows;
+        kstr = 8 * rows;
+    }
     const bf16x8 *xh = (const bf16x8 *)Xhi + lane;
     const bf16x8 *xl = (const bf16x8 *)Xlo + lane;
 
     auto load = [&](GemvBatch<U, SPLIT> &B, int kt) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            B.fa[u] = __builtin_nontemporal_load(wa + (size_t)(kt + u) * 64);
-            B.fb[u] = __builtin_nontemporal_load(wb + (size_t)(kt + u) * 64);
+            B.fa[u] = __builtin_nontemporal_load(wa + (size_t)(kt + u) * kstr);
+            B.fb[u] = __builtin_nontemporal_load(wb + (size_t)(kt + u) * kstr);
             B.fh[u] = xh[(size_t)(kt + u) * 64];
             if (SPLIT) B.fl[u] = xl[(size_t)(kt + u) * 64];
         }
@@ -539,8 +568,8 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         consume(cur);
     }
     for (int kt = k0 + nfull * U; kt < k1; ++kt) {
-        const bf16x8 fa = __builtin_nontemporal_load(wa + (size_t)kt * 64);
-        const bf16x8 fb = __builtin_nontemporal_load(wb + (size_t)kt * 64);
+        const bf16x8 fa = __builtin_nontemporal_load(wa + (size_t)kt * kstr);
+        const bf16x8 fb = __builtin_nontemporal_load(wb + (size_t)kt * kstr);
         const bf16x8 fh = xh[(size_t)kt * 64];
         a = MFMA(fa, fh, a);
         b = MFMA(fb, fh, b);
@@ -1278,7 +1307,7 @@ inline int gemv_slices(int n_pairs, int KT) {
 // into KS slices (about two workgroups per compute unit) and a second small kernel adds them.
 template <bool SPLIT, class Epi>
 hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, const __bf16 *Xlo, int n_pairs, int KT,
-                       const Epi &epi) {
+                       const Epi &epi, int rows = 16) {
     const spd_dims &D = *c.D;
     float *kpart = (float *)(c.ws + D.ws_kpart);
     if (n_pairs >= 192) {
@@ -1286,11 +1315,11 @@ hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, c
         if (KT >= 64) {
             constexpr int W = 16, U = 2;     // 16 waves share 512 VGPRs per lane and SIMD: two batches of 2 k-tiles fit
             hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
-                               1, kpart, epi);
+                               1, kpart, rows, epi);
         } else {
             constexpr int W = 8, U = 2;
             hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
-                               1, kpart, epi);
+                               1, kpart, rows, epi);
         }
         return hipGetLastError();
     }
@@ -1298,11 +1327,11 @@ hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, c
     const int KS = gemv_slices(n_pairs, KT);
     if (KS <= 1) {
         hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, 1,
-                           kpart, epi);
+                           kpart, rows, epi);
         return hipGetLastError();
     }
     hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 1, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
-                       kpart, epi);
+                       kpart, rows, epi);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((k_gemv_finish<Epi>), dim3(n_pairs), dim3(256), 0, c.s, kpart, KS, epi);
@@ -1317,10 +1346,10 @@ hipError_t launch_gemv_sliced(const spd_call &c, bool split, const __bf16 *Wp, c
     const __bf16 *Xlo = Xhi + plane;
     if (split)
         hipLaunchKernelGGL((k_gemv<W, U, true, 2, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
-                           (float *)nullptr, epi);
+                           (float *)nullptr, 16, epi);
     else
         hipLaunchKernelGGL((k_gemv<W, U, false, 2, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
-                           (float *)nullptr, epi);
+                           (float *)nullptr, 16, epi);
     return hipGetLastError();
 }
 
@@ -1506,7 +1535,15 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     e1.uhat = uhat; e1.ulo = ulo;
     if (spd_profile::enabled(SPD_STAGE_GATEUP)) {
         spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
-        SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+        if (D.gud_cols && M <= 16) {
+            // decode: the copy with narrow column groups, one workgroup per group
+            e1.cols = D.gud_cols;
+            const __bf16 *wd = (const __bf16 *)(w + D.w_gud), *xlo = xhat + D.pl_x;
+            SPD_TRY(c.split ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
+                            : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
+        } else {
+            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+        }
     }
 
     const bool do_fuse = fuse && M <= 16;

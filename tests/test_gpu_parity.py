@@ -135,7 +135,13 @@ SMALL_MHA = Workload(name="small-bf16-mha", hidden=128, n_q_heads=4, n_kv_heads=
                      n_layers=1, tp=2, dtype=BF16, seed=12, batch=2, q_len=1, ctx=64, mask=(1,))
 
 
-@pytest.mark.parametrize("w", [SMALL, SMALL_MHA], ids=lambda w: w.name)
+# 3200 FFN columns per rank: 200 tiles of 16 do not fill the chip evenly, so decode-sized calls read the
+# copy of the gate/up weights with 13-column groups (247 groups, the last one with 2 real columns)
+NARROW_GU = Workload(name="narrow-gate-up", hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=6400, n_layers=1,
+                     tp=2, dtype=BF16, seed=14, batch=3, q_len=1, ctx=64, mask=(1,))
+
+
+@pytest.mark.parametrize("w", [SMALL, SMALL_MHA, NARROW_GU], ids=lambda w: w.name)
 @pytest.mark.parametrize("batch,q_len,positions", [
     (3, 1, [0, 17, 40]),          # decode, ragged contexts, one sequence with a single key
     (2, 7, [0, 5]),               # 14 tokens: a partial m-tile

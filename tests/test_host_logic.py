@@ -166,6 +166,33 @@ def test_pack_every_value_lands_exactly_once():
     B.spd_destroy(ctx)
 
 
+def test_pack_keeps_a_second_gate_up_copy_when_tiles_do_not_fill_the_chip():
+    # 3200 FFN columns = 200 tiles of 16: decode reads a copy regrouped into 13-column groups, so
+    # every gate/up value is stored exactly twice and everything else once
+    w = workloads.Workload(name="narrow", hidden=64, n_q_heads=2, n_kv_heads=2, head_dim=32, ffn=3200, n_layers=1,
+                           tp=1, dtype=workloads.BF16, seed=3, batch=1, q_len=1, ctx=32, mask=(1,))
+    ctx = B.spd_create(B.make_config(w))
+    shard = inputs.layer_shard(w, 0, 0)
+    n = 0
+    for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+        a = shard[k]
+        a[...] = (np.arange(n, n + a.size, dtype=np.int64) % 251 + 1).reshape(a.shape).astype(np.float32)
+        n += a.size
+    packed = B.spd_pack_shard_local(ctx, shard)
+    assert packed.size == B.spd_get_sizes(ctx).weight_bytes
+    vals = packed[2 * 256:].view(np.uint16)                           # skip the two fp32 gain vectors (64 floats, padded)
+    as_f32 = (vals.astype(np.uint32) << 16).view(np.float32)
+    got = np.bincount(as_f32.astype(np.int64), minlength=252)
+    want = np.zeros(252, dtype=np.int64)
+    for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+        want += np.bincount(shard[k].astype(np.int64).ravel(), minlength=252) * (2 if k in ("wg", "wu") else 1)
+    assert np.array_equal(got[1:], want[1:])
+    back = B.spd_unpack_shard(ctx, packed, {k: v.shape for k, v in shard.items()})
+    for k in ("wg", "wu", "wd"):
+        assert np.array_equal(back[k], shard[k]), k
+    B.spd_destroy(ctx)
+
+
 def test_pack_rejects_values_that_are_not_bf16():
     w = SMALL_BF16
     ctx = B.spd_create(B.make_config(w))
