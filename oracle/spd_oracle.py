@@ -36,6 +36,7 @@ The paper prints no worked numeric example of a block output, and its perplexiti
 """
 from __future__ import annotations
 
+import math
 from dataclasses import dataclass
 from typing import Dict, List, Optional, Sequence
 
@@ -303,3 +304,39 @@ def rank_sum(base: Optional[np.ndarray], slots: np.ndarray) -> np.ndarray:
     """What a kept sync point delivers to every device: base + sum over ranks of the partials."""
     s = np.sum(np.asarray(slots, F64), axis=0)
     return s if base is None else np.asarray(base, F64) + s
+
+
+# --------------------------------------------------------------------------- which blocks drop their sync point
+
+TIER_TP, TIER_ISB, TIER_SB, TIER_ESB = 0, 1, 2, 3
+
+
+def mask_from_sensitivity(S: Sequence[float], n_spd: int, tau1: float, tau2: float):
+    """Sync-point drop by sensitivity (Alg. 1, Sec. 4.2).
+
+    The blocks are ranked by ascending sync sensitivity S; the first n_spd of the ranking
+    become SPD blocks.  Each of them is put in a tier by its sensitivity: in-sensitive
+    (S <= tau1: SPD alone), sensitive (S <= tau2: SPD after block-to-block distillation),
+    extremely sensitive (otherwise: head grouping as well).  Blocks outside the budget keep
+    their sync point.  Equal sensitivities: the paper does not say; the block with the lower
+    index ranks first.
+
+    Returns (mask, tier): mask[l] = 1 iff block l drops its attention sync point."""
+    L = len(S)
+    if not 0 <= n_spd <= L:
+        raise ValueError("n_spd out of range")
+    if any(math.isnan(float(v)) for v in S) or math.isnan(tau1) or math.isnan(tau2):
+        raise ValueError("NaN")
+    B = sorted(range(L), key=lambda l: (float(S[l]), l))
+    mask = [0] * L
+    tier = [TIER_TP] * L
+    for i in range(n_spd):
+        blk = B[i]
+        mask[blk] = 1
+        if S[blk] <= tau1:
+            tier[blk] = TIER_ISB
+        elif S[blk] <= tau2:
+            tier[blk] = TIER_SB
+        else:
+            tier[blk] = TIER_ESB
+    return mask, tier

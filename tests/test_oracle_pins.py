@@ -446,3 +446,66 @@ def test_bf16_cache_storage_rounds_once_at_the_store():
     np.testing.assert_array_equal(stored.k[:, :, :3], O.round_to_bf16(exact.k[:, :, :3]))
     np.testing.assert_array_equal(stored.v[:, :, :3], O.round_to_bf16(exact.v[:, :, :3]))
     assert 0 < np.max(np.abs(ya - yb)) < 0.05 * np.max(np.abs(ya))       # a small, real difference
+
+
+# ------------------------------------------------------------------------------------------------
+# Alg. 1: which blocks drop their sync point
+# ------------------------------------------------------------------------------------------------
+def test_mask_builder_worked_example():
+    # ranking by hand: S = [0.5, 0.01, 12, 0.03, 0.04] -> blocks 1, 3, 4, 0, 2.  Budget 4 with the
+    # thresholds of Sec. 5 (0.05, 10): 1, 3, 4 are in-sensitive, 0 is sensitive, 2 keeps its sync.
+    mask, tier = O.mask_from_sensitivity([0.5, 0.01, 12.0, 0.03, 0.04], 4, 0.05, 10.0)
+    assert mask == [1, 1, 0, 1, 1]
+    assert tier == [O.TIER_SB, O.TIER_ISB, O.TIER_TP, O.TIER_ISB, O.TIER_ISB]
+    # the whole model: the last block is extremely sensitive
+    mask, tier = O.mask_from_sensitivity([0.5, 0.01, 12.0, 0.03, 0.04], 5, 0.05, 10.0)
+    assert mask == [1] * 5 and tier[2] == O.TIER_ESB
+    # thresholds are inclusive (Alg. 1 compares with <=)
+    mask, tier = O.mask_from_sensitivity([0.05, 10.0, 10.000001], 3, 0.05, 10.0)
+    assert tier == [O.TIER_ISB, O.TIER_SB, O.TIER_ESB]
+
+
+def test_mask_builder_selection_by_repeated_minimum():
+    # an independent route to the same ranking: take the least sensitive remaining block n_spd times
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        L = int(rng.integers(1, 12))
+        S = rng.choice([0.0, 0.01, 0.05, 0.3, 10.0, 11.0, 50.0], size=L).tolist() if trial % 2 else rng.random(L).tolist()
+        n = int(rng.integers(0, L + 1))
+        mask, tier = O.mask_from_sensitivity(S, n, 0.05, 10.0)
+        left = list(range(L))
+        want = [0] * L
+        for _ in range(n):
+            best = left[0]
+            for l in left:
+                if S[l] < S[best]:
+                    best = l              # strict: the first (lowest index) of equal values stays
+            want[best] = 1
+            left.remove(best)
+        assert mask == want
+        assert sum(mask) == n
+        # nobody outside the budget is less sensitive than somebody inside it
+        if 0 < n < L:
+            assert max(S[l] for l in range(L) if mask[l]) <= min(S[l] for l in range(L) if not mask[l])
+        for l in range(L):
+            if not mask[l]:
+                assert tier[l] == O.TIER_TP
+            else:
+                assert tier[l] == (O.TIER_ISB if S[l] <= 0.05 else O.TIER_SB if S[l] <= 10.0 else O.TIER_ESB)
+
+
+def test_mask_builder_budget_is_monotone_and_feeds_the_sync_count():
+    S = [3.0, 0.2, 0.2, 7.0, 0.01, 40.0]
+    prev = [0] * len(S)
+    for n in range(len(S) + 1):
+        mask, _ = O.mask_from_sensitivity(S, n, 0.05, 10.0)
+        assert all(a <= b for a, b in zip(prev, mask))        # a larger budget only adds blocks
+        prev = mask
+        # every block ends with a sync point; a block outside the budget has a second one (Sec. 3)
+        assert sum(1 if m else 2 for m in mask) == 2 * len(S) - n
+    # equal sensitivities: the lower index first
+    assert O.mask_from_sensitivity(S, 2, 0.05, 10.0)[0] == [0, 1, 0, 0, 1, 0]
+    with pytest.raises(ValueError):
+        O.mask_from_sensitivity(S, 7, 0.05, 10.0)
+    with pytest.raises(ValueError):
+        O.mask_from_sensitivity([0.1, float("nan")], 1, 0.05, 10.0)
