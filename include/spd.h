@@ -143,6 +143,25 @@ int spd_rank_ffn_cols(const spd_ctx *ctx, int32_t rank, int32_t *first, int32_t 
  * Sec. 3.  mask: host, [n_layers], each 0 or 1.  Returns the count or a negative code. */
 int64_t spd_sync_count(const spd_ctx *ctx, const uint8_t *mask);
 
+/* Sync-point drop by sensitivity (Alg. 1, Sec. 4.2): ranks the n_layers blocks by ascending
+ * sync sensitivity and lets the first n_spd of the ranking drop their attention sync point.
+ * Every dropped block gets a tier from its sensitivity s: SPD_TIER_ISB (s <= tau1: SPD as is),
+ * SPD_TIER_SB (s <= tau2: SPD after block-to-block distillation), SPD_TIER_ESB (otherwise: head
+ * grouping as well); blocks outside the budget get SPD_TIER_TP.  Blocks of equal sensitivity
+ * rank by index.  The sensitivities themselves are measured on calibration data outside this
+ * library (Sec. 4.2, Fig. 4); Sec. 5 uses tau1 = 0.05 (0.02 for the largest models), tau2 = 10.
+ *   sensitivity  host, [n_layers] doubles, no NaN
+ *   mask         host, [n_layers], receives 1 = sync dropped (the mask spd_model_forward takes)
+ *   tier         host, [n_layers], receives the SPD_TIER_* codes; may be NULL
+ * Host only, no device work.  SPD_EINVAL: NULL sensitivity or mask, n_layers <= 0, n_spd
+ * outside [0, n_layers], NaN in the sensitivities or thresholds. */
+#define SPD_TIER_TP 0
+#define SPD_TIER_ISB 1
+#define SPD_TIER_SB 2
+#define SPD_TIER_ESB 3
+int spd_mask_from_sensitivity(const double *sensitivity, int32_t n_layers, int32_t n_spd, double tau1, double tau2,
+                              uint8_t *mask, uint8_t *tier);
+
 /* ---------------------------------------------------------------- packing (host only)
  * Slices rank `rank`'s heads / FFN columns out of the dense layer and lays them out the
  * way the kernels stream them (bit-exact copies of the values, zero padding only).

@@ -34,6 +34,7 @@ class spd_config(C.Structure):
 
 
 SPD_SPLIT_AUTO, SPD_SPLIT_ALWAYS, SPD_SPLIT_NEVER = 0, 1, 2
+SPD_TIER_TP, SPD_TIER_ISB, SPD_TIER_SB, SPD_TIER_ESB = 0, 1, 2, 3
 
 
 class spd_sizes(C.Structure):
@@ -64,6 +65,8 @@ _PROTOS = {
     "spd_rank_kv_heads": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "spd_rank_ffn_cols": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "spd_sync_count": (C.c_int64, [C.c_void_p, C.c_void_p]),
+    "spd_mask_from_sensitivity": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
+                                            C.c_void_p]),
     "spd_pack_shard": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spd_layer_weights), C.c_void_p]),
     "spd_pack_shard_local": (C.c_int, [C.c_void_p, C.POINTER(spd_layer_weights), C.c_void_p]),
     "spd_unpack_shard": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(spd_layer_weights)]),
@@ -184,6 +187,17 @@ def spd_sync_count(ctx: int, mask: Sequence[int]) -> int:
     if n < 0:
         raise SpdError(int(n), "spd_sync_count")
     return int(n)
+
+
+def spd_mask_from_sensitivity(sensitivity: Sequence[float], n_spd: int, tau1: float, tau2: float):
+    """Returns (mask, tier), two lists of n_layers ints."""
+    s = np.ascontiguousarray(sensitivity, dtype=np.float64)
+    mask = np.zeros(s.size, dtype=np.uint8)
+    tier = np.zeros(s.size, dtype=np.uint8)
+    _check(lib().spd_mask_from_sensitivity(s.ctypes.data if s.size else None, s.size, int(n_spd), float(tau1),
+                                           float(tau2), mask.ctypes.data, tier.ctypes.data),
+           "spd_mask_from_sensitivity")
+    return mask.tolist(), tier.tolist()
 
 
 def _weights_struct(W: Dict[str, np.ndarray]) -> spd_layer_weights:

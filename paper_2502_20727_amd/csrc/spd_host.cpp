@@ -2,6 +2,7 @@
 // and the packers that lay one rank's shard and KV cache out the way the kernels read them.
 // Nothing in this file touches a device.
 #include <cmath>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -256,6 +257,28 @@ int64_t spd_sync_count(const spd_ctx *ctx, const uint8_t *mask) {
         n += mask[l] ? 1 : 2;
     }
     return n;
+}
+
+int spd_mask_from_sensitivity(const double *sensitivity, int32_t n_layers, int32_t n_spd, double tau1, double tau2,
+                              uint8_t *mask, uint8_t *tier) {
+    if (!sensitivity || !mask || n_layers <= 0 || n_spd < 0 || n_spd > n_layers) return SPD_EINVAL;
+    if (tau1 != tau1 || tau2 != tau2) return SPD_EINVAL;
+    for (int l = 0; l < n_layers; ++l)
+        if (sensitivity[l] != sensitivity[l]) return SPD_EINVAL;
+    std::vector<int32_t> order(n_layers);
+    for (int l = 0; l < n_layers; ++l) order[l] = l;
+    // ascending sensitivity; a stable sort keeps blocks of equal sensitivity in index order
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return sensitivity[a] < sensitivity[b]; });
+    for (int l = 0; l < n_layers; ++l) {
+        mask[l] = 0;
+        if (tier) tier[l] = SPD_TIER_TP;
+    }
+    for (int i = 0; i < n_spd; ++i) {
+        const int32_t blk = order[i];
+        mask[blk] = 1;
+        if (tier) tier[blk] = sensitivity[blk] <= tau1 ? SPD_TIER_ISB : (sensitivity[blk] <= tau2 ? SPD_TIER_SB : SPD_TIER_ESB);
+    }
+    return SPD_OK;
 }
 
 int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *packed_host) {

@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 from paper_2502_20727_amd import binding as B
+from oracle import spd_oracle as O
 from paper_2502_20727_amd import inputs, workloads
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -115,6 +116,43 @@ def test_sync_count(w):
     with pytest.raises(B.SpdError):
         B.spd_sync_count(ctx, [2] + [0] * (L - 1))
     B.spd_destroy(ctx)
+
+
+def test_mask_from_sensitivity_is_the_oracle_bit_for_bit():
+    # integer logic: exact agreement with the oracle's Alg. 1 on random sensitivities with many ties,
+    # infinities, every budget from 0 to L, and both threshold settings of Sec. 5
+    rng = np.random.default_rng(21)
+    pool = [0.0, 0.01, 0.02, 0.05, 0.0500001, 0.3, 10.0, 10.5, 50.0, float("inf"), -1.0]
+    n_cases = 0
+    for trial in range(300):
+        L = int(rng.integers(1, 90))
+        S = rng.choice(pool, size=L) if trial % 3 else rng.lognormal(-2.0, 3.0, size=L)
+        for n_spd in {0, L, int(rng.integers(0, L + 1)), int(rng.integers(0, L + 1))}:
+            for tau1 in (0.05, 0.02):
+                want = O.mask_from_sensitivity(S.tolist(), n_spd, tau1, 10.0)
+                got = B.spd_mask_from_sensitivity(S, n_spd, tau1, 10.0)
+                assert got[0] == want[0] and got[1] == want[1], (S, n_spd, tau1)
+                n_cases += 1
+    assert n_cases > 1000
+    # the mask is what spd_sync_count and spd_model_forward take
+    w = workloads.LLAMA70B_DECODE
+    ctx = B.spd_create(B.make_config(w))
+    S = rng.random(w.n_layers)
+    mask, tier = B.spd_mask_from_sensitivity(S, 64, 0.02, 10.0)
+    assert B.spd_sync_count(ctx, mask) == w.n_layers + (w.n_layers - 64)
+    assert tier.count(B.SPD_TIER_TP) == 16
+    B.spd_destroy(ctx)
+
+
+def test_mask_from_sensitivity_rejects():
+    S = [0.1, 0.2, 0.3]
+    for bad in (dict(n_spd=-1), dict(n_spd=4), dict(tau1=float("nan")), dict(tau2=float("nan")),
+                dict(sensitivity=[0.1, float("nan"), 0.3]), dict(sensitivity=[])):
+        kw = dict(sensitivity=S, n_spd=1, tau1=0.05, tau2=10.0)
+        kw.update(bad)
+        with pytest.raises(B.SpdError) as e:
+            B.spd_mask_from_sensitivity(**kw)
+        assert e.value.code == B.SPD_EINVAL
 
 
 def test_workload_masks():
