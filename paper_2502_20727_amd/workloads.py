@@ -88,10 +88,30 @@ LLAMA70B_PREFILL = Workload(
     head_dim=128, ffn=28672, n_layers=80, tp=8, dtype=BF16, seed=4, batch=4, q_len=2048,
     ctx=2048, mask=_all(80), note="rank 0, causal prefill, every layer SPD")
 
+# the shape the paper quotes its latency breakdown on (Fig. 2: one sequence of 128 tokens), and the
+# 4-way shards of the two smaller models (Sec. 5 runs them on 4 as well as 8 devices)
+LLAMA70B_PREFILL_128 = Workload(
+    name="llama2-70b-tp8-prefill-b1x128", hidden=8192, n_q_heads=64, n_kv_heads=8,
+    head_dim=128, ffn=28672, n_layers=80, tp=8, dtype=BF16, seed=5, batch=1, q_len=128,
+    ctx=128, mask=_all(80), note="rank 0, one sequence of 128 tokens, every layer SPD")
+
+LLAMA7B_TP4_DECODE = Workload(
+    name="llama2-7b-tp4-decode-b1-ctx2048", hidden=4096, n_q_heads=32, n_kv_heads=32,
+    head_dim=128, ffn=11008, n_layers=32, tp=4, dtype=BF16, seed=6, batch=1, q_len=1,
+    ctx=2048, mask=_all(32), note="rank 0 of 4, every layer SPD")
+
+LLAMA13B_TP4_DECODE = Workload(
+    name="llama2-13b-tp4-decode-b8-ctx4096", hidden=5120, n_q_heads=40, n_kv_heads=40,
+    head_dim=128, ffn=13824, n_layers=40, tp=4, dtype=BF16, seed=7, batch=8, q_len=1,
+    ctx=4096, mask=tuple(0 if l % 4 == 3 else 1 for l in range(40)),
+    note="rank 0 of 4, every 4th layer keeps its attention sync point")
+
 WORKLOADS = {w.name: w for w in
-             (TOY, LLAMA7B_DECODE, LLAMA13B_DECODE, LLAMA70B_DECODE, LLAMA70B_PREFILL)}
+             (TOY, LLAMA7B_DECODE, LLAMA13B_DECODE, LLAMA70B_DECODE, LLAMA70B_PREFILL, LLAMA70B_PREFILL_128,
+              LLAMA7B_TP4_DECODE, LLAMA13B_TP4_DECODE)}
 ALIASES = {"toy": TOY, "7b-decode": LLAMA7B_DECODE, "13b-decode": LLAMA13B_DECODE,
-           "70b-decode": LLAMA70B_DECODE, "70b-prefill": LLAMA70B_PREFILL}
+           "70b-decode": LLAMA70B_DECODE, "70b-prefill": LLAMA70B_PREFILL, "70b-prefill-128": LLAMA70B_PREFILL_128,
+           "7b-tp4-decode": LLAMA7B_TP4_DECODE, "13b-tp4-decode": LLAMA13B_TP4_DECODE}
 
 
 def get(name: str) -> Workload:

@@ -337,7 +337,7 @@ def test_edge_cases(gpu):
 # ------------------------------------------------------------------------------------------------
 # full-size shapes, in the launch configuration the bench times (2 layers each: one SPD, one TP)
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name", ["7b-decode", "13b-decode", "70b-decode"])
+@pytest.mark.parametrize("name", ["7b-decode", "13b-decode", "70b-decode", "7b-tp4-decode", "13b-tp4-decode"])
 def test_full_size_decode_shapes(gpu, name):
     import torch
     full = workloads.get(name)
@@ -361,6 +361,33 @@ def test_full_size_decode_shapes(gpu, name):
                                    0, peers.astype(np.float64))
         err = assert_close(out.cpu().numpy(), want, w, f"{name} layer {layer_ids[l]} flag {w.mask[l]}")
         say(f"  layer {layer_ids[l]} flag {w.mask[l]}: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
+        x = out
+    case.close()
+
+
+def test_full_size_short_prefill(gpu):
+    """LLaMA2-70B shard, one sequence of 128 tokens (the shape of the paper's latency breakdown,
+    Fig. 2), an SPD block then a TP block, every output row checked, with split activations (the
+    2e-2 bound as it stands; a single-pass run of this shape measures 9e-2, see the long prefill)."""
+    import torch
+    full = workloads.get("70b-prefill-128")
+    w = full.with_layers(2).with_mask((1, 0))
+    M = full.q_len
+    case = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, full.n_layers - 1], act_split=B.SPD_SPLIT_ALWAYS)
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    x, slots = case.to_dev(X), case.to_dev(peers)
+    say("full-size short prefill: 1 x 128 tokens")
+    for l in range(2):
+        x_host = x.cpu().numpy()
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, l, w.mask[l], 0, case.dev.weights[l], case.dev.kv[l], [0], 1, M, x, slots, out,
+                            case.dev.workspace)
+        torch.cuda.synchronize()
+        want = O.block_single_rank(case.sh, x_host, case.shards[l][0], case.caches[l][0], [0], 1, M, w.mask[l], 0,
+                                   peers.astype(np.float64))
+        err = assert_close(out.cpu().numpy(), want, w, f"short prefill layer {l}")
+        say(f"  flag {w.mask[l]}: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
         x = out
     case.close()
 
