@@ -340,3 +340,32 @@ def mask_from_sensitivity(S: Sequence[float], n_spd: int, tau1: float, tau2: flo
         else:
             tier[blk] = TIER_ESB
     return mask, tier
+
+
+# --------------------------------------------------------------------------- head grouping
+
+def grouped_shards(sh: Shapes, dense: Dict[str, np.ndarray], kv_heads: Sequence[int],
+                   mlp_of_rank: Sequence[int]) -> List[Dict[str, np.ndarray]]:
+    """Per-device weights after head grouping (Sec. 4.2.3, Fig. 5).
+
+    kv_heads lists the KV heads in the order they are laid over the devices: device r holds
+    kv_heads[r*kv : (r+1)*kv], each with its own query heads (for multi-head attention a KV
+    head is a head); the columns of W_Q, W_K, W_V and the rows of W_O move with their head.
+    mlp_of_rank[r] is the MLP partition (contiguous block of FFN columns) matched with device r.
+    dense: wq [h, Hq*d], wk/wv [h, Hkv*d], wo [Hq*d, h], wg/wu [h, F], wd [F, h], g1, g2."""
+    d, g = sh.head_dim, sh.n_q_heads // sh.n_kv_heads
+    assert sorted(kv_heads) == list(range(sh.n_kv_heads)) and sorted(mlp_of_rank) == list(range(sh.tp))
+    out = []
+    for r in range(sh.tp):
+        mine = [int(k) for k in kv_heads[r * sh.kv:(r + 1) * sh.kv]]
+        q_cols = [c for k in mine for qh in range(k * g, (k + 1) * g) for c in range(qh * d, (qh + 1) * d)]
+        kv_cols = [c for k in mine for c in range(k * d, (k + 1) * d)]
+        m = int(mlp_of_rank[r])
+        ffn = slice(m * sh.f, (m + 1) * sh.f)
+        out.append({
+            "wq": dense["wq"][:, q_cols].copy(), "wk": dense["wk"][:, kv_cols].copy(),
+            "wv": dense["wv"][:, kv_cols].copy(), "wo": dense["wo"][q_cols, :].copy(),
+            "wg": dense["wg"][:, ffn].copy(), "wu": dense["wu"][:, ffn].copy(), "wd": dense["wd"][ffn, :].copy(),
+            "g1": dense["g1"].copy(), "g2": dense["g2"].copy(),
+        })
+    return out

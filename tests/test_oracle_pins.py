@@ -509,3 +509,39 @@ def test_mask_builder_budget_is_monotone_and_feeds_the_sync_count():
         O.mask_from_sensitivity(S, 7, 0.05, 10.0)
     with pytest.raises(ValueError):
         O.mask_from_sensitivity([0.1, float("nan")], 1, 0.05, 10.0)
+
+
+# ------------------------------------------------------------------------------------------------
+# head grouping: which heads and which MLP partition live on a device (Sec. 4.2.3, Fig. 5)
+# ------------------------------------------------------------------------------------------------
+def test_head_grouping_moves_weights_but_not_the_tp_result():
+    sh = O.Shapes(hidden=16, n_q_heads=8, n_kv_heads=4, head_dim=4, ffn=24, tp=2)     # 2 query heads per KV head
+    rng = np.random.default_rng(23)
+    shards = make_shards(rng, sh)
+    dense = to_dense(shards)
+    X = rng.standard_normal((3, sh.hidden))
+    run = lambda s, flag: O.block_all_ranks(sh, X, s, fresh_caches(sh, 1, 4), [0], 1, 3, flag)[0]
+    # the identity grouping is the contiguous split
+    ident = O.grouped_shards(sh, dense, [0, 1, 2, 3], [0, 1])
+    for a, b in zip(ident, shards):
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+    # a device's query heads are those of its KV heads: KV head 3 brings query heads 6 and 7
+    moved = O.grouped_shards(sh, dense, [3, 0, 2, 1], [1, 0])
+    d = sh.head_dim
+    assert np.array_equal(moved[0]["wq"][:, :2 * d], dense["wq"][:, 6 * d:8 * d])
+    assert np.array_equal(moved[0]["wo"][2 * d:4 * d, :], dense["wo"][0:2 * d, :])
+    assert np.array_equal(moved[1]["wk"][:, d:2 * d], dense["wk"][:, d:2 * d])
+    assert np.array_equal(moved[0]["wd"], dense["wd"][sh.f:, :]) and np.array_equal(moved[1]["wg"], dense["wg"][:, :sh.f])
+    # every dense column / row lands on exactly one device
+    for name, axis in (("wq", 1), ("wk", 1), ("wv", 1), ("wg", 1), ("wu", 1), ("wo", 0), ("wd", 0)):
+        got = np.sort(np.concatenate([s[name] for s in moved], axis=axis).ravel())
+        assert np.array_equal(got, np.sort(dense[name].ravel())), name
+    # with every sync point kept the block computes the same function wherever the heads live;
+    # an SPD block does not (each MLP partition sees only its own device's heads)
+    np.testing.assert_allclose(run(moved, 0), run(shards, 0), rtol=1e-11, atol=1e-12)
+    assert np.max(np.abs(run(moved, 1) - run(shards, 1))) > 1e-4
+    # the matching alone (same heads, MLP partitions swapped) also changes only the SPD block
+    swapped = O.grouped_shards(sh, dense, [0, 1, 2, 3], [1, 0])
+    np.testing.assert_allclose(run(swapped, 0), run(shards, 0), rtol=1e-11, atol=1e-12)
+    assert np.max(np.abs(run(swapped, 1) - run(shards, 1))) > 1e-4
