@@ -167,6 +167,16 @@ int spd_mask_from_sensitivity(const double *sensitivity, int32_t n_layers, int32
  * way the kernels stream them (bit-exact copies of the values, zero padding only).
  * `packed_host` receives weight_bytes bytes; the caller then copies them to the device. */
 int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host);
+/* Same after head grouping (Sec. 4.2.3, Fig. 5): the heads are laid over the devices in the
+ * order `kv_heads` (a permutation of 0 .. n_kv_heads-1; device r holds kv_heads[r*kv .. r*kv+kv)
+ * with the query heads that attend through them, so that the columns of W_Q, W_K, W_V and the
+ * rows of W_O move together with their head), and device r is matched with MLP partition
+ * mlp_of_rank[r] (a permutation of 0 .. tp_degree-1; partition m = FFN columns [m*f, m*f+f)).
+ * Either array may be NULL = identity; with both NULL this is spd_pack_shard().  How the
+ * grouping and the matching are found (attention scores and MLP output norms on calibration
+ * data, Eq. 1 and 2) is outside this library.  SPD_EINVAL if an array is not a permutation. */
+int spd_pack_shard_grouped(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, const int32_t *kv_heads,
+                           const int32_t *mlp_of_rank, void *packed_host);
 /* Same, from matrices that already are one rank's slices. */
 int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *shard, void *packed_host);
 /* Inverse of spd_pack_shard_local(): writes the rank's slices back in natural layout

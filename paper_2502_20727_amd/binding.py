@@ -68,6 +68,8 @@ _PROTOS = {
     "spd_mask_from_sensitivity": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
                                             C.c_void_p]),
     "spd_pack_shard": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spd_layer_weights), C.c_void_p]),
+    "spd_pack_shard_grouped": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spd_layer_weights), C.c_void_p, C.c_void_p,
+                                         C.c_void_p]),
     "spd_pack_shard_local": (C.c_int, [C.c_void_p, C.POINTER(spd_layer_weights), C.c_void_p]),
     "spd_unpack_shard": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(spd_layer_weights)]),
     "spd_kv_pack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
@@ -217,6 +219,18 @@ def spd_pack_shard(ctx: int, rank: int, dense: Dict[str, np.ndarray], out: Optio
         out = np.empty(spd_get_sizes(ctx).weight_bytes, dtype=np.uint8)
     s = _weights_struct(dense)
     _check(lib().spd_pack_shard(ctx, rank, C.byref(s), out.ctypes.data), "spd_pack_shard")
+    return out
+
+
+def spd_pack_shard_grouped(ctx: int, rank: int, dense: Dict[str, np.ndarray], kv_heads: Optional[Sequence[int]],
+                           mlp_of_rank: Optional[Sequence[int]], out: Optional[np.ndarray] = None) -> np.ndarray:
+    if out is None:
+        out = np.empty(spd_get_sizes(ctx).weight_bytes, dtype=np.uint8)
+    s = _weights_struct(dense)
+    kh = None if kv_heads is None else np.ascontiguousarray(kv_heads, dtype=np.int32)
+    mr = None if mlp_of_rank is None else np.ascontiguousarray(mlp_of_rank, dtype=np.int32)
+    _check(lib().spd_pack_shard_grouped(ctx, rank, C.byref(s), None if kh is None else kh.ctypes.data,
+                                        None if mr is None else mr.ctypes.data, out.ctypes.data), "spd_pack_shard_grouped")
     return out
 
 

@@ -347,6 +347,49 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
     return ok ? SPD_OK : SPD_EINVAL;   // a weight that is not a bf16 value
 }
 
+static bool is_permutation(const int32_t *p, int n) {
+    std::vector<char> seen(n, 0);
+    for (int i = 0; i < n; ++i) {
+        if (p[i] < 0 || p[i] >= n || seen[p[i]]) return false;
+        seen[p[i]] = 1;
+    }
+    return true;
+}
+
+int spd_pack_shard_grouped(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, const int32_t *kv_heads,
+                           const int32_t *mlp_of_rank, void *packed_host) {
+    if (!ctx || !weights_ok(dense) || !packed_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (rank < 0 || rank >= D.tp) return SPD_EINVAL;
+    const int n_kv = ctx->cfg.n_kv_heads;
+    if (kv_heads && !is_permutation(kv_heads, n_kv)) return SPD_EINVAL;
+    if (mlp_of_rank && !is_permutation(mlp_of_rank, D.tp)) return SPD_EINVAL;
+    const int h = D.h, d = D.d, kv = D.kv, g = D.group, qd = D.q * d, kvd = kv * d;
+    // gather the device's heads into contiguous matrices: columns of W_Q / W_K / W_V, rows of W_O
+    std::vector<float> wq((size_t)h * qd), wk((size_t)h * kvd), wv((size_t)h * kvd), wo((size_t)qd * h);
+    for (int j = 0; j < kv; ++j) {
+        const int head = kv_heads ? kv_heads[rank * kv + j] : rank * kv + j;
+        for (int k = 0; k < h; ++k) {
+            std::memcpy(&wk[(size_t)k * kvd + j * d], dense->wk + (size_t)k * dense->ld_k + (size_t)head * d, (size_t)d * 4);
+            std::memcpy(&wv[(size_t)k * kvd + j * d], dense->wv + (size_t)k * dense->ld_v + (size_t)head * d, (size_t)d * 4);
+            std::memcpy(&wq[(size_t)k * qd + (size_t)j * g * d], dense->wq + (size_t)k * dense->ld_q + (size_t)head * g * d,
+                        (size_t)g * d * 4);
+        }
+        for (int r = 0; r < g * d; ++r)
+            std::memcpy(&wo[((size_t)j * g * d + r) * h], dense->wo + ((size_t)head * g * d + r) * dense->ld_o, (size_t)h * 4);
+    }
+    const int m = mlp_of_rank ? mlp_of_rank[rank] : rank;
+    spd_layer_weights s = *dense;
+    s.wq = wq.data(); s.ld_q = qd;
+    s.wk = wk.data(); s.ld_k = kvd;
+    s.wv = wv.data(); s.ld_v = kvd;
+    s.wo = wo.data(); s.ld_o = h;
+    s.wg += (size_t)m * D.f;
+    s.wu += (size_t)m * D.f;
+    s.wd += (size_t)m * D.f * (size_t)dense->ld_d;
+    return spd_pack_shard_local(ctx, &s, packed_host);
+}
+
 int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host) {
     if (!ctx || !weights_ok(dense) || !packed_host) return SPD_EINVAL;
     const spd_dims &D = ctx->D;

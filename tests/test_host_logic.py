@@ -183,6 +183,40 @@ def test_pack_is_a_lossless_slice(w):
     B.spd_destroy(ctx)
 
 
+GQA_F32 = workloads.Workload(name="gqa-f32", hidden=32, n_q_heads=8, n_kv_heads=4, head_dim=8, ffn=48, n_layers=1, tp=2,
+                             dtype=workloads.F32, seed=9, batch=1, q_len=1, ctx=32, mask=(1,))
+GQA_BF16 = workloads.Workload(name="gqa-bf16", hidden=64, n_q_heads=8, n_kv_heads=4, head_dim=32, ffn=96, n_layers=1,
+                              tp=2, dtype=workloads.BF16, seed=9, batch=1, q_len=1, ctx=32, mask=(1,))
+
+
+@pytest.mark.parametrize("w", [GQA_F32, GQA_BF16, SMALL_BF16], ids=lambda w: w.name)
+def test_grouped_pack_is_the_oracle_grouping_bit_for_bit(w):
+    # head grouping (Sec. 4.2.3): the packed bytes of every device equal the packing of the shard the
+    # oracle cuts out of the dense layer for the same head order and MLP matching
+    ctx = B.spd_create(B.make_config(w))
+    dense = inputs.dense_layer(w, 0)
+    sh = O.Shapes(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, w.tp, w.rms_eps, w.rope_base)
+    rng = np.random.default_rng(4)
+    for trial in range(6):
+        kvh = rng.permutation(w.n_kv_heads).tolist() if trial else list(range(w.n_kv_heads))
+        mlp = rng.permutation(w.tp).tolist() if trial != 1 else list(range(w.tp))
+        want = O.grouped_shards(sh, dense, kvh, mlp)
+        for r in range(w.tp):
+            got = B.spd_pack_shard_grouped(ctx, r, dense, kvh, mlp)
+            ref = B.spd_pack_shard_local(ctx, {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in want[r].items()})
+            assert np.array_equal(got, ref), (trial, r)
+    # identity arguments (or none) are the plain contiguous split
+    for r in range(w.tp):
+        assert np.array_equal(B.spd_pack_shard_grouped(ctx, r, dense, None, None), B.spd_pack_shard(ctx, r, dense))
+    for bad_kv, bad_mlp in (([0] * w.n_kv_heads, None), (None, [0] * w.tp), (list(range(1, w.n_kv_heads + 1)), None)):
+        with pytest.raises(B.SpdError) as e:
+            B.spd_pack_shard_grouped(ctx, 0, dense, bad_kv, bad_mlp)
+        assert e.value.code == B.SPD_EINVAL
+    with pytest.raises(B.SpdError):
+        B.spd_pack_shard_grouped(ctx, w.tp, dense, None, None)
+    B.spd_destroy(ctx)
+
+
 def test_pack_every_value_lands_exactly_once():
     # a packed bf16 shard is a permutation of the shard's values plus zero padding
     w = SMALL_BF16
