@@ -211,24 +211,35 @@ def mlp_partial(sh: Shapes, R: np.ndarray, W: Dict[str, np.ndarray],
 
 # --------------------------------------------------------------------------- whole blocks
 
+def output_bias(shard: Dict[str, np.ndarray], hidden: int) -> np.ndarray:
+    """The bias b of the attention output projection, zero for a block without bias."""
+    b = shard.get("bo")
+    return np.zeros(hidden, F64) if b is None else np.asarray(b, F64)
+
+
 def block_all_ranks(sh: Shapes, X: np.ndarray, shards: List[Dict[str, np.ndarray]],
                     caches: List[KVCache], positions: Sequence[int], batch: int, q_len: int,
                     spd: int, detail: Optional[dict] = None):
     """One decoder block with every device emulated.  Returns (X', number of sync points).
 
-    spd = 0: TP block, two all-reduces (Sec. 3).  spd = 1: SPD block without bias
-    (Sec. 4.1.1): MLP input X + Y_i, Y_i added before the one remaining all-reduce, X after.
+    spd = 0: TP block, two all-reduces (Sec. 3).  spd = 1: SPD block (Sec. 4.1.1): MLP input
+    X + Y_i, Y_i added before the one remaining all-reduce, X after.  A shard may carry "bo", the
+    bias of the output projection (replicated, it cannot be split along the rows of W_O): the
+    block with bias of Sec. 4.1.2.
     """
     X = np.asarray(X, F64)
+    # P_i: the device's partial weight multiplication of the output projection (no bias in it)
     Y = [attention_partial(sh, X, shards[i], caches[i], positions, batch, q_len)
          for i in range(sh.tp)]
+    b = output_bias(shards[0], sh.hidden)
     if spd:
-        Z = [mlp_partial(sh, X + Y[i], shards[i]) for i in range(sh.tp)]
+        # with bias (Sec. 4.1.2): MLP input X + P_i + b; P_i joins before the sync, b once after it
+        Z = [mlp_partial(sh, X + Y[i] + b, shards[i]) for i in range(sh.tp)]
         P = [Y[i] + Z[i] for i in range(sh.tp)]          # Y_i goes in before the sync
-        out = X + sum(P)                                 # X after it
+        out = X + sum(P) + b                             # X (and the bias) after it
         syncs = 1
     else:
-        R = X + sum(Y)                                   # sync point after attention
+        R = X + sum(Y) + b                               # sync point after attention, then the bias once
         Z = [mlp_partial(sh, R, shards[i]) for i in range(sh.tp)]
         P = Z
         out = R + sum(Z)                                 # sync point after the MLP
@@ -252,13 +263,14 @@ def block_single_rank(sh: Shapes, X: np.ndarray, shard: Dict[str, np.ndarray], c
     sel = np.arange(X.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
     S = np.array(slots[:, sel], dtype=F64)                 # the partial sums met at a sync point
     Y = attention_partial(sh, X, shard, cache, positions, batch, q_len, rows=rows, detail=detail)
+    b = output_bias(shard, sh.hidden)
     if spd:
-        Z = mlp_partial(sh, X[sel] + Y, shard, detail)
+        Z = mlp_partial(sh, X[sel] + Y + b, shard, detail)
         S[rank] = Y + Z
-        out = X[sel] + np.sum(S, axis=0)
+        out = X[sel] + np.sum(S, axis=0) + b
     else:
         S[rank] = Y
-        R = X[sel] + np.sum(S, axis=0)
+        R = X[sel] + np.sum(S, axis=0) + b
         Z = mlp_partial(sh, R, shard, detail)
         S[rank] = Z
         out = R + np.sum(S, axis=0)
@@ -274,7 +286,7 @@ def dense_block(sh: Shapes, X: np.ndarray, dense: Dict[str, np.ndarray], cache: 
     one = Shapes(sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, 1,
                  sh.rms_eps, sh.rope_base)
     X = np.asarray(X, F64)
-    R = X + attention_partial(one, X, dense, cache, positions, batch, q_len)
+    R = X + attention_partial(one, X, dense, cache, positions, batch, q_len) + output_bias(dense, sh.hidden)
     return R + mlp_partial(one, R, dense)
 
 

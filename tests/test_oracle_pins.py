@@ -545,3 +545,46 @@ def test_head_grouping_moves_weights_but_not_the_tp_result():
     swapped = O.grouped_shards(sh, dense, [0, 1, 2, 3], [1, 0])
     np.testing.assert_allclose(run(swapped, 0), run(shards, 0), rtol=1e-11, atol=1e-12)
     assert np.max(np.abs(run(swapped, 1) - run(shards, 1))) > 1e-4
+
+
+# ------------------------------------------------------------------------------------------------
+# block with bias in the output projection (Sec. 4.1.2)
+# ------------------------------------------------------------------------------------------------
+def test_block_with_bias():
+    sh = O.Shapes(hidden=16, n_q_heads=4, n_kv_heads=2, head_dim=4, ffn=24, tp=2)
+    rng = np.random.default_rng(29)
+    shards = make_shards(rng, sh)
+    X = rng.standard_normal((5, sh.hidden))
+    bo = rng.standard_normal(sh.hidden)
+    with_b = [dict(s, bo=bo) for s in shards]
+    zero_b = [dict(s, bo=np.zeros(sh.hidden)) for s in shards]
+    run = lambda s, flag, det=None: O.block_all_ranks(sh, X, s, fresh_caches(sh, 1, 8), [0], 1, 5, flag, det)[0]
+    for flag in (0, 1):
+        # a zero bias is the block without bias
+        np.testing.assert_array_equal(run(zero_b, flag), run(shards, flag))
+        assert np.max(np.abs(run(with_b, flag) - run(shards, flag))) > 1e-3
+    # TP with bias is the single-device block with bias: attention output = sum_i P_i + b, b once
+    dense = to_dense(shards)
+    dense["bo"] = bo
+    want = O.dense_block(sh, X, dense, O.KVCache(1, sh.n_kv_heads, 8, sh.head_dim), [0], 1, 5)
+    np.testing.assert_allclose(run(with_b, 0), want, rtol=1e-11, atol=1e-12)
+    # SPD with bias: the output is X + sum_i P_i + b + sum_i Z_i with the bias counted once,
+    # and device i's MLP saw X + P_i + b (Sec. 4.1.2)
+    det = {}
+    out = run(with_b, 1, det)
+    np.testing.assert_allclose(out, X + sum(det["Y"]) + bo + sum(det["Z"]), rtol=1e-12, atol=1e-12)
+    for i in range(sh.tp):
+        np.testing.assert_allclose(det["Z"][i], O.mlp_partial(sh, X + det["Y"][i] + bo, shards[i]), rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(det["P"][i], det["Y"][i] + det["Z"][i], rtol=1e-12, atol=1e-12)     # no bias before the sync
+    # the bias is counted once, not once per device: with the MLP switched off (zero down projection)
+    # raising every bias entry by one raises the output by exactly one
+    big = [dict(s, bo=bo + 1.0) for s in shards]
+    nomlp = lambda ss: [dict(s, wd=np.zeros_like(s["wd"])) for s in ss]
+    for flag in (0, 1):
+        np.testing.assert_allclose(run(nomlp(big), flag) - run(nomlp(with_b), flag), np.ones_like(X), rtol=0, atol=1e-12)
+    # the single-rank view agrees with the all-ranks run
+    det = {}
+    full = run(with_b, 1, det)
+    got = O.block_single_rank(sh, X, with_b[1], O.KVCache(1, sh.kv, 8, sh.head_dim), [0], 1, 5, 1, 1,
+                              np.stack(det["P"]).copy())
+    np.testing.assert_allclose(got, full, rtol=1e-11, atol=1e-12)
