@@ -76,6 +76,7 @@ typedef struct spd_config {
     float rms_eps;       /* 1e-5 for LLaMA2 */
     float rope_base;     /* 10000 for LLaMA2 */
     int32_t act_split;   /* SPD_BF16 only: SPD_SPLIT_AUTO | SPD_SPLIT_ALWAYS | SPD_SPLIT_NEVER */
+    int32_t o_bias;      /* 1: the attention output projection has a bias (block with bias, Sec. 4.1.2); else 0 */
 } spd_config;
 
 /* bf16 MFMA needs bf16 activations.  With "split" activations every activation that feeds a
@@ -105,6 +106,11 @@ typedef struct spd_sizes {
 typedef struct spd_layer_weights {
     const float *wq, *wk, *wv, *wo, *wg, *wu, *wd, *g1, *g2;
     int64_t ld_q, ld_k, ld_v, ld_o, ld_g, ld_u, ld_d;
+    const float *bo;     /* [h] bias of the output projection, replicated on every rank (it cannot be split
+                            along the rows of W_O); required iff the configuration has o_bias = 1, else NULL.
+                            Kept in fp32.  Block with bias (Sec. 4.1.2): the device's MLP input is
+                            X + P_r + b, the partial product P_r joins the partial sum before the sync
+                            point and b is added once after it. */
 } spd_layer_weights;
 
 /* Optional taps: when a pointer is non-NULL the block copies that intermediate of the
@@ -124,7 +130,7 @@ typedef struct spd_taps {
  * max_ctx not a multiple of 32.  SPD_EUNSUPPORTED: n_kv_heads < tp_degree (a KV head
  * shared by several ranks); unknown dtype; for SPD_BF16: hidden or head_dim not a
  * multiple of 32, ffn / tp_degree not a multiple of 16, more than 16 query heads per
- * KV head.  act_split outside its three values: SPD_EINVAL. */
+ * KV head.  act_split outside its three values, o_bias outside {0, 1}: SPD_EINVAL. */
 int spd_create(const spd_config *cfg, spd_ctx **out);
 void spd_destroy(spd_ctx *ctx);
 int spd_get_config(const spd_ctx *ctx, spd_config *out);

@@ -30,7 +30,7 @@ class SpdError(RuntimeError):
 class spd_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "n_layers",
                                          "tp_degree", "dtype", "max_batch", "max_ctx", "max_tokens")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("act_split", C.c_int32)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("act_split", C.c_int32), ("o_bias", C.c_int32)]
 
 
 SPD_SPLIT_AUTO, SPD_SPLIT_ALWAYS, SPD_SPLIT_NEVER = 0, 1, 2
@@ -46,7 +46,7 @@ _FP = C.POINTER(C.c_float)
 
 class spd_layer_weights(C.Structure):
     _fields_ = [(n, _FP) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")] + \
-               [(n, C.c_int64) for n in ("ld_q", "ld_k", "ld_v", "ld_o", "ld_g", "ld_u", "ld_d")]
+               [(n, C.c_int64) for n in ("ld_q", "ld_k", "ld_v", "ld_o", "ld_g", "ld_u", "ld_d")] + [("bo", _FP)]
 
 
 class spd_taps(C.Structure):
@@ -135,12 +135,12 @@ def _i32(values: Sequence[int]):
 # --------------------------------------------------------------------------- host-only calls
 
 def make_config(w: Workload, max_batch: Optional[int] = None, max_ctx: Optional[int] = None,
-                max_tokens: Optional[int] = None, act_split: int = 0) -> spd_config:
+                max_tokens: Optional[int] = None, act_split: int = 0, o_bias: int = 0) -> spd_config:
     mb = max_batch if max_batch is not None else w.batch
     mc = max_ctx if max_ctx is not None else (w.ctx + 31) // 32 * 32
     mt = max_tokens if max_tokens is not None else max(w.batch * w.q_len, mb)
     return spd_config(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, w.n_layers, w.tp, w.dtype,
-                      mb, mc, mt, w.rms_eps, w.rope_base, act_split)
+                      mb, mc, mt, w.rms_eps, w.rope_base, act_split, o_bias)
 
 
 def spd_create(cfg: spd_config) -> int:
@@ -211,6 +211,9 @@ def _weights_struct(W: Dict[str, np.ndarray]) -> spd_layer_weights:
     for name, ld in (("wq", "ld_q"), ("wk", "ld_k"), ("wv", "ld_v"), ("wo", "ld_o"), ("wg", "ld_g"),
                      ("wu", "ld_u"), ("wd", "ld_d")):
         setattr(s, ld, W[name].shape[1])
+    if W.get("bo") is not None:          # bias of the output projection (block with bias)
+        assert W["bo"].dtype == np.float32 and W["bo"].flags.c_contiguous
+        s.bo = W["bo"].ctypes.data_as(_FP)
     return s
 
 
@@ -338,13 +341,15 @@ class DeviceShard:
     """
 
     def __init__(self, w: Workload, ranks: Sequence[int], device, max_ctx: Optional[int] = None,
-                 max_tokens: Optional[int] = None, max_batch: Optional[int] = None, act_split: int = 0):
+                 max_tokens: Optional[int] = None, max_batch: Optional[int] = None, act_split: int = 0,
+                 o_bias: int = 0):
         import torch
         self.torch = torch
         self.w = w
         self.ranks = list(ranks)
         self.device = device
-        self.cfg = make_config(w, max_batch=max_batch, max_ctx=max_ctx, max_tokens=max_tokens, act_split=act_split)
+        self.cfg = make_config(w, max_batch=max_batch, max_ctx=max_ctx, max_tokens=max_tokens, act_split=act_split,
+                               o_bias=o_bias)
         self.ctx = spd_create(self.cfg)
         self.sizes = spd_get_sizes(self.ctx)
         nr = len(self.ranks)

@@ -51,8 +51,8 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
 // performs that final rank-sum into x_out (and the next block's first-norm preparation when
 // next_g1 is given); *end_done tells the caller whether it did.
 int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const char *weights, char *kv,
-               const float *x, float *slots, const float **base_out, int64_t *syncs, float *x_out,
-               const float *next_g1, bool *end_done) {
+               const float *x, float *slots, const float **base_out, const float **bias_out, int64_t *syncs,
+               float *x_out, const float *next_g1, bool *end_done) {
     const spd_dims &D = ctx->D;
     const size_t slot_n = (size_t)c.M * D.h;
     float *ybuf = (float *)(c.ws + D.ws_y), *rbuf = (float *)(c.ws + D.ws_r);
@@ -61,10 +61,15 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
     auto wr = [&](int r) { return weights + (all ? (size_t)r * D.weight_bytes : 0); };
     auto kr = [&](int r) { return kv + (all ? (size_t)r * D.kv_bytes : 0); };
 
+    // block with bias (Sec. 4.1.2): the output projection's bias b joins a sum over the ranks once,
+    // after the sync point: the attention one in a TP block, the one that ends the block in an SPD
+    // block (whose MLP input X + P_r + b takes it locally)
+    const float *bo = D.o_bias ? (const float *)(wr(r0) + D.w_bo) : nullptr;
+    *bias_out = spd ? bo : nullptr;
     *end_done = false;
     if (D.dtype == SPD_BF16) {
         spd_bf16::spd_end_sync es;
-        es.slots = slots; es.tp = D.tp; es.rank = r0; es.x_out = x_out; es.next_g1 = next_g1;
+        es.slots = slots; es.tp = D.tp; es.rank = r0; es.x_out = x_out; es.next_g1 = next_g1; es.bias = *bias_out;
         const spd_bf16::spd_end_sync *fuse = (!all && x_out) ? &es : nullptr;
         if (spd) {
             es.base = x;
@@ -76,7 +81,7 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
         } else {
             for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 0, slots + r * slot_n));
             // kept sync point: R = X + sum_r Y_r, fused with the second norm's elementwise part
-            SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1));
+            SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1, bo));
             *syncs += 1;
             es.base = rbuf;
             for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n, fuse, end_done));
@@ -87,13 +92,13 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
     if (spd) {
         for (int r = r0; r < r1; ++r) {
             SPD_HIP(spd_f32::attention_half(c, wr(r), kr(r), x, ybuf));
-            SPD_HIP(spd_common::rank_sum(x, ybuf, 1, (int64_t)slot_n, rbuf, c.s));       // local fold X + Y_r
+            SPD_HIP(spd_common::rank_sum(x, ybuf, 1, (int64_t)slot_n, rbuf, c.s, bo, D.h));   // local fold X + Y_r (+ b)
             SPD_HIP(spd_f32::mlp_half(c, wr(r), rbuf, ybuf, slots + r * slot_n));        // slot = Y_r + Z_r
         }
         *base_out = x;
     } else {
         for (int r = r0; r < r1; ++r) SPD_HIP(spd_f32::attention_half(c, wr(r), kr(r), x, slots + r * slot_n));
-        SPD_HIP(spd_common::rank_sum(x, slots, D.tp, (int64_t)slot_n, rbuf, c.s));       // kept sync point
+        SPD_HIP(spd_common::rank_sum(x, slots, D.tp, (int64_t)slot_n, rbuf, c.s, bo, D.h));   // kept sync point
         *syncs += 1;
         for (int r = r0; r < r1; ++r) SPD_HIP(spd_f32::mlp_half(c, wr(r), rbuf, nullptr, slots + r * slot_n));
         *base_out = rbuf;
@@ -143,14 +148,14 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
         SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)(w + D.w_g1), true, 0));
         c.nch1 = spd_bf16::prep_chunks(c);
     }
-    const float *base = nullptr;
+    const float *base = nullptr, *bias = nullptr;
     int64_t syncs = 0;
     bool end_done = false;
-    const int rc2 = block_core(ctx, c, spd_flag, rank, w, (char *)kv_cache, x_in, slots, &base, &syncs, x_out, nullptr,
-                               &end_done);
+    const int rc2 = block_core(ctx, c, spd_flag, rank, w, (char *)kv_cache, x_in, slots, &base, &bias, &syncs, x_out,
+                               nullptr, &end_done);
     if (rc2 != SPD_OK) return rc2;
     // the sync point that ends every block, SPD or not
-    if (!end_done) SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
+    if (!end_done) SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s, bias, D.h));
     return SPD_OK;
 }
 
@@ -178,21 +183,21 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
         c.nch1 = spd_bf16::prep_chunks(c);
     }
     for (int l = 0; l < L; ++l) {
-        const float *base = nullptr;
+        const float *base = nullptr, *bias = nullptr;
         const bool more = l + 1 < L;
         const float *g1 = (bf && more) ? (const float *)((const char *)layer_weights[l + 1] + D.w_g1) : nullptr;
         bool end_done = false;
         const int rc2 = block_core(ctx, c, spd_mask[l], rank, (const char *)layer_weights[l], (char *)layer_kv[l], x,
-                                   slots, &base, &syncs, x_out, g1, &end_done);
+                                   slots, &base, &bias, &syncs, x_out, g1, &end_done);
         if (rc2 != SPD_OK) return rc2;
         // end-of-block sync point; in the bf16 path it also prepares the next block's first norm
         if (end_done) {
             c.nch1 = D.h / 32;                   // the fused epilogue left one partial per pair of n-tiles
         } else if (bf) {
-            SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0));
+            SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0, bias));
             c.nch1 = spd_bf16::prep_chunks(c);
         } else if (spd_profile::enabled(SPD_STAGE_PREP)) {
-            SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s));
+            SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s, bias, D.h));
         }
         syncs += 1;
         x = x_out;

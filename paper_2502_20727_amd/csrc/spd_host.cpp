@@ -70,6 +70,8 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     size_t o = 0;
     D.w_g1 = o; o = spd_align256(o + h * 4);
     D.w_g2 = o; o = spd_align256(o + h * 4);
+    D.o_bias = c.o_bias;
+    if (c.o_bias) { D.w_bo = o; o = spd_align256(o + h * 4); }
     D.w_qkv = o; o = spd_align256(o + h * (size_t)D.nqkv * es);
     D.w_o = o; o = spd_align256(o + qd * h * es);
     D.w_g = o; o = spd_align256(o + h * f * es);
@@ -156,8 +158,10 @@ void unpack_frags(const uint16_t *srcp, int n_tiles, int k_tiles, Dst dst) {
 }
 
 bool weights_ok(const spd_layer_weights *w) {
-    return w && w->wq && w->wk && w->wv && w->wo && w->wg && w->wu && w->wd && w->g1 && w->g2;
+    return w && w->wq && w->wk && w->wv && w->wo && w->wg && w->wu && w->wd && w->g1 && w->g2;     // bo: see bias_ok()
 }
+
+bool bias_ok(const spd_ctx *ctx, const spd_layer_weights *w) { return (ctx->D.o_bias != 0) == (w->bo != nullptr); }
 
 }  // namespace
 
@@ -186,6 +190,7 @@ int spd_create(const spd_config *cfg, spd_ctx **out) {
     if (c.max_batch > SPD_MAX_BATCH || c.max_ctx % 32) return SPD_EINVAL;
     if (c.max_tokens < c.max_batch) return SPD_EINVAL;
     if (c.dtype != SPD_F32 && c.dtype != SPD_BF16) return SPD_EUNSUPPORTED;
+    if (c.o_bias != 0 && c.o_bias != 1) return SPD_EINVAL;
     if (c.act_split != SPD_SPLIT_AUTO && c.act_split != SPD_SPLIT_ALWAYS && c.act_split != SPD_SPLIT_NEVER)
         return SPD_EINVAL;
     if (c.n_kv_heads < c.tp_degree) return SPD_EUNSUPPORTED;   // a KV head shared by several ranks
@@ -282,12 +287,13 @@ int spd_mask_from_sensitivity(const double *sensitivity, int32_t n_layers, int32
 }
 
 int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *packed_host) {
-    if (!ctx || !weights_ok(w) || !packed_host) return SPD_EINVAL;
+    if (!ctx || !weights_ok(w) || !packed_host || !bias_ok(ctx, w)) return SPD_EINVAL;
     const spd_dims &D = ctx->D;
     char *base = (char *)packed_host;
     std::memset(base, 0, D.weight_bytes);
     std::memcpy(base + D.w_g1, w->g1, (size_t)D.h * 4);
     std::memcpy(base + D.w_g2, w->g2, (size_t)D.h * 4);
+    if (D.o_bias) std::memcpy(base + D.w_bo, w->bo, (size_t)D.h * 4);
     const int h = D.h, d = D.d, q = D.q, kv = D.kv, f = D.f, qd = q * d, kvd = kv * d;
     if (D.dtype == SPD_F32) {
         float *wqkv = (float *)(base + D.w_qkv);
@@ -358,7 +364,7 @@ static bool is_permutation(const int32_t *p, int n) {
 
 int spd_pack_shard_grouped(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, const int32_t *kv_heads,
                            const int32_t *mlp_of_rank, void *packed_host) {
-    if (!ctx || !weights_ok(dense) || !packed_host) return SPD_EINVAL;
+    if (!ctx || !weights_ok(dense) || !packed_host || !bias_ok(ctx, dense)) return SPD_EINVAL;
     const spd_dims &D = ctx->D;
     if (rank < 0 || rank >= D.tp) return SPD_EINVAL;
     const int n_kv = ctx->cfg.n_kv_heads;
@@ -391,7 +397,7 @@ int spd_pack_shard_grouped(const spd_ctx *ctx, int32_t rank, const spd_layer_wei
 }
 
 int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host) {
-    if (!ctx || !weights_ok(dense) || !packed_host) return SPD_EINVAL;
+    if (!ctx || !weights_ok(dense) || !packed_host || !bias_ok(ctx, dense)) return SPD_EINVAL;
     const spd_dims &D = ctx->D;
     if (rank < 0 || rank >= D.tp) return SPD_EINVAL;
     spd_layer_weights s = *dense;
@@ -414,6 +420,7 @@ int spd_unpack_shard(const spd_ctx *ctx, const void *packed_host, const spd_laye
     float *wg = (float *)o->wg, *wu = (float *)o->wu, *wd = (float *)o->wd;
     std::memcpy((float *)o->g1, base + D.w_g1, (size_t)h * 4);
     std::memcpy((float *)o->g2, base + D.w_g2, (size_t)h * 4);
+    if (D.o_bias && o->bo) std::memcpy((float *)o->bo, base + D.w_bo, (size_t)h * 4);
     if (D.dtype == SPD_F32) {
         const float *wqkv = (const float *)(base + D.w_qkv);
         for (int k = 0; k < h; ++k) {

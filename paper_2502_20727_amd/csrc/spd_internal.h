@@ -73,6 +73,8 @@ struct spd_dims {
     int h, q, kv, d, f, f_pad, group, nqkv, tp, dtype;
     int gud_cols, gud_groups;     // decode-only gate/up copy: FFN columns per workgroup and number of groups (0: none)
     size_t w_gud;                 // its offset in a layer's packed weights
+    int o_bias;                   // the output projection has a bias, kept at w_bo (fp32, [h])
+    size_t w_bo;
     int max_batch, max_ctx, max_tokens, m_pad;
     float eps, rope_base;
     // packed shard (bytes from its start)
@@ -129,7 +131,9 @@ struct scope {
 }
 
 namespace spd_common {
-hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s);
+// out = base + (slot_0 + ... ) [+ bias[i % h] when bias is given]
+hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s,
+                    const float *bias = nullptr, int h = 0);
 hipError_t fill_zero_u32(uint32_t *p, size_t n, hipStream_t s);
 hipError_t copy2d(const float *src, int lds, float *dst, int ldd, int rows, int cols, hipStream_t s);
 }
@@ -144,8 +148,9 @@ hipError_t mlp_half(const spd_call &c, const char *w, const float *r_in, const f
 namespace spd_bf16 {
 // out = base + sum slots (optional), xhat = bf16(out * g) packed (optional), partial sums of squares
 // which = 0: the block's first norm (xhat, ss1); which = 1: its second norm (xhat2, ss2)
+// bias (may be NULL): [h], added to `out` after the sum
 hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_slots, float *out,
-                const float *gain, bool want_xhat, int which);
+                const float *gain, bool want_xhat, int which, const float *bias = nullptr);
 // QKV + rotary + cache append + attention + O projection.
 //   spd = 1: ybuf <- Y_r, xhat2 <- bf16((X + Y_r) g2) and its partial sums of squares
 //   spd = 0: slot <- Y_r
@@ -159,6 +164,7 @@ struct spd_end_sync {
     int tp, rank;
     float *x_out;
     const float *next_g1;
+    const float *bias;        // [h] added once after the sum (SPD block with bias), or NULL
 };
 // gate/up + SwiGLU + down.  spd = 1: slot <- ybuf + Z_r; spd = 0: slot <- Z_r.  With `fuse`
 // (calls of at most 16 tokens) the down projection's epilogue also performs the end-of-block

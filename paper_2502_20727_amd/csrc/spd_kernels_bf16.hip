@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
                                               int n_slots, size_t slot_stride, float *__restrict__ out,
                                               const float *__restrict__ gain, __bf16 *__restrict__ xhat,
                                               __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h, int tpw,
-                                              int m_pad) {
+                                              int m_pad, const float *__restrict__ bias) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int KT = h >> 5;
     const int chunk = blockIdx.x * 4 + wave;
@@ -109,6 +109,11 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
                 const float4 b0 = *(const float4 *)(base + o), b1 = *(const float4 *)(base + o + 4);
                 v[0] = b0.x + v[0]; v[1] = b0.y + v[1]; v[2] = b0.z + v[2]; v[3] = b0.w + v[3];
                 v[4] = b1.x + v[4]; v[5] = b1.y + v[5]; v[6] = b1.z + v[6]; v[7] = b1.w + v[7];
+            }
+            if (bias) {      // the output projection's bias, once, after the sum (Sec. 4.1.2)
+                const float4 c0 = *(const float4 *)(bias + col), c1 = *(const float4 *)(bias + col + 4);
+                v[0] += c0.x; v[1] += c0.y; v[2] += c0.z; v[3] += c0.w;
+                v[4] += c1.x; v[5] += c1.y; v[6] += c1.z; v[7] += c1.w;
             }
             if (out) {
                 *(float4 *)(out + o) = make_float4(v[0], v[1], v[2], v[3]);
@@ -267,6 +272,7 @@ struct EpiO {
     static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
+    const float *bo = nullptr; // bias of the output projection or NULL: part of the SPD block's MLP input (Sec. 4.1.2)
     float *ybuf, *slot, *ss2;
     __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
     struct Pre {
@@ -282,6 +288,11 @@ struct EpiO {
             const size_t o = (size_t)m * h;
             p.x0 = *(const float4 *)(x + o + na);
             p.x1 = *(const float4 *)(x + o + nb);
+            if (bo) {        // X + b now, P_r when the accumulators are there
+                const float4 ba = *(const float4 *)(bo + na), bb = *(const float4 *)(bo + nb);
+                p.x0.x += ba.x; p.x0.y += ba.y; p.x0.z += ba.z; p.x0.w += ba.w;
+                p.x1.x += bb.x; p.x1.y += bb.y; p.x1.z += bb.z; p.x1.w += bb.w;
+            }
             p.ga = *(const float4 *)(g2 + na);
             p.gb = *(const float4 *)(g2 + nb);
         }
@@ -381,6 +392,7 @@ struct EpiDownT {
     // optional: the sync point that ends the block, fused (one rank; the peers' partial sums are
     // inputs).  base == NULL: not fused.
     const float *base, *slots, *g1;
+    const float *bias;         // [h] added once after the sum (SPD block with bias) or NULL
     size_t slot_stride;
     int tp, rank, m_pad;
     float *x_out, *ss1;
@@ -419,7 +431,12 @@ struct EpiDownT {
             }
         }
         const float4 bs = *(const float4 *)(base + o);
-        return make_float4(bs.x + acc.x, bs.y + acc.y, bs.z + acc.z, bs.w + acc.w);
+        float4 r = make_float4(bs.x + acc.x, bs.y + acc.y, bs.z + acc.z, bs.w + acc.w);
+        if (bias) {
+            const float4 bb = *(const float4 *)(bias + (o % (size_t)h));
+            r.x += bb.x; r.y += bb.y; r.z += bb.z; r.w += bb.w;
+        }
+        return r;
     }
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float, const Pre &p) const {
@@ -1379,17 +1396,17 @@ inline int prep_nch(int h, int M) { return (int)cdiv(h / 32, prep_tpw(M)); }
 namespace spd_bf16 {
 
 hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_slots, float *out, const float *gain,
-                bool want_xhat, int which) {
+                bool want_xhat, int which, const float *bias) {
     const spd_dims &D = *c.D;
     const int tpw = prep_tpw(c.M), nch = prep_nch(D.h, c.M);
     __bf16 *xhat = want_xhat ? (__bf16 *)(c.ws + (which ? D.ws_xhat2 : D.ws_xhat)) : nullptr;
     __bf16 *xlo = (want_xhat && (which ? c.split : c.split_all)) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
-    if (n_slots == 0 && out == base) out = nullptr;   // nothing to rewrite
+    if (n_slots == 0 && out == base && !bias) out = nullptr;   // nothing to rewrite
     if (!spd_profile::enabled(SPD_STAGE_PREP)) return hipSuccess;
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
     hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                       (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad);
+                       (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
     return hipGetLastError();
 }
 
@@ -1495,6 +1512,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     EpiO e2;
     e2.M = M; e2.h = D.h; e2.spd = spd; e2.m_pad = D.m_pad;
     e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
+    e2.bo = D.o_bias ? (const float *)(w + D.w_bo) : nullptr;
     e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
     e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
     e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
@@ -1551,11 +1569,11 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     auto fill = [&](auto &e2) {
         e2.M = M; e2.h = D.h; e2.spd = spd;
         e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
-        e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
+        e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.bias = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
         e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
         if (do_fuse) {
             e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp;
-            e2.rank = fuse->rank; e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.ss1 = (float *)(c.ws + D.ws_ss1);
+            e2.rank = fuse->rank; e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.bias = fuse->bias; e2.ss1 = (float *)(c.ws + D.ws_ss1);
             if (fuse->next_g1) {
                 e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);
                 e2.xlo = c.split_all ? e2.xhat + D.pl_x : nullptr;

@@ -7,7 +7,7 @@ namespace {
 constexpr int TB = 256;
 
 __global__ void k_rank_sum(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
-                           int64_t n, float *__restrict__ out) {
+                           int64_t n, float *__restrict__ out, const float *__restrict__ bias, int h) {
     // partials are summed in ascending slot order, the base is added last
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -16,11 +16,13 @@ __global__ void k_rank_sum(const float *__restrict__ base, const float *__restri
         acc = slots[i];
         for (int s = 1; s < n_slots; ++s) acc += slots[(int64_t)s * n + i];
     }
-    out[i] = base ? base[i] + acc : acc;
+    if (base) acc = base[i] + acc;
+    if (bias) acc += bias[i % h];          // the output projection's bias, once, after the sum
+    out[i] = acc;
 }
 
 __global__ void k_rank_sum4(const float4 *__restrict__ base, const float4 *__restrict__ slots, int n_slots,
-                            int64_t n4, float4 *__restrict__ out) {
+                            int64_t n4, float4 *__restrict__ out, const float4 *__restrict__ bias, int h4) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n4) return;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -34,6 +36,10 @@ __global__ void k_rank_sum4(const float4 *__restrict__ base, const float4 *__res
     if (base) {
         const float4 b = base[i];
         acc.x = b.x + acc.x; acc.y = b.y + acc.y; acc.z = b.z + acc.z; acc.w = b.w + acc.w;
+    }
+    if (bias) {
+        const float4 b = bias[i % h4];
+        acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
     }
     out[i] = acc;
 }
@@ -202,14 +208,16 @@ hipError_t gemm(const float *A, int lda, const float *W, int ldw, const float *a
 
 namespace spd_common {
 
-hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s) {
+hipError_t rank_sum(const float *base, const float *slots, int n_slots, int64_t n, float *out, hipStream_t s,
+                    const float *bias, int h) {
     if (n <= 0) return hipSuccess;
-    const bool al = ((((uintptr_t)base) | ((uintptr_t)slots) | ((uintptr_t)out)) & 15) == 0 && (n % 4) == 0;
+    const bool al = ((((uintptr_t)base) | ((uintptr_t)slots) | ((uintptr_t)out) | ((uintptr_t)bias)) & 15) == 0 &&
+                    (n % 4) == 0 && (!bias || h % 4 == 0);
     if (al)
         hipLaunchKernelGGL(k_rank_sum4, dim3(blocks_for(n / 4)), dim3(TB), 0, s, (const float4 *)base,
-                           (const float4 *)slots, n_slots, n / 4, (float4 *)out);
+                           (const float4 *)slots, n_slots, n / 4, (float4 *)out, (const float4 *)bias, h / 4);
     else
-        hipLaunchKernelGGL(k_rank_sum, dim3(blocks_for(n)), dim3(TB), 0, s, base, slots, n_slots, n, out);
+        hipLaunchKernelGGL(k_rank_sum, dim3(blocks_for(n)), dim3(TB), 0, s, base, slots, n_slots, n, out, bias, h);
     return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ from .workloads import BF16, Workload
 # tensor ids (part of the generator key)
 T_WQ, T_WK, T_WV, T_WO, T_WG, T_WU, T_WD, T_G1, T_G2 = range(1, 10)
 T_X, T_KCACHE, T_VCACHE, T_SLOTS, T_MISC = range(10, 15)
+T_BO = 15
 
 _LIB = None
 
@@ -80,6 +81,11 @@ def layer_shard(w: Workload, layer: int, rank: int) -> Dict[str, np.ndarray]:
         "g1": normal((h,), s, T_G1, layer, 0, mean=1.0, std=0.02),
         "g2": normal((h,), s, T_G2, layer, 0, mean=1.0, std=0.02),
     }
+
+
+def output_bias(w: Workload, layer: int, std: float = 0.5) -> np.ndarray:
+    """[hidden] bias of the attention output projection for the block-with-bias variant (fp32, the same on every rank)."""
+    return normal((w.hidden,), w.seed, T_BO, layer, 0, std=std)
 
 
 def dense_layer(w: Workload, layer: int) -> Dict[str, np.ndarray]:

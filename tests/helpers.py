@@ -45,7 +45,8 @@ class Case:
 
     def __init__(self, w: Workload, device, ranks: Sequence[int], positions: Sequence[int],
                  layer_ids: Optional[Sequence[int]] = None, max_ctx: Optional[int] = None,
-                 max_tokens: Optional[int] = None, prefill_layers: bool = True, act_split: int = 0):
+                 max_tokens: Optional[int] = None, prefill_layers: bool = True, act_split: int = 0,
+                 bias_std: float = 0.0):
         import torch
         self.torch = torch
         self.w = w
@@ -55,7 +56,7 @@ class Case:
         self.layer_ids = list(layer_ids) if layer_ids is not None else list(range(w.n_layers))
         assert len(self.layer_ids) == w.n_layers
         self.dev = B.DeviceShard(w, self.ranks, device, max_ctx=max_ctx, max_tokens=max_tokens,
-                                 max_batch=len(self.positions), act_split=act_split)
+                                 max_batch=len(self.positions), act_split=act_split, o_bias=1 if bias_std else 0)
         mc = self.dev.cfg.max_ctx
         self.shards: List[List[dict]] = []
         self.caches: List[List[O.KVCache]] = []
@@ -63,6 +64,10 @@ class Case:
         n_pre = max(self.positions) if self.positions else 0
         for li, layer in enumerate(self.layer_ids):
             sh = [inputs.layer_shard(w, layer, r) for r in self.ranks]
+            if bias_std:     # block with bias: the same output-projection bias on every rank
+                bo = inputs.output_bias(w, layer, bias_std)
+                for d in sh:
+                    d["bo"] = bo
             self.shards.append(sh)
             self.dev.load_layer(li, sh)
             caches, kvs = [], []

@@ -190,6 +190,45 @@ def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
 
 
 # ------------------------------------------------------------------------------------------------
+# block with bias in the output projection (Sec. 4.1.2): both paths, both block kinds
+# ------------------------------------------------------------------------------------------------
+TOY_BIAS = Workload(name="toy-f32-bias", hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn=344, n_layers=3, tp=2,
+                    dtype=F32, seed=15, batch=2, q_len=1, ctx=32, mask=(1, 0, 1))
+SMALL_BIAS = Workload(name="small-bf16-bias", hidden=256, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=832, n_layers=3,
+                      tp=4, dtype=BF16, seed=16, batch=3, q_len=1, ctx=64, mask=(1, 0, 1))
+
+
+@pytest.mark.parametrize("w", [TOY_BIAS, SMALL_BIAS], ids=lambda w: w.name)
+@pytest.mark.parametrize("batch,q_len,positions", [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8])],
+                         ids=["decode", "chunk20", "chunk80"])
+@pytest.mark.parametrize("mode", ["all-ranks", "one-rank"])
+def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
+    """Three blocks (SPD, TP, SPD) with a bias of the size of the activations on the output projection:
+    model forward against the oracle, with every rank emulated and from one rank's point of view."""
+    import torch
+    M = batch * q_len
+    ranks = list(range(w.tp)) if mode == "all-ranks" else [1]
+    case = Case(w, gpu, ranks=ranks, positions=positions, max_ctx=64, max_tokens=max(48, M), bias_std=1.0)
+    X = inputs.hidden_states(w, M)
+    say(f"case {w.name} {mode} batch={batch} q_len={q_len}")
+    peers = inputs.peer_slots(w, M) if mode == "one-rank" else np.zeros((w.tp, M, w.hidden), np.float32)
+    slots = case.to_dev(peers).reshape(w.tp, M, w.hidden)
+    out = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward(case.dev.ctx, w.mask, case.dev.rank_arg(), case.dev.weights, case.dev.kv, positions,
+                                batch, q_len, case.to_dev(X), slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    assert syncs == 4
+    if mode == "all-ranks":
+        want, _ = O.model_all_ranks(case.sh, X, case.shards, case.caches, positions, batch, q_len, w.mask)
+    else:
+        want = O.model_single_rank(case.sh, X, [s[0] for s in case.shards], [c[0] for c in case.caches], positions,
+                                   batch, q_len, w.mask, 1, peers.astype(np.float64))
+    err = assert_close(out.cpu().numpy(), want, w, f"{w.name} {mode}", scale=3.0 if w.dtype == BF16 else 1.0)
+    say(f"  max err {err:.2e} (max |oracle| {np.max(np.abs(want)):.2f})")
+    case.close()
+
+
+# ------------------------------------------------------------------------------------------------
 # bf16 path, one rank of eight with peer slots as inputs, several layers, mixed mask
 # ------------------------------------------------------------------------------------------------
 MID = Workload(name="mid-bf16", hidden=1024, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=11008, n_layers=4,

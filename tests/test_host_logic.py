@@ -265,6 +265,34 @@ def test_pack_keeps_a_second_gate_up_copy_when_tiles_do_not_fill_the_chip():
     B.spd_destroy(ctx)
 
 
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32])
+def test_pack_with_output_bias(w):
+    # block with bias (Sec. 4.1.2): the bias travels with the packed shard, in fp32, and must be given
+    # exactly when the configuration says the block has one
+    ctx_b, ctx = B.spd_create(B.make_config(w, o_bias=1)), B.spd_create(B.make_config(w))
+    shard = inputs.layer_shard(w, 0, 1)
+    bo = (inputs.output_bias(w, 0) * (1.0 + 2.0 ** -20)).astype(np.float32)       # not bf16 values: kept as fp32
+    with pytest.raises(B.SpdError):
+        B.spd_pack_shard_local(ctx_b, shard)                 # bias missing
+    with pytest.raises(B.SpdError):
+        B.spd_pack_shard_local(ctx, dict(shard, bo=bo))      # bias not expected
+    packed = B.spd_pack_shard_local(ctx_b, dict(shard, bo=bo))
+    assert packed.size == B.spd_get_sizes(ctx_b).weight_bytes > B.spd_get_sizes(ctx).weight_bytes
+    shapes = {k: v.shape for k, v in shard.items()}
+    shapes["bo"] = bo.shape
+    back = B.spd_unpack_shard(ctx_b, packed, shapes)
+    assert np.array_equal(back["bo"], bo)
+    for k in shard:
+        assert np.array_equal(back[k], shard[k]), k
+    bad = B.make_config(w)
+    bad.o_bias = 2
+    with pytest.raises(B.SpdError) as e:
+        B.spd_create(bad)
+    assert e.value.code == B.SPD_EINVAL
+    B.spd_destroy(ctx_b)
+    B.spd_destroy(ctx)
+
+
 def test_pack_rejects_values_that_are_not_bf16():
     w = SMALL_BF16
     ctx = B.spd_create(B.make_config(w))
