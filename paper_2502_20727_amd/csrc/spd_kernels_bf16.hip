@@ -226,29 +226,31 @@ struct EpiQKV {
 // the slices in ascending order, rounds, and appends the new key and value to the cache.
 struct EpiQKVPart {
     static constexpr bool kNeedsRs = true;
-    int M, q, kv, d, h, nqkv, nch, m_pad;
+    int M, q_len, q, kv, d, h, nqkv, nch, m_pad;
+    int part_rows;             // token rows per slice of `part`
     float eps;
     const float *ss, *cosT, *sinT;
     float *part;
     spd_positions P;
     typedef EpiQKV::Pre Pre;
 
-    __device__ __forceinline__ Pre pre(int pair, int, int lane) const {
+    __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
         Pre p;
         p.c = p.s = make_float4(0.f, 0.f, 0.f, 0.f);
-        const int m = lane & 15, g = lane >> 4;
+        const int m = mt * 16 + (lane & 15), g = lane >> 4;
         const int tph = d >> 4, half = d >> 1;
         const int head = (2 * pair) / tph;
         if (m < M && head < q + kv) {
+            const int pos = P.pos[m / q_len] + (m % q_len);
             const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;
-            p.c = *(const float4 *)(cosT + (size_t)P.pos[m] * half + ca);
-            p.s = *(const float4 *)(sinT + (size_t)P.pos[m] * half + ca);
+            p.c = *(const float4 *)(cosT + (size_t)pos * half + ca);
+            p.s = *(const float4 *)(sinT + (size_t)pos * half + ca);
         }
         return p;
     }
 
-    __device__ __forceinline__ void slice(int pair, int ks, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
-        const int m = lane & 15, g = lane >> 4;
+    __device__ __forceinline__ void slice(int pair, int ks, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
+        const int m = mt * 16 + (lane & 15), g = lane >> 4;
         if (m >= M) return;
         const int tph = d >> 4;
         const int head = (2 * pair) / tph;
@@ -262,7 +264,7 @@ struct EpiQKVPart {
             lo = make_float4(a[0] * c.x - b[0] * s.x, a[1] * c.y - b[1] * s.y, a[2] * c.z - b[2] * s.z, a[3] * c.w - b[3] * s.w);
             hi = make_float4(b[0] * c.x + a[0] * s.x, b[1] * c.y + a[1] * s.y, b[2] * c.z + a[2] * s.z, b[3] * c.w + a[3] * s.w);
         }
-        float *dst = part + ((size_t)ks * 16 + m) * nqkv;
+        float *dst = part + ((size_t)ks * part_rows + m) * nqkv;
         *(float4 *)(dst + ca) = lo;
         *(float4 *)(dst + cb) = hi;
     }
@@ -625,7 +627,7 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         sq += shfl_xor_f(sq, 32);
         rs = 1.0f / sqrtf(sq / (float)epi.h + epi.eps);
     }
-    if constexpr (MODE == 2) epi.slice(pair, ks, a, b, lane, rs, pre);
+    if constexpr (MODE == 2) epi.slice(pair, ks, 0, a, b, lane, rs, pre);
     else epi(pair, 0, a, b, lane, rs, pre);
 }
 
@@ -682,6 +684,144 @@ __global__ void __launch_bounds__(256) k_gemv_finish(const float *__restrict__ k
         rs = 1.0f / sqrtf(sq / (float)epi.h + epi.eps);
     }
     epi(pair, 0, a, b, lane, rs, pre);
+}
+
+// ------------------------------------------------------------------------------------------
+// Projection for 17 .. 16*MT tokens per workgroup ("skinny": still bound by streaming the weights).
+// Like k_gemv, one workgroup per pair of n-tiles (or narrow group) and slice of K, the W waves
+// splitting K; every wave multiplies each weight fragment it streams with MT m-tiles of
+// activations (read through the L2, where they stay resident).  grid = (pairs, KS, groups of MT
+// m-tiles).  The W x MT partial tile pairs meet in LDS; wave w finishes m-tiles w, w + W, ...
+//   MODE 0: whole K (KS = 1), Epi::operator();  MODE 2: K slices, Epi::slice (linear epilogues)
+// ------------------------------------------------------------------------------------------
+template <int MT, bool SPLIT>
+struct SkinnyBatch {
+    bf16x8 fa, fb, fh[MT], fl[SPLIT ? MT : 1];
+};
+
+template <int W, int MT, bool SPLIT, int MODE, class Epi>
+__global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
+                                                    const __bf16 *__restrict__ Xlo, int KT, int KS, int n_mtiles, int rows,
+                                                    Epi epi) {
+    extern __shared__ __attribute__((aligned(16))) char sk_lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pair = blockIdx.x, ks = blockIdx.y, mt0 = blockIdx.z * MT;
+    const int kb0 = (int)(((long)ks * KT) / KS), kb1 = (int)(((long)(ks + 1) * KT) / KS);
+    const int nk = kb1 - kb0;
+    const int k0 = kb0 + (wave * nk) / W, k1 = kb0 + ((wave + 1) * nk) / W;
+    f32x4 acc[MT][2];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[i][0] = acc[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const bf16x8 *wa, *wb;
+    size_t kstr;
+    if (rows == 16) {
+        wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
+        wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
+        kstr = 64;
+    } else {
+        const int rr = (lane & 15) < rows ? (lane & 15) : rows - 1;
+        wa = (const bf16x8 *)Wp + (size_t)pair * KT * 8 * rows + (lane >> 4) * rows + rr;
+        wb = wa + 4 * rows;
+        kstr = 8 * rows;
+    }
+    // m-tiles past the call's last one repeat it (their results are dropped)
+    const bf16x8 *xh[MT], *xl[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int mt = mt0 + i < n_mtiles ? mt0 + i : n_mtiles - 1;
+        xh[i] = (const bf16x8 *)(Xhi + spd_frag_index(mt, 0, KT)) + lane;
+        xl[i] = (const bf16x8 *)(Xlo + spd_frag_index(mt, 0, KT)) + lane;
+    }
+    auto load = [&](SkinnyBatch<MT, SPLIT> &B, int kt) {
+        B.fa = __builtin_nontemporal_load(wa + (size_t)kt * kstr);
+        B.fb = __builtin_nontemporal_load(wb + (size_t)kt * kstr);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            B.fh[i] = xh[i][(size_t)kt * 64];
+            if (SPLIT) B.fl[i] = xl[i][(size_t)kt * 64];
+        }
+    };
+    auto consume = [&](const SkinnyBatch<MT, SPLIT> &B) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            acc[i][0] = MFMA(B.fa, B.fh[i], acc[i][0]);
+            acc[i][1] = MFMA(B.fb, B.fh[i], acc[i][1]);
+            if (SPLIT) {
+                acc[i][0] = MFMA(B.fa, B.fl[i], acc[i][0]);
+                acc[i][1] = MFMA(B.fb, B.fl[i], acc[i][1]);
+            }
+        }
+    };
+    const int n = k1 - k0;
+    SkinnyBatch<MT, SPLIT> cur, oth;
+    if (n > 0) load(cur, k0);
+    int i = 0;
+    for (; i + 2 < n; i += 2) {          // steady state: no branch between the loads and their use
+        load(oth, k0 + i + 1);
+        consume(cur);
+        load(cur, k0 + i + 2);
+        consume(oth);
+    }
+    if (i + 1 < n) {
+        load(oth, k0 + i + 1);
+        consume(cur);
+        consume(oth);
+    } else if (i < n) {
+        consume(cur);
+    }
+    f32x4 *red = (f32x4 *)sk_lds;        // [W][MT][2][64]
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        red[((wave * MT + t) * 2 + 0) * 64 + lane] = acc[t][0];
+        red[((wave * MT + t) * 2 + 1) * 64 + lane] = acc[t][1];
+    }
+    __syncthreads();
+    for (int t = wave; t < MT; t += W) {
+        const int mt = mt0 + t;
+        if (mt >= n_mtiles) break;
+        f32x4 a = red[((0 * MT + t) * 2 + 0) * 64 + lane], b = red[((0 * MT + t) * 2 + 1) * 64 + lane];
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+            a += red[((w * MT + t) * 2 + 0) * 64 + lane];
+            b += red[((w * MT + t) * 2 + 1) * 64 + lane];
+        }
+        float rs = 1.f;
+        if constexpr (Epi::kNeedsRs) rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
+        if constexpr (MODE == 2) epi.slice(pair, ks, mt, a, b, lane, rs, epi.pre(pair, mt, lane));
+        else epi(pair, mt, a, b, lane, rs, epi.pre(pair, mt, lane));
+    }
+}
+
+// Adds the K slices that EpiQKVPart left for a call of more than one token per sequence (the
+// decode kernel adds them itself): queries to hi + lo bf16 pairs, keys and values rounded into the
+// cache.  One thread per 4 consecutive columns of a token.
+__global__ void __launch_bounds__(256) k_qkv_gather(const float *__restrict__ part, int KS, int m_pad, int M, int q_len, int q,
+                                                    int kv, int d, int max_ctx, spd_positions P, __bf16 *__restrict__ qbuf,
+                                                    __bf16 *__restrict__ qlo, __bf16 *__restrict__ kc, __bf16 *__restrict__ vc) {
+    const int nqkv = (q + 2 * kv) * d, n4 = nqkv / 4;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)M * n4) return;
+    const int m = (int)(id / n4), col = (int)(id % n4) * 4;
+    const float *src = part + (size_t)m * nqkv + col;
+    float4 acc = *(const float4 *)src;
+    for (int s = 1; s < KS; ++s) {
+        const float4 v = *(const float4 *)(src + (size_t)s * m_pad * nqkv);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const bf16x4 hi = cvt4(acc.x, acc.y, acc.z, acc.w);
+    const int qd = q * d, bseq = m / q_len, pos = P.pos[bseq] + (m % q_len);
+    if (col < qd) {
+        *(bf16x4 *)(qbuf + (size_t)m * qd + col) = hi;
+        *(bf16x4 *)(qlo + (size_t)m * qd + col) = cvt4_lo(acc.x, acc.y, acc.z, acc.w, hi);
+    } else if (col < qd + kv * d) {
+        const int c = col - qd, head = c / d, dc = c % d;
+        *(bf16x4 *)(kc + ((size_t)bseq * kv + head) * (size_t)max_ctx * d + spd_kcache_off(pos, dc, d)) = hi;
+    } else {
+        const int c = col - qd - kv * d, head = c / d, dc = c % d;
+        __bf16 *dst = vc + ((size_t)bseq * kv + head) * (size_t)max_ctx * d;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dst[spd_vcache_off(pos, dc + i, d)] = hi[i];
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1370,6 +1510,36 @@ hipError_t launch_gemv_sliced(const spd_call &c, bool split, const __bf16 *Wp, c
     return hipGetLastError();
 }
 
+// 17 .. 512 tokens: the skinny kernel, groups of MT m-tiles in grid.z.  KS > 1 only with MODE 2.
+constexpr int SKINNY_W = 8;
+template <int MT, bool SPLIT, int MODE, class Epi>
+hipError_t launch_skinny_mt(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, const __bf16 *Xlo, int n_groups, int KT,
+                            int KS, int n_mtiles, int rows, const Epi &epi) {
+    constexpr int lds = SKINNY_W * MT * 2 * 1024;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_skinny<SKINNY_W, MT, SPLIT, MODE, Epi>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_skinny<SKINNY_W, MT, SPLIT, MODE, Epi>), dim3(n_groups, KS, (n_mtiles + MT - 1) / MT), dim3(SKINNY_W * 64),
+                       lds, c.s, Wp, Xhi, Xlo, KT, KS, n_mtiles, rows, epi);
+    return hipGetLastError();
+}
+template <int MODE, class Epi>
+hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_groups, int KT,
+                         int KS, int rows, const Epi &epi) {
+    const int n_mtiles = (c.M + 15) / 16;
+    const __bf16 *Xlo = Xhi + plane;
+    if (n_mtiles <= 4)
+        return split ? launch_skinny_mt<4, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
+                     : launch_skinny_mt<4, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
+    return split ? launch_skinny_mt<8, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
+                 : launch_skinny_mt<8, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
+}
+constexpr int SKINNY_MAX_MTILES = 32;      // beyond 512 tokens the LDS-tiled GEMM re-reads the weights less often
+
 template <class Epi>
 hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
                        const Epi &epi) {
@@ -1377,6 +1547,7 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
     const __bf16 *Xlo = Xhi + plane;
     if (n_mtiles == 1)
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
+    if (n_mtiles <= SKINNY_MAX_MTILES) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
     if (!split && (KT % 2) == 0 && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
     constexpr int MT = 4, W = 4;
     const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
@@ -1388,7 +1559,8 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
 }
 
 // chunking of the sum-of-squares partials written by prep()
-inline int prep_tpw(int M) { return M <= 64 ? 1 : 8; }
+// k-tiles per wave of k_prep: enough waves to occupy the chip at every call size
+inline int prep_tpw(int M) { return M <= 64 ? 1 : (M <= 512 ? 2 : 8); }
 inline int prep_nch(int h, int M) { return (int)cdiv(h / 32, prep_tpw(M)); }
 
 }  // namespace
@@ -1422,28 +1594,42 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     __bf16 *kc = (__bf16 *)kvc, *vc = (__bf16 *)(kvc + D.kv_v);
     float *ybuf = (float *)(c.ws + D.ws_y);
 
-    // a decode step whose QKV projection needs K slices hands the slices to the attention kernel
-    // (no second kernel to add them up); every other shape finishes Q, K and V in the projection
-    int qkv_slices = (c.q_len == 1 && M <= 16) ? gemv_slices(D.nqkv / 32, D.h / 32) : 1;
-    const bool fused_q = qkv_slices > 1;
-    if (fused_q) {      // about 320 workgroups of 8 waves, at most SPD_MAX_QKV_SLICES slices
-        const int want = (320 + D.nqkv / 32 - 1) / (D.nqkv / 32);
+    // K-sliced QKV projections (too few column tiles to occupy the chip) with the linear epilogue:
+    //  - a decode step hands the slices to the attention kernel (no second kernel to add them up);
+    //  - a call of 17 .. 512 tokens adds them with a small gather kernel
+    const int n_mtiles = (M + 15) / 16, qkv_pairs = D.nqkv / 32;
+    int qkv_slices = 1;
+    bool fused_q = false, gather_q = false;
+    if (gemv_slices(qkv_pairs, D.h / 32) > 1) {
+        // about 320 workgroups of 8 waves, at most SPD_MAX_QKV_SLICES slices, at least two k-tiles per wave
+        const int want = (320 + qkv_pairs - 1) / qkv_pairs;
         qkv_slices = want < 2 ? 2 : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
         if (qkv_slices > D.h / 32 / GEMV_SLICE_W) qkv_slices = D.h / 32 / GEMV_SLICE_W;
-        if (qkv_slices < 2) qkv_slices = 2;
+        while (qkv_slices > 1 && (size_t)qkv_slices * 16 * n_mtiles * D.nqkv > (size_t)SPD_MAX_KPART * 512) --qkv_slices;
+        fused_q = qkv_slices > 1 && c.q_len == 1 && n_mtiles == 1;
+        gather_q = qkv_slices > 1 && !fused_q && n_mtiles > 1 && n_mtiles <= SKINNY_MAX_MTILES;
+        if (!fused_q && !gather_q) qkv_slices = 1;
     }
     float *qkvp = (float *)(c.ws + D.ws_kpart);
-    if (fused_q) {
+    if (fused_q || gather_q) {
         EpiQKVPart e1;
-        e1.M = M; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
-        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
+        e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
+        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.part_rows = 16 * n_mtiles; e1.eps = D.eps;
         e1.ss = (const float *)(c.ws + D.ws_ss1);
         e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
         e1.part = qkvp; e1.P = c.pos;
         if (spd_profile::enabled(SPD_STAGE_QKV)) {
             spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-            SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32,
-                                       qkv_slices, e1));
+            if (fused_q) {
+                SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
+                                           qkv_slices, e1));
+            } else {
+                SPD_TRY(launch_skinny<2>(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
+                                         qkv_slices, 16, e1));
+                hipLaunchKernelGGL(k_qkv_gather, dim3(cdiv((int64_t)M * (D.nqkv / 4), 256)), dim3(256), 0, c.s, qkvp, qkv_slices,
+                                   16 * n_mtiles, M, c.q_len, D.q, D.kv, D.d, D.max_ctx, c.pos, qbuf, qlo, kc, vc);
+                SPD_TRY(hipGetLastError());
+            }
         }
     } else {
         EpiQKV e1;
@@ -1559,6 +1745,10 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             const __bf16 *wd = (const __bf16 *)(w + D.w_gud), *xlo = xhat + D.pl_x;
             SPD_TRY(c.split ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
                             : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
+        } else if (D.gud_cols && M <= 16 * SKINNY_MAX_MTILES) {
+            e1.cols = D.gud_cols;
+            SPD_TRY(launch_skinny<0>(c, c.split, (const __bf16 *)(w + D.w_gud), xhat, D.pl_x, D.gud_groups, D.h / 32, 1,
+                                     D.gud_cols, e1));
         } else {
             SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
         }
