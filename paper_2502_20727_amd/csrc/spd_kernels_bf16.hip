@@ -1469,8 +1469,10 @@ hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, c
     float *kpart = (float *)(c.ws + D.ws_kpart);
     if (n_pairs >= 192) {
         // enough pairs to occupy the chip: one workgroup per pair, no slices
-        if (KT >= 64) {
-            constexpr int W = 16, U = 2;     // 16 waves share 512 VGPRs per lane and SIMD: two batches of 2 k-tiles fit
+        if (KT >= 32) {
+            // 16 waves share 512 VGPRs per lane and SIMD: two batches of 2 k-tiles fit.  With as few as
+            // 2 k-tiles per wave everything is requested at once, which is what a short kernel wants.
+            constexpr int W = 16, U = 2;
             hipLaunchKernelGGL((k_gemv<W, U, SPLIT, 0, Epi>), dim3(n_pairs, 1), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT,
                                1, kpart, rows, epi);
         } else {
@@ -1495,11 +1497,13 @@ hipError_t launch_gemv(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, c
     return hipGetLastError();
 }
 
-// K-sliced launch for an epilogue that is linear in the accumulators (Epi::slice); no second kernel
+// K-sliced launch for an epilogue that is linear in the accumulators (Epi::slice); no second kernel.
+// Workgroups of 16 waves, about one per compute unit: every wave requests its whole share at once.
+constexpr int QKV_SLICE_W = 16;
 template <class Epi>
 hipError_t launch_gemv_sliced(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs,
                               int KT, int KS, const Epi &epi) {
-    constexpr int W = GEMV_SLICE_W, U = 2;
+    constexpr int W = QKV_SLICE_W, U = 2;
     const __bf16 *Xlo = Xhi + plane;
     if (split)
         hipLaunchKernelGGL((k_gemv<W, U, true, 2, Epi>), dim3(n_pairs, KS), dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, KS,
@@ -1601,10 +1605,12 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     int qkv_slices = 1;
     bool fused_q = false, gather_q = false;
     if (gemv_slices(qkv_pairs, D.h / 32) > 1) {
-        // about 320 workgroups of 8 waves, at most SPD_MAX_QKV_SLICES slices, at least two k-tiles per wave
-        const int want = (320 + qkv_pairs - 1) / qkv_pairs;
+        // decode: about 240 workgroups of 16 waves; 17 .. 512 tokens: about 320 of 8 waves; at most
+        // SPD_MAX_QKV_SLICES slices and at least two k-tiles per wave
+        const bool dec = c.q_len == 1 && n_mtiles == 1;
+        const int want = ((dec ? 240 : 320) + qkv_pairs - 1) / qkv_pairs, wv = dec ? QKV_SLICE_W : SKINNY_W;
         qkv_slices = want < 2 ? 2 : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
-        if (qkv_slices > D.h / 32 / GEMV_SLICE_W) qkv_slices = D.h / 32 / GEMV_SLICE_W;
+        if (qkv_slices > D.h / 32 / (2 * wv)) qkv_slices = D.h / 32 / (2 * wv);
         while (qkv_slices > 1 && (size_t)qkv_slices * 16 * n_mtiles * D.nqkv > (size_t)SPD_MAX_KPART * 512) --qkv_slices;
         fused_q = qkv_slices > 1 && c.q_len == 1 && n_mtiles == 1;
         gather_q = qkv_slices > 1 && !fused_q && n_mtiles > 1 && n_mtiles <= SKINNY_MAX_MTILES;
