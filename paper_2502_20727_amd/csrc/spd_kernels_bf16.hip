@@ -1249,17 +1249,20 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
         load_q<DT>(qf, qbuf_in, qlo_in, b, kvh * group + col, qd, d, cvalid, lane);
     }
     if (has_blocks) {
-        // two key blocks at a time, both loaded before the first is used (no branch in between, so
-        // that the second block's loads stay in flight while the first block is processed)
-        for (int vb = b0 + wave; vb < b1; vb += 8) {
-            const int vb2 = vb + 4 < b1 ? vb + 4 : vb;      // clamp: a repeated block is masked below
-            if (vb != b0 + wave) {
-                load_kv<DT>(f0, kbase, vbase, vb, d, lane);
-                load_kv<DT>(f1, kbase, vbase, vb2, d, lane);
-            }
-            attn_block<DT>(st, qf, f0, vb, cvalid ? n_keys : 0, scale, lane);
-            attn_block<DT>(st, qf, f1, vb2, (cvalid && vb + 4 < b1) ? n_keys : 0, scale, lane);
+        // the wave's blocks are b0 + wave + 4 j, j < nw.  Two register buffers used alternately: while
+        // one block is processed the loads of the next but one are already in flight.  No branch
+        // between loads and use: an index past the wave's last block repeats that block, masked.
+        const int nw = (b1 - b0 - wave + 3) >> 2;
+        auto blk = [&](int j) { return b0 + wave + 4 * (j < nw ? j : nw - 1); };
+        int j = 0;
+        for (; j + 2 < nw; j += 2) {
+            attn_block<DT>(st, qf, f0, blk(j), cvalid ? n_keys : 0, scale, lane);
+            load_kv<DT>(f0, kbase, vbase, blk(j + 2), d, lane);
+            attn_block<DT>(st, qf, f1, blk(j + 1), cvalid ? n_keys : 0, scale, lane);
+            load_kv<DT>(f1, kbase, vbase, blk(j + 3), d, lane);
         }
+        attn_block<DT>(st, qf, f0, blk(j), cvalid ? n_keys : 0, scale, lane);
+        attn_block<DT>(st, qf, f1, blk(j + 1), (cvalid && j + 1 < nw) ? n_keys : 0, scale, lane);
     }
     if (newtok && wave == 0) {
         // the new token as a block whose only key is key 0: K row 0, V contraction slot 0
@@ -1655,11 +1658,22 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     if (!spd_profile::enabled(SPD_STAGE_ATTN)) {
         // skipped
     } else if (c.q_len == 1) {
-        // about 8 key blocks (256 keys) per workgroup, two per wave
-        const int nblk = (c.max_pos_end + 31) / 32;
-        int splits = (nblk + 7) / 8;
-        if (splits < 1) splits = 1;
-        if (splits > SPD_MAX_SPLITS) splits = SPD_MAX_SPLITS;
+        // key blocks per workgroup (4 waves, so multiples of 4): the number of rounds the launch takes
+        // on 256 compute units times the length of a round, a round costing about 5 blocks' worth of
+        // start-up besides its blocks
+        const int nblk = (c.max_pos_end + 31) / 32, units = D.kv * c.batch;
+        int splits = 1;
+        long best = -1;
+        for (int per = 4; per <= 64; per += 4) {
+            int sp = (nblk + per - 1) / per;
+            if (sp < 1) sp = 1;
+            if (sp > SPD_MAX_SPLITS) continue;
+            const long rounds = ((long)sp * units + 255) / 256, cost = rounds * (per + 5);
+            if (best < 0 || cost < best) {
+                best = cost;
+                splits = sp;
+            }
+        }
         float *part = (float *)(c.ws + D.ws_apart);
         const dim3 grid(splits, D.kv, c.batch);
 #define SPD_DECODE(DTV)                                                                                              \
