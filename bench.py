@@ -30,7 +30,7 @@ import numpy as np
 # this script (summaries and the copy-kernel calibration are under profiles/); None = not measured.
 # FETCH_SIZE counts 2 KiB per unit on this device (a 1 GiB copy reads 524300), WRITE_SIZE 1 KiB.
 MEASURED_TRAFFIC = {
-    "llama2-70b-tp8-decode-b16-ctx4096": (59513 * 2 + 224) * 1024,        # 122.1 MB vs 117.9 MB algorithmic
+    "llama2-70b-tp8-decode-b16-ctx4096": (59518 * 2 + 320) * 1024,        # 122.2 MB vs 117.9 MB algorithmic
     "llama2-70b-tp8-prefill-b4x2048": (1078690 * 2 + 57344) * 1024,       # 2.27 GB: tiles re-read past the L2
 }
 
@@ -278,7 +278,7 @@ def main():
         roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=8000.0, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
-    roof["kernel"] = "k_gemm_lds<EpiGU>" if prefill else "k_gemv<16,2,split,EpiGU>"
+    roof["kernel"] = "k_gemm_lds<EpiGU>" if prefill else "k_gemv<16,2,split,0,EpiGU>"
     roof["stage"] = "gate/up projection + SwiGLU"
     roof["launches_timed"] = n
     roof["mean_us"] = mean_us
