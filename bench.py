@@ -9,7 +9,7 @@ the workload's SPD mask; the same model is also timed with every sync point kept
 
   python bench.py [--workload 70b-decode|7b-decode|13b-decode|70b-prefill] [--steps K] [--warmup W]
 
-Prints ONE JSON line (see the design doc for the fields).
+Prints ONE JSON line: metric, value (us per layer of one rank's shard), roofline of the dominant kernel, CPU oracle baseline.
 """
 from __future__ import annotations
 

@@ -1793,9 +1793,12 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     if (spd_profile::enabled(SPD_STAGE_DOWN)) {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
         if (do_fuse) {
+            // at most 16 tokens: always the weight-streaming kernel (the fused epilogue exists for it only)
             EpiDownT<true> e2;
             fill(e2);
-            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            const __bf16 *wd = (const __bf16 *)(w + D.w_d);
+            SPD_TRY(c.split ? launch_gemv<true>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
+                            : launch_gemv<false>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
         } else {
             EpiDownT<false> e2;
             fill(e2);
