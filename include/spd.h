@@ -136,6 +136,9 @@ void spd_destroy(spd_ctx *ctx);
 int spd_get_config(const spd_ctx *ctx, spd_config *out);
 int spd_get_sizes(const spd_ctx *ctx, spd_sizes *out);
 const char *spd_strerror(int code);
+/* After a call returned SPD_EHIP: which HIP call of this thread failed and with what error (a
+ * string owned by the library, valid until the thread's next failing call).  Empty if none. */
+const char *spd_last_hip_error(void);
 
 /* ---------------------------------------------------------------- rank indexing (host only)
  * Sec. 4.2.3: the heads (and FFN columns) of device `rank` are a contiguous block of

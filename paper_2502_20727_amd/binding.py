@@ -24,7 +24,11 @@ SPD_MAX_BATCH = 64
 class SpdError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {strerror(code)} ({code})")
+        detail = ""
+        if code == SPD_EHIP:
+            msg = lib().spd_last_hip_error()
+            detail = f": {msg.decode()}" if msg else ""
+        super().__init__(f"{where}: {strerror(code)} ({code}){detail}")
 
 
 class spd_config(C.Structure):
@@ -60,6 +64,7 @@ _PROTOS = {
     "spd_destroy": (None, [C.c_void_p]),
     "spd_get_config": (C.c_int, [C.c_void_p, C.POINTER(spd_config)]),
     "spd_get_sizes": (C.c_int, [C.c_void_p, C.POINTER(spd_sizes)]),
+    "spd_last_hip_error": (C.c_char_p, []),
     "spd_strerror": (C.c_char_p, [C.c_int]),
     "spd_rank_q_heads": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "spd_rank_kv_heads": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
@@ -96,6 +101,13 @@ def lib():
     global _lib
     if _lib is None:
         path = build.ensure_hip()
+        # PyTorch ships its own HIP runtime.  The library must bind to the same one as the tensors it
+        # is handed, so torch (when installed) is imported before the library is loaded: loaded the
+        # other way round, the process holds two runtimes and this library's calls see no device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = C.CDLL(path)
         for name, (res, args) in _PROTOS.items():
             fn = getattr(l, name)          # AttributeError if the symbol is not exported

@@ -3,14 +3,27 @@
 #include <cstring>
 #include <vector>
 
+#include <cstdio>
+
 #include "spd_internal.h"
 
 namespace {
 
-#define SPD_HIP(x)                          \
-    do {                                    \
-        if ((x) != hipSuccess) return SPD_EHIP; \
+// what the last failing HIP call of this thread was (spd_last_hip_error())
+thread_local char g_hip_msg[256] = "";
+
+#define SPD_HIP(x)                                                                                              \
+    do {                                                                                                        \
+        const hipError_t e_ = (x);                                                                              \
+        if (e_ != hipSuccess) {                                                                                 \
+            std::snprintf(g_hip_msg, sizeof(g_hip_msg), "%s (%s) at %s:%d", hipGetErrorName(e_), #x, __FILE__, __LINE__); \
+            return SPD_EHIP;                                                                                    \
+        }                                                                                                       \
     } while (0)
+
+// launch errors are read with hipGetLastError(), which also returns whatever an earlier, unrelated
+// call of this thread left behind: every entry point starts from a clean slate
+inline void clear_stale_hip_error() { (void)hipGetLastError(); }
 
 inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
@@ -112,6 +125,7 @@ extern "C" {
 
 int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream) {
     if (!ctx || !workspace || (((uintptr_t)workspace) & 255)) return SPD_EINVAL;
+    clear_stale_hip_error();
     const spd_dims &D = ctx->D;
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -127,6 +141,7 @@ int spd_rank_sum(const spd_ctx *ctx, const float *base, const float *slots, int3
     if (!ctx || !out || n_slots < 0 || n_elems < 0) return SPD_EINVAL;
     if (n_slots > 0 && !slots) return SPD_EINVAL;
     if (n_elems == 0) return SPD_OK;
+    clear_stale_hip_error();
     SPD_HIP(spd_common::rank_sum(base, slots, n_slots, n_elems, out, (hipStream_t)stream));
     return SPD_OK;
 }
@@ -141,6 +156,7 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
     if (spd_flag != 0 && spd_flag != 1) return SPD_EINVAL;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return SPD_EINVAL;
     if (c.M == 0) return SPD_OK;
+    clear_stale_hip_error();
     const spd_dims &D = ctx->D;
     c.taps = taps;
     const char *w = (const char *)packed_weights;
@@ -174,6 +190,7 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
     }
     if (n_rank_sums) *n_rank_sums = 0;
     if (c.M == 0) return SPD_OK;
+    clear_stale_hip_error();
     const bool bf = D.dtype == SPD_BF16;
     int64_t syncs = 0;
     const float *x = x_in;
@@ -205,6 +222,8 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
     if (n_rank_sums) *n_rank_sums = syncs;
     return SPD_OK;
 }
+
+const char *spd_last_hip_error(void) { return g_hip_msg; }
 
 }  // extern "C"
 
