@@ -144,6 +144,19 @@ def test_mask_from_sensitivity_is_the_oracle_bit_for_bit():
     B.spd_destroy(ctx)
 
 
+def test_sync_points_stated_by_the_paper():
+    # the same golden rows as the oracle's pin, through the library's mask builder and sync counter
+    path = os.path.join(os.path.dirname(__file__), "golden", "sync_points.txt")
+    rng = np.random.default_rng(32)
+    for n_blocks, n_spd, want in (map(int, l.split()[:3]) for l in open(path) if l.strip() and not l.startswith("#")):
+        w = workloads.Workload(name="g", hidden=64, n_q_heads=2, n_kv_heads=2, head_dim=32, ffn=64, n_layers=n_blocks,
+                               tp=2, dtype=workloads.BF16, seed=1, batch=1, q_len=1, ctx=32, mask=(1,) * n_blocks)
+        ctx = B.spd_create(B.make_config(w))
+        mask, _ = B.spd_mask_from_sensitivity(rng.random(n_blocks), n_spd, 0.05, 10.0)
+        assert B.spd_sync_count(ctx, mask) == want
+        B.spd_destroy(ctx)
+
+
 def test_mask_from_sensitivity_rejects():
     S = [0.1, 0.2, 0.3]
     for bad in (dict(n_spd=-1), dict(n_spd=4), dict(tau1=float("nan")), dict(tau2=float("nan")),

@@ -588,3 +588,23 @@ def test_block_with_bias():
     got = O.block_single_rank(sh, X, with_b[1], O.KVCache(1, sh.kv, 8, sh.head_dim), [0], 1, 5, 1, 1,
                               np.stack(det["P"]).copy())
     np.testing.assert_allclose(got, full, rtol=1e-11, atol=1e-12)
+
+
+def test_sync_points_stated_by_the_paper():
+    """tests/golden/sync_points.txt: block counts and SPD shares the paper states, and the number of sync
+    points they imply; the oracle's mask builder and block loop must count the same."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "sync_points.txt")
+    rows = [l.split()[:3] for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 7
+    sh = O.Shapes(hidden=8, n_q_heads=2, n_kv_heads=2, head_dim=4, ffn=8, tp=2)
+    rng = np.random.default_rng(31)
+    for n_blocks, n_spd, want in (map(int, r) for r in rows):
+        S = rng.random(n_blocks).tolist()
+        mask, _ = O.mask_from_sensitivity(S, n_spd, 0.05, 10.0)
+        assert sum(1 if m else 2 for m in mask) == want
+    # and the block loop itself reports what it did (a short model: 5 blocks, 3 of them SPD -> 7 sync points)
+    shards = [make_shards(rng, sh) for _ in range(5)]
+    X = rng.standard_normal((2, sh.hidden))
+    _, syncs = O.model_all_ranks(sh, X, shards, [fresh_caches(sh, 1, 4) for _ in range(5)], [0], 1, 2, [1, 0, 1, 1, 0])
+    assert syncs == 7
