@@ -878,21 +878,29 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
 }
 
 // ------------------------------------------------------------------------------------------
-// GEMM for prefill-sized calls: a workgroup of 8 waves computes a 256 (output features) x 256
-// (tokens) tile; both operands are staged through LDS in steps of 64 contraction elements,
-// double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
+// GEMM for prefill-sized calls: a workgroup computes a 256 (output features) x 256 (tokens) tile
+// with 8 waves (or 256 x 128 with 4); both operands are staged through LDS in steps of 64 (or 32)
+// contraction elements, double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
 // memory, so a stage is filled with gfx950's direct global->LDS loads (one instruction per
 // fragment, no staging registers) and read back with conflict-free 16-byte LDS reads.  Each
 // wave owns 4 n-tiles x 8 m-tiles (128 accumulator registers).  One barrier per step.
 // ------------------------------------------------------------------------------------------
-constexpr int GL_WN = 4, GL_WM = 2, GL_TI = 4, GL_TJ = 8;
-constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // 16 x 16 tiles per workgroup
-constexpr int GL_STAGE = (GL_BN + GL_BM) * 2 * 1024;                 // 64 KiB per stage
-constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
+// Tile shapes.  WN x WM waves, each TI n-tiles x TJ m-tiles; KPS k-tiles per step.
+struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per compute unit (128 KiB of LDS)
+    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 8, KPS = 2, MINB = 1;
+};
+struct GemmMid {      // 4 waves, 256 x 128, steps of 32: 48 KiB of LDS, two or three workgroups per compute unit
+    static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2;
+};
 
-template <class Epi>
-__global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
-                                                                 int KT, int n_ntiles, int n_mtiles, int TN, Epi epi) {
+template <class Epi, class G>
+__global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
+                                                                   int KT, int n_ntiles, int n_mtiles, int TN, Epi epi) {
+    constexpr int GL_WN = G::WN, GL_WM = G::WM, GL_TI = G::TI, GL_TJ = G::TJ, KPS = G::KPS;
+    constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // tiles per workgroup
+    constexpr int GL_STAGE = (GL_BN + GL_BM) * KPS * 1024;
+    constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
+    static_assert((GL_BN + GL_BM) % (GL_WN * GL_WM) == 0 && GL_TI % 2 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wn = wave % GL_WN, wm = wave / GL_WN;
@@ -903,8 +911,8 @@ __global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *_
     for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
         for (int j = 0; j < GL_TJ; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    // this wave's share of the copies: GL_FPW tile rows; the two k-tiles of a row are 2 KiB
-    // contiguous both in global memory and in LDS.  Rows past the matrix repeat its last tile.
+    // this wave's share of the copies: GL_FPW tile rows; the KPS k-tiles of a row are contiguous
+    // both in global memory and in LDS.  Rows past the matrix repeat its last tile.
     const __bf16 *src[GL_FPW];
 #pragma unroll
     for (int i = 0; i < GL_FPW; ++i) {
@@ -922,15 +930,16 @@ __global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *_
     auto issue = [&](int stage, int ks) {
 #pragma unroll
         for (int i = 0; i < GL_FPW; ++i) {
-            const __bf16 *g = src[i] + (size_t)ks * 1024;
-            char *l = lds + stage * GL_STAGE + (wave * GL_FPW + i) * 2048;
+            const __bf16 *g = src[i] + (size_t)ks * (KPS * 512);
+            char *l = lds + stage * GL_STAGE + (wave * GL_FPW + i) * (KPS * 1024);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                              (__attribute__((address_space(3))) void *)l, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                             (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
+            if (KPS == 2)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                                 (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
         }
     };
-    const int nks = KT >> 1;
+    const int nks = KT / KPS;
     issue(0, 0);
     for (int ks = 0; ks < nks; ++ks) {
         const int cur = ks & 1;
@@ -938,26 +947,26 @@ __global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *_
         __syncthreads();                                     // everybody's have, and nobody still reads the other stage
         if (ks + 1 < nks) issue(cur ^ 1, ks + 1);
         const char *st = lds + cur * GL_STAGE;
-        // all 24 fragments of the step are requested first, then the 64 MFMAs run in program order
+        // all fragments of the step are requested first, then the MFMAs run in program order
         // (the scheduling barriers keep the compiler from re-interleaving reads and MFMAs, which
         // would make it wait for the whole LDS queue before every group of MFMAs)
-        bf16x8 a[2][GL_TI], b[2][GL_TJ];
+        bf16x8 a[KPS][GL_TI], b[KPS][GL_TJ];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int kt = 0; kt < KPS; ++kt) {
 #pragma unroll
             for (int j = 0; j < GL_TJ; ++j)
-                b[kt][j] = *(const bf16x8 *)(st + GL_BN * 2048 + ((wm * GL_TJ + j) * 2 + kt) * 1024 + lane * 16);
+                b[kt][j] = *(const bf16x8 *)(st + GL_BN * KPS * 1024 + ((wm * GL_TJ + j) * KPS + kt) * 1024 + lane * 16);
 #pragma unroll
-            for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * 2 + kt) * 1024 + lane * 16);
+            for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * KPS + kt) * 1024 + lane * 16);
         }
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < KPS; ++kt)
 #pragma unroll
             for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
                 for (int j = 0; j < GL_TJ; ++j) {
                     acc[i][j] = MFMA(a[kt][i], b[kt][j], acc[i][j]);
-                    __builtin_amdgcn_sched_barrier(0);
+                    if (KPS == 2) __builtin_amdgcn_sched_barrier(0);
                 }
     }
     // norm factors of all the wave's m-tiles first, so that their loads are in flight together
@@ -1000,19 +1009,28 @@ __global__ void __launch_bounds__(GL_WN * GL_WM * 64) k_gemm_lds(const __bf16 *_
     }
 }
 
-template <class Epi>
-hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
+template <class G, class Epi>
+hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
+    constexpr int BN = G::WN * G::TI, BM = G::WM * G::TJ, STAGE = (BN + BM) * G::KPS * 1024;
     static bool attr_set = false;       // the attribute is per kernel instantiation; setting it twice is harmless
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_lds<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * GL_STAGE);
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
-    const int TN = (n_ntiles + GL_BN - 1) / GL_BN, TM = (n_mtiles + GL_BM - 1) / GL_BM;
-    hipLaunchKernelGGL((k_gemm_lds<Epi>), dim3(TN * TM), dim3(GL_WN * GL_WM * 64), 2 * GL_STAGE, c.s, Wp, Xp, KT, n_ntiles,
+    const int TN = (n_ntiles + BN - 1) / BN, TM = (n_mtiles + BM - 1) / BM;
+    hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(TN * TM), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
                        n_mtiles, TN, epi);
     return hipGetLastError();
+}
+
+template <class Epi>
+hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
+    // both shapes measure the same on the 70B shard (the big one is ahead by 1-3 % on QKV and down);
+    // the mid one also takes an odd number of k-tiles
+    if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid>(c, Wp, Xp, n_pairs, KT, epi);
+    return launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1555,7 +1573,7 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
     if (n_mtiles == 1)
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
     if (n_mtiles <= SKINNY_MAX_MTILES) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
-    if (!split && (KT % 2) == 0 && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
+    if (!split && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
     constexpr int MT = 4, W = 4;
     const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
     if (split)
