@@ -200,6 +200,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="70b-decode")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers than the workload names")
+    ap.add_argument("--batch", type=int, default=None, help="exploration: another number of sequences than the workload names")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-synced", action="store_true", help="skip the all-sync-points-kept run")
@@ -231,6 +232,9 @@ def main():
     w = workloads.get(args.workload)
     if args.layers:
         w = w.with_layers(args.layers)
+    if args.batch:
+        from dataclasses import replace
+        w = replace(w, batch=args.batch, name=f"{w.name}+batch{args.batch}")
     prefill = w.q_len > 1
     steps = args.steps if args.steps is not None else (5 if prefill else 50)
     warmup = args.warmup if args.warmup is not None else (2 if prefill else 10)

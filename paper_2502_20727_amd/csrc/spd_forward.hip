@@ -45,7 +45,7 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->taps = nullptr;
     c->max_pos_end = 0;
     c->split_all = D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_ALWAYS;
-    c->split = c->split_all || (D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= 16);
+    c->split = c->split_all || (D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= SPD_AUTO_SPLIT_TOKENS);
     c->nch1 = 0;
     std::memset(&c->pos, 0, sizeof(c->pos));
     for (int b = 0; b < batch; ++b) {

@@ -30,6 +30,7 @@
 constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
 constexpr int SPD_N_COUNTERS = 8192;
+constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of at most this many tokens carry the MLP inputs as hi + lo pairs
 constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
 

@@ -1152,7 +1152,7 @@ __device__ __forceinline__ void load_q(bf16x8 *qf, const __bf16 *__restrict__ qb
 // cache's bf16, appends them to the cache and attends to them as one more (single-key) block.
 template <int DT, bool FUSED>
 __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ qbuf_in, const __bf16 *__restrict__ qlo_in,
-                                                     const float *__restrict__ qkvp, int KS, int nqkv, __bf16 *__restrict__ qbuf_out,
+                                                     const float *__restrict__ qkvp, int KS, int part_rows, int nqkv, __bf16 *__restrict__ qbuf_out,
                                                      __bf16 *__restrict__ qlo_out, __bf16 *__restrict__ kc, __bf16 *__restrict__ vc,
                                                      float *__restrict__ part, spd_positions P, int q, int kv, int max_ctx,
                                                      int n_splits) {
@@ -1193,14 +1193,14 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
             const int e = min((int)threadIdx.x + 256 * sl, nq4 - 1);
             const float *src = qkvp + (size_t)b * nqkv + kvh * group * d + 4 * e;
 #pragma unroll
-            for (int j = 0; j < MAXKS; ++j) qs[sl][j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * 16 * nqkv);
+            for (int j = 0; j < MAXKS; ++j) qs[sl][j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * part_rows * nqkv);
         }
         if (newtok) {                                                     // uniform
             const int e = min((int)threadIdx.x, 2 * nk4 - 1);
             const int colq = e < nk4 ? qd + kvh * d + 4 * e : qd + kv * d + kvh * d + 4 * (e - nk4);
             const float *src = qkvp + (size_t)b * nqkv + colq;
 #pragma unroll
-            for (int j = 0; j < MAXKS; ++j) ns[j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * 16 * nqkv);
+            for (int j = 0; j < MAXKS; ++j) ns[j] = *(const float4 *)(src + (size_t)min(j, KS - 1) * part_rows * nqkv);
         }
     }
     // (a wave without blocks loads a block it will not use: one code path, no waiting at a join)
@@ -1633,7 +1633,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         qkv_slices = want < 2 ? 2 : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
         if (qkv_slices > D.h / 32 / (2 * wv)) qkv_slices = D.h / 32 / (2 * wv);
         while (qkv_slices > 1 && (size_t)qkv_slices * 16 * n_mtiles * D.nqkv > (size_t)SPD_MAX_KPART * 512) --qkv_slices;
-        fused_q = qkv_slices > 1 && c.q_len == 1 && n_mtiles == 1;
+        // (a decode step of any batch size lets the attention kernel add the slices)
+        fused_q = qkv_slices > 1 && c.q_len == 1 && n_mtiles <= SKINNY_MAX_MTILES;
         gather_q = qkv_slices > 1 && !fused_q && n_mtiles > 1 && n_mtiles <= SKINNY_MAX_MTILES;
         if (!fused_q && !gather_q) qkv_slices = 1;
     }
@@ -1647,12 +1648,14 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e1.part = qkvp; e1.P = c.pos;
         if (spd_profile::enabled(SPD_STAGE_QKV)) {
             spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-            if (fused_q) {
+            if (n_mtiles == 1) {
                 SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
                                            qkv_slices, e1));
             } else {
                 SPD_TRY(launch_skinny<2>(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
                                          qkv_slices, 16, e1));
+            }
+            if (gather_q) {
                 hipLaunchKernelGGL(k_qkv_gather, dim3(cdiv((int64_t)M * (D.nqkv / 4), 256)), dim3(256), 0, c.s, qkvp, qkv_slices,
                                    16 * n_mtiles, M, c.q_len, D.q, D.kv, D.d, D.max_ctx, c.pos, qbuf, qlo, kc, vc);
                 SPD_TRY(hipGetLastError());
@@ -1697,10 +1700,10 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
 #define SPD_DECODE(DTV)                                                                                              \
     if (fused_q)                                                                                                     \
         hipLaunchKernelGGL((k_attn_decode<DTV, true>), grid, dim3(256), 0, c.s, (const __bf16 *)nullptr,             \
-                           (const __bf16 *)nullptr, qkvp, qkv_slices, D.nqkv, qbuf, qlo, kc, vc, part, c.pos, D.q, D.kv, \
+                           (const __bf16 *)nullptr, qkvp, qkv_slices, 16 * n_mtiles, D.nqkv, qbuf, qlo, kc, vc, part, c.pos, D.q, D.kv, \
                            D.max_ctx, splits);                                                                       \
     else                                                                                                             \
-        hipLaunchKernelGGL((k_attn_decode<DTV, false>), grid, dim3(256), 0, c.s, qbuf, qlo, (const float *)nullptr, 1,   \
+        hipLaunchKernelGGL((k_attn_decode<DTV, false>), grid, dim3(256), 0, c.s, qbuf, qlo, (const float *)nullptr, 1, 16,   \
                            D.nqkv, (__bf16 *)nullptr, (__bf16 *)nullptr, kc, vc, part, c.pos, D.q, D.kv, D.max_ctx, splits)
         switch (DT) {
             case 2: SPD_DECODE(2); break;
@@ -1792,7 +1795,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
         }
     }
 
-    const bool do_fuse = fuse && M <= 16;
+    const bool do_fuse = fuse && M <= 16 * SKINNY_MAX_MTILES;
     if (fused) *fused = do_fuse;
     auto fill = [&](auto &e2) {
         e2.M = M; e2.h = D.h; e2.spd = spd;
@@ -1811,12 +1814,15 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     if (spd_profile::enabled(SPD_STAGE_DOWN)) {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
         if (do_fuse) {
-            // at most 16 tokens: always the weight-streaming kernel (the fused epilogue exists for it only)
+            // the weight-streaming kernels only: the fused epilogue is for calls of up to 512 tokens
             EpiDownT<true> e2;
             fill(e2);
             const __bf16 *wd = (const __bf16 *)(w + D.w_d);
-            SPD_TRY(c.split ? launch_gemv<true>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
-                            : launch_gemv<false>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            if (M <= 16)
+                SPD_TRY(c.split ? launch_gemv<true>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
+                                : launch_gemv<false>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            else
+                SPD_TRY(launch_skinny<0>(c, c.split, wd, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
         } else {
             EpiDownT<false> e2;
             fill(e2);
