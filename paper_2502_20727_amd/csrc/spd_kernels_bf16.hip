@@ -1377,20 +1377,26 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
     if (alo) alo[o] = (__bf16)(val - (float)hi);
 }
 
-// Prefill (q_len > 1): grid (column-tile groups, kv heads, sequences), 4 waves, each wave owns
-// CT column tiles of 16 (token, head) columns and walks the causal key range once.
+// Prefill (q_len > 1): grid (groups of CT column tiles, kv heads, sequences), 4 waves.  All four
+// waves work on the same CT tiles of 16 (token, head) columns and deal the causal key range
+// among themselves block by block (the latest tokens attend thousands of keys: one wave walking
+// them alone would be the critical path of the launch); their partial states meet in LDS and
+// every wave finishes a quarter of the (tile, 16-feature slice) outputs.
 template <int DT, int CT>
 __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
                                                       const __bf16 *__restrict__ vc, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, spd_positions P, int q_len, int q, int kv,
                                                       int max_ctx) {
     constexpr int d = DT * 16;
+    extern __shared__ __attribute__((aligned(16))) char ap_lds[];
+    f32x4 *so = (f32x4 *)ap_lds;                                   // [4 waves][CT][DT][64 lanes]
+    float *sml = (float *)(ap_lds + 4 * CT * DT * 64 * 16);        // [4 waves][CT][2][16]: running max, running sum
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int group = q / kv, qd = q * d;
     const int n_cols = q_len * group;
-    const int ct0 = (blockIdx.x * 4 + wave) * CT;
-    if (ct0 * 16 >= n_cols) return;
+    // causal: the later a token, the more keys it attends; the long workgroups are launched first
+    const int ct0 = (gridDim.x - 1 - blockIdx.x) * CT;
     const int g = lane >> 4;
     const int pos0 = P.pos[b];
     bf16x8 qf[CT][DT];
@@ -1412,34 +1418,54 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
         st[c].l = 0.f;
         last_key = max(last_key, nk[c]);
     }
-    // the block range must be wave-uniform: take the maximum over the wave's columns
+    // the block range must be uniform: take the maximum over the columns
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) last_key = max(last_key, __shfl_xor(last_key, o, 64));
     const __bf16 *kbase = kc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
     const __bf16 *vbase = vc + ((size_t)b * kv + kvh) * (size_t)max_ctx * d;
     const float scale = 1.0f / sqrtf((float)d);
     const int nblk = (last_key + 31) >> 5;
-    for (int vb = 0; vb < nblk; ++vb) {
+    for (int vb = wave; vb < nblk; vb += 4) {
         KVFrags<DT> f;
         load_kv<DT>(f, kbase, vbase, vb, d, lane);
 #pragma unroll
         for (int c = 0; c < CT; ++c) attn_block<DT>(st[c], qf[c], f, vb, nk[c], scale, lane);
     }
+    // partial states to LDS
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
-        if (nk[c] == 0) continue;
-        const float inv = 1.0f / st[c].l;
-        const int mt = mrow[c] >> 4, r = mrow[c] & 15;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const int kidx = hd[c] * d + dt * 16 + 4 * g;
-            const float o0 = st[c].o[dt][0] * inv, o1 = st[c].o[dt][1] * inv, o2 = st[c].o[dt][2] * inv,
-                        o3 = st[c].o[dt][3] * inv;
-            const bf16x4 v = cvt4(o0, o1, o2, o3);
-            const size_t o = spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31);
-            *(bf16x4 *)(ahat + o) = v;
-            if (alo) *(bf16x4 *)(alo + o) = cvt4_lo(o0, o1, o2, o3, v);
+        for (int dt = 0; dt < DT; ++dt) so[((wave * CT + c) * DT + dt) * 64 + lane] = st[c].o[dt];
+        if (g == 0) {
+            sml[((wave * CT + c) * 2 + 0) * 16 + (lane & 15)] = st[c].m;
+            sml[((wave * CT + c) * 2 + 1) * 16 + (lane & 15)] = st[c].l;
         }
+    }
+    __syncthreads();
+    // wave w finishes the (tile, slice) pairs w, w + 4, ...: the four partial states are merged in wave order
+    for (int pr = wave; pr < CT * DT; pr += 4) {
+        const int c = pr / DT, dt = pr % DT;
+        if (nk[c] == 0) continue;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, sml[((w * CT + c) * 2 + 0) * 16 + (lane & 15)]);
+        float den = 0.f;
+        f32x4 num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float mw = sml[((w * CT + c) * 2 + 0) * 16 + (lane & 15)];
+            const float sc = (mw == -INFINITY) ? 0.f : __expf(mw - mm);
+            den += sml[((w * CT + c) * 2 + 1) * 16 + (lane & 15)] * sc;
+            num += so[((w * CT + c) * DT + dt) * 64 + lane] * sc;
+        }
+        const float inv = 1.0f / den;
+        const int mt = mrow[c] >> 4, r = mrow[c] & 15;
+        const int kidx = hd[c] * d + dt * 16 + 4 * g;
+        const float o0 = num[0] * inv, o1 = num[1] * inv, o2 = num[2] * inv, o3 = num[3] * inv;
+        const bf16x4 v = cvt4(o0, o1, o2, o3);
+        const size_t o = spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31);
+        *(bf16x4 *)(ahat + o) = v;
+        if (alo) *(bf16x4 *)(alo + o) = cvt4_lo(o0, o1, o2, o3, v);
     }
 }
 
@@ -1720,10 +1746,18 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     } else {
         constexpr int CT = 2;
         const int n_ct = (c.q_len * D.group + 15) / 16;
-        const dim3 grid(cdiv(n_ct, 4 * CT), D.kv, c.batch);
-#define SPD_PREFILL(DTV)                                                                                              \
-    hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), 0, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, D.q, \
-                       D.kv, D.max_ctx)
+        const dim3 grid(cdiv(n_ct, CT), D.kv, c.batch);
+#define SPD_PREFILL(DTV)                                                                                                   \
+    {                                                                                                                      \
+        constexpr int lds = 4 * CT * DTV * 64 * 16 + 4 * CT * 2 * 16 * 4;                                                  \
+        static bool attr_set = false;                                                                                      \
+        if (!attr_set) {                                                                                                   \
+            SPD_TRY(hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
+            attr_set = true;                                                                                               \
+        }                                                                                                                  \
+        hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
+                           D.q, D.kv, D.max_ctx);                                                                          \
+    }
         switch (DT) {
             case 2: SPD_PREFILL(2); break;
             case 4: SPD_PREFILL(4); break;
