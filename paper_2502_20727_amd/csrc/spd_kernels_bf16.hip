@@ -417,28 +417,40 @@ struct EpiDownT {
 
     // out = base + (slot_0 + slot_1 + ...), own partial standing in for slot `rank`: the same
     // order of additions as the stand-alone rank-sum
-    __device__ __forceinline__ float4 sync_sum(size_t o, float4 own) const {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // both halves of a tile at once, eight slots at a time: all 16 loads of a round (and the two base
+    // loads) are issued together (indices clamped, named registers: nothing here may end up in
+    // scratch memory); additions in ascending slot order, the base last, then the bias
+    __device__ __forceinline__ void sync_sum2(size_t oa, size_t ob, float4 own_a, float4 own_b, float4 &ra, float4 &rb) const {
+        float4 acc_a = make_float4(0.f, 0.f, 0.f, 0.f), acc_b = acc_a;
+        const int last = tp - 1;
+        const float4 bs_a = *(const float4 *)(base + oa), bs_b = *(const float4 *)(base + ob);
         for (int s0 = 0; s0 < tp; s0 += 8) {
-            float4 t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (s0 + j < tp && s0 + j != rank) t[j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + o);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (s0 + j >= tp) continue;
-                const float4 v = (s0 + j == rank) ? own : t[j];
-                if (s0 + j == 0) acc = v;
-                else { acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; }
-            }
+#define SPD_LD(j)                                                                                         \
+    const float4 ta##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + oa);         \
+    const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + ob);
+            SPD_LD(0) SPD_LD(1) SPD_LD(2) SPD_LD(3) SPD_LD(4) SPD_LD(5) SPD_LD(6) SPD_LD(7)
+#undef SPD_LD
+            auto add = [&](int s, const float4 &ta, const float4 &tb) {
+                if (s >= tp) return;
+                const float4 va = (s == rank) ? own_a : ta, vb = (s == rank) ? own_b : tb;
+                if (s == 0) {
+                    acc_a = va;
+                    acc_b = vb;
+                } else {
+                    acc_a.x += va.x; acc_a.y += va.y; acc_a.z += va.z; acc_a.w += va.w;
+                    acc_b.x += vb.x; acc_b.y += vb.y; acc_b.z += vb.z; acc_b.w += vb.w;
+                }
+            };
+            add(s0, ta0, tb0); add(s0 + 1, ta1, tb1); add(s0 + 2, ta2, tb2); add(s0 + 3, ta3, tb3);
+            add(s0 + 4, ta4, tb4); add(s0 + 5, ta5, tb5); add(s0 + 6, ta6, tb6); add(s0 + 7, ta7, tb7);
         }
-        const float4 bs = *(const float4 *)(base + o);
-        float4 r = make_float4(bs.x + acc.x, bs.y + acc.y, bs.z + acc.z, bs.w + acc.w);
+        ra = make_float4(bs_a.x + acc_a.x, bs_a.y + acc_a.y, bs_a.z + acc_a.z, bs_a.w + acc_a.w);
+        rb = make_float4(bs_b.x + acc_b.x, bs_b.y + acc_b.y, bs_b.z + acc_b.z, bs_b.w + acc_b.w);
         if (bias) {
-            const float4 bb = *(const float4 *)(bias + (o % (size_t)h));
-            r.x += bb.x; r.y += bb.y; r.z += bb.z; r.w += bb.w;
+            const float4 ba = *(const float4 *)(bias + (oa % (size_t)h)), bb = *(const float4 *)(bias + (ob % (size_t)h));
+            ra.x += ba.x; ra.y += ba.y; ra.z += ba.z; ra.w += ba.w;
+            rb.x += bb.x; rb.y += bb.y; rb.z += bb.z; rb.w += bb.w;
         }
-        return r;
     }
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float, const Pre &p) const {
@@ -455,8 +467,7 @@ struct EpiDownT {
         if (!FUSED) return;
         float4 xa = make_float4(0.f, 0.f, 0.f, 0.f), xb = xa;
         if (valid) {
-            xa = sync_sum(oa, pa);
-            xb = sync_sum(ob, pb);
+            sync_sum2(oa, ob, pa, pb, xa, xb);
             *(float4 *)(x_out + oa) = xa;
             *(float4 *)(x_out + ob) = xb;
         }
@@ -1829,6 +1840,10 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
         }
     }
 
+    // the closing sync point rides in the down projection's epilogue in the weight-streaming kernels (up
+    // to 512 tokens).  In the LDS-tiled GEMM it gains nothing: measured on the 70B prefill shape, the
+    // workgroups of a compute unit reach their epilogues together, so the slot reads do not overlap with
+    // anybody's contraction and the fused kernel takes exactly as long as GEMM + rank-sum kernel.
     const bool do_fuse = fuse && M <= 16 * SKINNY_MAX_MTILES;
     if (fused) *fused = do_fuse;
     auto fill = [&](auto &e2) {
@@ -1848,7 +1863,6 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     if (spd_profile::enabled(SPD_STAGE_DOWN)) {
         spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
         if (do_fuse) {
-            // the weight-streaming kernels only: the fused epilogue is for calls of up to 512 tokens
             EpiDownT<true> e2;
             fill(e2);
             const __bf16 *wd = (const __bf16 *)(w + D.w_d);
