@@ -88,16 +88,22 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
             es.base = x;
             for (int r = r0; r < r1; ++r) {
                 SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 1, slots + r * slot_n));
-                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 1, slots + r * slot_n, fuse, end_done));
+                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 1, slots + r * slot_n, fuse, end_done, true));
             }
             *base_out = x;
         } else {
-            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 0, slots + r * slot_n));
-            // kept sync point: R = X + sum_r Y_r, fused with the second norm's elementwise part
-            SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1, bo));
+            // kept sync point: R = X + sum_r Y_r (+ bias), with the second norm's elementwise part; for one
+            // rank and a call of at most 512 tokens the O projection's epilogue does it, otherwise prep()
+            spd_bf16::spd_mid_sync ms;
+            ms.slots = slots; ms.tp = D.tp; ms.rank = r0; ms.rbuf = rbuf;
+            bool mid_done = false;
+            for (int r = r0; r < r1; ++r)
+                SPD_HIP(spd_bf16::attention_half(c, wr(r), kr(r), x, 0, slots + r * slot_n, all ? nullptr : &ms, &mid_done));
+            if (!mid_done) SPD_HIP(spd_bf16::prep(c, x, slots, D.tp, rbuf, (const float *)(wr(r0) + D.w_g2), true, 1, bo));
             *syncs += 1;
             es.base = rbuf;
-            for (int r = r0; r < r1; ++r) SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n, fuse, end_done));
+            for (int r = r0; r < r1; ++r)
+                SPD_HIP(spd_bf16::mlp_half(c, wr(r), 0, slots + r * slot_n, fuse, end_done, mid_done));
             *base_out = rbuf;
         }
         return SPD_OK;

@@ -155,7 +155,16 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
 // QKV + rotary + cache append + attention + O projection.
 //   spd = 1: ybuf <- Y_r, xhat2 <- bf16((X + Y_r) g2) and its partial sums of squares
 //   spd = 0: slot <- Y_r
-hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot);
+// With `mid` (TP block, one rank, calls of at most 512 tokens) the O projection's epilogue also performs
+// the kept attention sync point: R = X + sum of the slots (+ bias) -> mid->rbuf, second norm prepared;
+// *mid_done tells whether it did (otherwise the caller runs prep()).
+struct spd_mid_sync {
+    const float *slots;       // [tp][M*h]
+    int tp, rank;
+    float *rbuf;
+};
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
+                          const spd_mid_sync *mid = nullptr, bool *mid_done = nullptr);
 // The sync point that ends a block, for one rank whose peers' partial sums are already in
 // `slots`: x_out = base + (slot_0 + ... + slot_tp-1), optionally followed by the elementwise
 // part of the next block's first norm (gain next_g1, may be NULL).
@@ -170,6 +179,9 @@ struct spd_end_sync {
 // gate/up + SwiGLU + down.  spd = 1: slot <- ybuf + Z_r; spd = 0: slot <- Z_r.  With `fuse`
 // (calls of at most 16 tokens) the down projection's epilogue also performs the end-of-block
 // sync point; returns through *fused whether it did.
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused);
+// ss_per_pair: the sums of squares of the MLP input were left per pair of n-tiles (by the O projection's
+// epilogue) rather than per prep() chunk
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
+                    bool ss_per_pair);
 int prep_chunks(const spd_call &c);
 }

@@ -146,6 +146,47 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
     if (ss && g == 0 && chunk * tpw < KT) ss[(size_t)chunk * m_pad + m] = ssum;
 }
 
+// The sum over the ranks at a sync point, for one rank whose own partial is still in registers:
+// out = base + (slot_0 + ... + slot_tp-1) [+ bias], the own partial standing in for slot `rank`.
+// both halves of a tile at once, eight slots at a time: all 16 loads of a round (and the two base
+// loads) are issued together (indices clamped, named registers: nothing here may end up in
+// scratch memory); additions in ascending slot order, the base last, then the bias
+__device__ __forceinline__ void rank_sum_pair(const float *__restrict__ slots, size_t slot_stride, int tp, int rank,
+                                          const float *__restrict__ base, const float *__restrict__ bias, int h, size_t oa,
+                                          size_t ob, float4 own_a, float4 own_b, float4 &ra, float4 &rb) {
+    float4 acc_a = make_float4(0.f, 0.f, 0.f, 0.f), acc_b = acc_a;
+    const int last = tp - 1;
+    const float4 bs_a = *(const float4 *)(base + oa), bs_b = *(const float4 *)(base + ob);
+    for (int s0 = 0; s0 < tp; s0 += 8) {
+#define SPD_LD(j)                                                                                         \
+const float4 ta##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + oa);         \
+const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + ob);
+        SPD_LD(0) SPD_LD(1) SPD_LD(2) SPD_LD(3) SPD_LD(4) SPD_LD(5) SPD_LD(6) SPD_LD(7)
+#undef SPD_LD
+        auto add = [&](int s, const float4 &ta, const float4 &tb) {
+            if (s >= tp) return;
+            const float4 va = (s == rank) ? own_a : ta, vb = (s == rank) ? own_b : tb;
+            if (s == 0) {
+                acc_a = va;
+                acc_b = vb;
+            } else {
+                acc_a.x += va.x; acc_a.y += va.y; acc_a.z += va.z; acc_a.w += va.w;
+                acc_b.x += vb.x; acc_b.y += vb.y; acc_b.z += vb.z; acc_b.w += vb.w;
+            }
+        };
+        add(s0, ta0, tb0); add(s0 + 1, ta1, tb1); add(s0 + 2, ta2, tb2); add(s0 + 3, ta3, tb3);
+        add(s0 + 4, ta4, tb4); add(s0 + 5, ta5, tb5); add(s0 + 6, ta6, tb6); add(s0 + 7, ta7, tb7);
+    }
+    ra = make_float4(bs_a.x + acc_a.x, bs_a.y + acc_a.y, bs_a.z + acc_a.z, bs_a.w + acc_a.w);
+    rb = make_float4(bs_b.x + acc_b.x, bs_b.y + acc_b.y, bs_b.z + acc_b.z, bs_b.w + acc_b.w);
+    if (bias) {
+        const float4 ba = *(const float4 *)(bias + (oa % (size_t)h)), bb = *(const float4 *)(bias + (ob % (size_t)h));
+        ra.x += ba.x; ra.y += ba.y; ra.z += ba.z; ra.w += ba.w;
+        rb.x += bb.x; rb.y += bb.y; rb.z += bb.z; rb.w += bb.w;
+    }
+}
+
+
 // ------------------------------------------------------------------------------------------
 // Epilogues.  Each receives the accumulators of one (pair of n-tiles, m-tile): a = tile
 // 2*pair, b = tile 2*pair+1; lane l: token m = mt*16 + l%16, features 4*(l/16) + i.
@@ -270,13 +311,20 @@ struct EpiQKVPart {
     }
 };
 
-struct EpiO {
+template <bool MID>      // MID: the epilogue can also perform the kept attention sync point (spd = 2)
+struct EpiOT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
     const float *bo = nullptr; // bias of the output projection or NULL: part of the SPD block's MLP input (Sec. 4.1.2)
     float *ybuf, *slot, *ss2;
     __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
+    // spd = 2: TP block whose kept attention sync point is performed here (one rank, the peers' partial
+    // sums already in `slots`): R = X + sum of the slots (+ bias) goes to rbuf and on to the second norm
+    const float *slots = nullptr;
+    size_t slot_stride = 0;
+    int tp = 0, rank = 0;
+    float *rbuf = nullptr;
     struct Pre {
         float4 x0, x1, ga, gb;
     };
@@ -286,7 +334,10 @@ struct EpiO {
         p.x0 = p.x1 = p.ga = p.gb = make_float4(0.f, 0.f, 0.f, 0.f);
         const int m = mt * 16 + (lane & 15), g = lane >> 4;
         const int na = pair * 32 + 4 * g, nb = na + 16;
-        if (spd && m < M) {
+        if (MID && spd == 2 && m < M) {      // the sum loads X itself
+            p.ga = *(const float4 *)(g2 + na);
+            p.gb = *(const float4 *)(g2 + nb);
+        } else if (spd && m < M) {
             const size_t o = (size_t)m * h;
             p.x0 = *(const float4 *)(x + o + na);
             p.x1 = *(const float4 *)(x + o + nb);
@@ -314,7 +365,20 @@ struct EpiO {
         }
         float ra[4] = {0.f, 0.f, 0.f, 0.f}, rb[4] = {0.f, 0.f, 0.f, 0.f};
         float pa[4] = {0.f, 0.f, 0.f, 0.f}, pb[4] = {0.f, 0.f, 0.f, 0.f};
-        if (valid) {
+        if (MID && valid && spd == 2) {
+            const size_t o = (size_t)m * h;
+            const float4 own_a = make_float4(a[0], a[1], a[2], a[3]), own_b = make_float4(b[0], b[1], b[2], b[3]);
+            *(float4 *)(slot + o + na) = own_a;
+            *(float4 *)(slot + o + nb) = own_b;
+            float4 qa, qb;
+            rank_sum_pair(slots, slot_stride, tp, rank, x, bo, h, o + na, o + nb, own_a, own_b, qa, qb);
+            *(float4 *)(rbuf + o + na) = qa;
+            *(float4 *)(rbuf + o + nb) = qb;
+            ra[0] = qa.x; ra[1] = qa.y; ra[2] = qa.z; ra[3] = qa.w;
+            rb[0] = qb.x; rb[1] = qb.y; rb[2] = qb.z; rb[3] = qb.w;
+            pa[0] = ra[0] * p.ga.x; pa[1] = ra[1] * p.ga.y; pa[2] = ra[2] * p.ga.z; pa[3] = ra[3] * p.ga.w;
+            pb[0] = rb[0] * p.gb.x; pb[1] = rb[1] * p.gb.y; pb[2] = rb[2] * p.gb.z; pb[3] = rb[3] * p.gb.w;
+        } else if (valid) {
             const size_t o = (size_t)m * h;
             *(float4 *)(ybuf + o + na) = make_float4(a[0], a[1], a[2], a[3]);
             *(float4 *)(ybuf + o + nb) = make_float4(b[0], b[1], b[2], b[3]);
@@ -417,40 +481,8 @@ struct EpiDownT {
 
     // out = base + (slot_0 + slot_1 + ...), own partial standing in for slot `rank`: the same
     // order of additions as the stand-alone rank-sum
-    // both halves of a tile at once, eight slots at a time: all 16 loads of a round (and the two base
-    // loads) are issued together (indices clamped, named registers: nothing here may end up in
-    // scratch memory); additions in ascending slot order, the base last, then the bias
     __device__ __forceinline__ void sync_sum2(size_t oa, size_t ob, float4 own_a, float4 own_b, float4 &ra, float4 &rb) const {
-        float4 acc_a = make_float4(0.f, 0.f, 0.f, 0.f), acc_b = acc_a;
-        const int last = tp - 1;
-        const float4 bs_a = *(const float4 *)(base + oa), bs_b = *(const float4 *)(base + ob);
-        for (int s0 = 0; s0 < tp; s0 += 8) {
-#define SPD_LD(j)                                                                                         \
-    const float4 ta##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + oa);         \
-    const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_stride + ob);
-            SPD_LD(0) SPD_LD(1) SPD_LD(2) SPD_LD(3) SPD_LD(4) SPD_LD(5) SPD_LD(6) SPD_LD(7)
-#undef SPD_LD
-            auto add = [&](int s, const float4 &ta, const float4 &tb) {
-                if (s >= tp) return;
-                const float4 va = (s == rank) ? own_a : ta, vb = (s == rank) ? own_b : tb;
-                if (s == 0) {
-                    acc_a = va;
-                    acc_b = vb;
-                } else {
-                    acc_a.x += va.x; acc_a.y += va.y; acc_a.z += va.z; acc_a.w += va.w;
-                    acc_b.x += vb.x; acc_b.y += vb.y; acc_b.z += vb.z; acc_b.w += vb.w;
-                }
-            };
-            add(s0, ta0, tb0); add(s0 + 1, ta1, tb1); add(s0 + 2, ta2, tb2); add(s0 + 3, ta3, tb3);
-            add(s0 + 4, ta4, tb4); add(s0 + 5, ta5, tb5); add(s0 + 6, ta6, tb6); add(s0 + 7, ta7, tb7);
-        }
-        ra = make_float4(bs_a.x + acc_a.x, bs_a.y + acc_a.y, bs_a.z + acc_a.z, bs_a.w + acc_a.w);
-        rb = make_float4(bs_b.x + acc_b.x, bs_b.y + acc_b.y, bs_b.z + acc_b.z, bs_b.w + acc_b.w);
-        if (bias) {
-            const float4 ba = *(const float4 *)(bias + (oa % (size_t)h)), bb = *(const float4 *)(bias + (ob % (size_t)h));
-            ra.x += ba.x; ra.y += ba.y; ra.z += ba.z; ra.w += ba.w;
-            rb.x += bb.x; rb.y += bb.y; rb.z += bb.z; rb.w += bb.w;
-        }
+        rank_sum_pair(slots, slot_stride, tp, rank, base, bias, h, oa, ob, own_a, own_b, ra, rb);
     }
 
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float, const Pre &p) const {
@@ -1646,7 +1678,8 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
 
 int prep_chunks(const spd_call &c) { return prep_nch(c.D->h, c.M); }
 
-hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot) {
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
+                          const spd_mid_sync *mid, bool *mid_done) {
     const spd_dims &D = *c.D;
     const int M = c.M, qd = D.q * D.d;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat);
@@ -1781,16 +1814,35 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     }
     spd_profile::end(SPD_STAGE_ATTN, c.s);
 
-    EpiO e2;
-    e2.M = M; e2.h = D.h; e2.spd = spd; e2.m_pad = D.m_pad;
-    e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
-    e2.bo = D.o_bias ? (const float *)(w + D.w_bo) : nullptr;
-    e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
-    e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
-    e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
+    const bool fuse_mid = mid && !spd && M <= 16 * SKINNY_MAX_MTILES;
+    if (mid_done) *mid_done = fuse_mid;
+    auto fill_o = [&](auto &e2) {
+        e2.M = M; e2.h = D.h; e2.spd = spd; e2.m_pad = D.m_pad;
+        e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
+        e2.bo = D.o_bias ? (const float *)(w + D.w_bo) : nullptr;
+        e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
+        e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
+        e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
+    };
     if (spd_profile::enabled(SPD_STAGE_O)) {
         spd_profile::scope prof(SPD_STAGE_O, c.s);
-        SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_o), ahat, D.pl_a, D.h / 32, qd / 32, e2));
+        const __bf16 *wo = (const __bf16 *)(w + D.w_o);
+        if (fuse_mid) {
+            // the weight-streaming kernels only
+            EpiOT<true> e2;
+            fill_o(e2);
+            e2.spd = 2;
+            e2.slots = mid->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = mid->tp; e2.rank = mid->rank; e2.rbuf = mid->rbuf;
+            if (M <= 16)
+                SPD_TRY(c.split_all ? launch_gemv<true>(c, wo, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2)
+                                    : launch_gemv<false>(c, wo, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2));
+            else
+                SPD_TRY(launch_skinny<0>(c, c.split_all, wo, ahat, D.pl_a, D.h / 32, qd / 32, 1, 16, e2));
+        } else {
+            EpiOT<false> e2;
+            fill_o(e2);
+            SPD_TRY(launch_proj(c, c.split_all, wo, ahat, D.pl_a, D.h / 32, qd / 32, e2));
+        }
     }
 
     if (c.taps) {
@@ -1809,7 +1861,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     return hipSuccess;
 }
 
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused) {
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
+                    bool ss_per_pair) {
     const spd_dims &D = *c.D;
     const int M = c.M;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat2);
@@ -1820,7 +1873,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.m_pad = D.m_pad; e1.eps = D.eps;
     // SPD block: the O-projection epilogue wrote one partial per pair of n-tiles (h/32 of them);
     // TP block: prep() wrote them after the kept sync point
-    e1.nch = spd ? D.h / 32 : prep_nch(D.h, M);
+    e1.nch = ss_per_pair ? D.h / 32 : prep_nch(D.h, M);
     e1.ss = (const float *)(c.ws + D.ws_ss2);
     e1.uhat = uhat; e1.ulo = ulo;
     if (spd_profile::enabled(SPD_STAGE_GATEUP)) {
