@@ -282,7 +282,15 @@ def main():
         roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=8000.0, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
-    roof["kernel"] = "k_gemm_lds<EpiGU>" if prefill else "k_gemv<16,2,split,0,EpiGU>"
+    M_tok = w.batch * w.q_len
+    if M_tok > 512:
+        roof["kernel"] = "k_gemm_lds<EpiGU,GemmBig>"
+    elif M_tok > 16:
+        roof["kernel"] = "k_skinny<8,MT,*,0,EpiGU>"
+    elif w.ffn_per_rank // 16 >= 192:
+        roof["kernel"] = "k_gemv<16,2,split,0,EpiGU>"
+    else:
+        roof["kernel"] = "k_gemv<8,2,split,1,EpiGU> + k_gemv_finish<EpiGU>"
     roof["stage"] = "gate/up projection + SwiGLU"
     roof["launches_timed"] = n
     roof["mean_us"] = mean_us
