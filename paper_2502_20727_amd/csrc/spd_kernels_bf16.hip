@@ -533,7 +533,7 @@ struct EpiDownT {
 // waves split that slice, each wave streaming its weight fragments straight from HBM into
 // registers in batches of U k-tiles, the next batch in flight while the current one feeds the
 // MFMAs.  The waves' partial tiles are added through LDS in wave order.  With KS = 1 the first
-// wave then runs the epilogue; with KS > 1 (PARTIAL) the workgroup parks its tile in `kpart`
+// wave then runs the epilogue; with KS > 1 and MODE 1 the workgroup parks its tile in `kpart`
 // and k_gemv_finish adds the KS tiles in slice order: sums never depend on timing.  MODE 2 is
 // for epilogues that are linear in the accumulators: every slice runs Epi::slice() on its own
 // partial sums and the consumer of the result adds the slices.
