@@ -835,6 +835,158 @@ __global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Projection with many n-tiles for 65 .. 128 tokens ("mid").  In k_skinny every workgroup pulls all
+// activations of its slice of K through the L2 for only two n-tiles, and from about 64 tokens on
+// that traffic (K x M x 2 B per workgroup), not the weight stream, sets the time.  Here a
+// workgroup owns 8 pairs of n-tiles (wave w: pair 8 * group + w) and one of KS slices of K; all
+// waves walk the same k-tiles, so the activation fragments of a stage (MID_KB k-tiles x MT
+// m-tiles) are fetched once per workgroup, by one wave each, and shared through LDS, while each
+// wave streams its own weight fragments HBM -> registers.  Loads run three stages ahead of the
+// MFMAs in a ring of four register sets; the steady-state loop has no branch (stages past the
+// slice's end repeat its last one and are never consumed).  Workgroups start their slice at
+// different stages (a rotation), otherwise all of them hit the same memory channels together.
+// K is cut into slices because 8 pairs per workgroup leave too few workgroups: the partial tiles go
+// to `kpart` [pair][slice][m-tile] and k_mid_finish adds them in slice order and runs the epilogue.
+// ------------------------------------------------------------------------------------------
+constexpr int MID_KB = 2;        // k-tiles per stage
+constexpr int MID_PAIRS = 8;     // pairs of n-tiles per workgroup (one per wave)
+template <int MT>
+struct MidSet {
+    bf16x8 wa[MID_KB], wb[MID_KB], x[MT / 4];
+};
+
+template <int MT>
+__global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp, int KT,
+                                                        int KS, int n_pairs, int n_mtiles, f32x4 *__restrict__ kpart) {
+    __shared__ __attribute__((aligned(1024))) char lds[2 * MT * MID_KB * 1024];
+    constexpr int XPW = MT / 4;           // activation fragments of a stage fetched by one wave
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int pair = blockIdx.x * MID_PAIRS + wave;
+    const bool live = pair < n_pairs;
+    if (!live) pair = n_pairs - 1;        // a spare wave repeats the last pair and drops the result
+    const int ks = blockIdx.y;
+    const int nst = (KT + MID_KB - 1) / MID_KB;                  // stages in all of K
+    const int sb0 = (int)(((long)ks * nst) / KS), sb1 = (int)(((long)(ks + 1) * nst) / KS);
+    const int ns = sb1 - sb0;                                    // >= 1: the launcher keeps KS <= nst
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)ns);
+    auto stage_of = [&](int st) {
+        st = st < ns ? st : ns - 1;
+        st += rot;
+        return sb0 + (st >= ns ? st - ns : st);
+    };
+    const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
+    const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
+    const bf16x8 *xsrc[XPW];
+#pragma unroll
+    for (int i = 0; i < XPW; ++i) {
+        const int mt = (wave * XPW + i) / MID_KB;
+        xsrc[i] = (const bf16x8 *)(Xp + spd_frag_index(mt < n_mtiles ? mt : n_mtiles - 1, 0, KT)) + lane;
+    }
+    f32x4 acc[MT][2];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[m][0] = acc[m][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    auto load = [&](MidSet<MT> &S, int st) {
+        const int kt0 = stage_of(st) * MID_KB;
+#pragma unroll
+        for (int i = 0; i < XPW; ++i) {
+            const int kt = kt0 + (wave * XPW + i) % MID_KB;
+            S.x[i] = xsrc[i][(size_t)(kt < KT ? kt : KT - 1) * 64];
+        }
+#pragma unroll
+        for (int kb = 0; kb < MID_KB; ++kb) {
+            const int kt = kt0 + kb < KT ? kt0 + kb : KT - 1;
+            S.wa[kb] = __builtin_nontemporal_load(wa + (size_t)kt * 64);
+            S.wb[kb] = __builtin_nontemporal_load(wb + (size_t)kt * 64);
+        }
+    };
+    auto put = [&](const MidSet<MT> &S, int buf) {
+#pragma unroll
+        for (int i = 0; i < XPW; ++i) *(bf16x8 *)(lds + (buf * MT * MID_KB + wave * XPW + i) * 1024 + lane * 16) = S.x[i];
+    };
+    auto compute = [&](const MidSet<MT> &S, int buf, int st) {
+        const int kt0 = stage_of(st) * MID_KB;
+#pragma unroll
+        for (int kb = 0; kb < MID_KB; ++kb) {
+            if (kb > 0 && kt0 + kb >= KT) break;                 // odd number of k-tiles: the last stage holds one
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const bf16x8 x = *(const bf16x8 *)(lds + (buf * MT * MID_KB + m * MID_KB + kb) * 1024 + lane * 16);
+                acc[m][0] = MFMA(S.wa[kb], x, acc[m][0]);
+                acc[m][1] = MFMA(S.wb[kb], x, acc[m][1]);
+            }
+        }
+    };
+    // stage t lives in set t % 4, its activations in LDS buffer t % 2
+    MidSet<MT> st[4];
+    load(st[0], 0);
+    load(st[1], 1);
+    load(st[2], 2);
+    put(st[0], 0);
+    __syncthreads();
+    int s0 = 0;
+    for (; s0 + 4 <= ns; s0 += 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            load(st[(j + 3) & 3], s0 + j + 3);
+            compute(st[j], j & 1, s0 + j);
+            put(st[(j + 1) & 3], (j + 1) & 1);
+            __syncthreads();       // everybody is done with buffer j % 2, buffer (j + 1) % 2 is complete
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        if (s0 + j < ns) {
+            compute(st[j], j & 1, s0 + j);
+            put(st[(j + 1) & 3], (j + 1) & 1);
+        }
+        __syncthreads();
+    }
+    if (!live) return;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        if (m >= n_mtiles) break;
+        f32x4 *dst = kpart + ((((size_t)pair * KS + ks) * n_mtiles + m) * 2) * 64 + lane;
+        dst[0] = acc[m][0];
+        dst[64] = acc[m][1];
+    }
+}
+
+// Adds the KS partial tiles of (pair, m-tile) in slice order and runs the epilogue; one wave per
+// tile pair, four pairs per workgroup.  grid = (ceil(pairs / 4), m-tiles).
+template <class Epi>
+__global__ void __launch_bounds__(256) k_mid_finish(const f32x4 *__restrict__ kpart, int KS, int n_pairs, int n_mtiles, Epi epi) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pair = blockIdx.x * 4 + wave, mt = blockIdx.y;
+    if (pair >= n_pairs) return;
+    const typename Epi::Pre pre = epi.pre(pair, mt, lane);
+    float rs = 1.f;
+    if constexpr (Epi::kNeedsRs) rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
+    const f32x4 *src = kpart + (((size_t)pair * KS * n_mtiles + mt) * 2) * 64 + lane;
+    const size_t sstr = (size_t)n_mtiles * 128;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    int sl = 0;
+    for (; sl + 4 <= KS; sl += 4) {
+        f32x4 ta[4], tb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ta[j] = src[(size_t)(sl + j) * sstr];
+            tb[j] = src[(size_t)(sl + j) * sstr + 64];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            a += ta[j];
+            b += tb[j];
+        }
+    }
+    for (; sl < KS; ++sl) {
+        a += src[(size_t)sl * sstr];
+        b += src[(size_t)sl * sstr + 64];
+    }
+    epi(pair, mt, a, b, lane, rs, pre);
+}
+
 // Adds the K slices that EpiQKVPart left for a call of more than one token per sequence (the
 // decode kernel adds them itself): queries to hi + lo bf16 pairs, keys and values rounded into the
 // cache.  One thread per 4 consecutive columns of a token.
@@ -1632,6 +1784,29 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
     return split ? launch_skinny_mt<8, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
                  : launch_skinny_mt<8, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
 }
+// 65 .. 128 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel.
+// Returns false in *done when the shape is not its kind (the caller then takes the skinny kernel).
+constexpr int MID_MIN_PAIRS = 128;
+template <class Epi>
+hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, int n_pairs, int KT, const Epi &epi, bool *done) {
+    const spd_dims &D = *c.D;
+    const int n_mtiles = (c.M + 15) / 16;
+    *done = false;
+    if (n_mtiles <= 4 || n_mtiles > 8 || n_pairs < MID_MIN_PAIRS) return hipSuccess;
+    const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS, nst = (KT + MID_KB - 1) / MID_KB;
+    // one round of workgroups (one fits a compute unit), at least 4 stages per slice
+    int KS = 254 / groups;
+    if (KS > nst / 4) KS = nst / 4;
+    while (KS > 1 && (size_t)n_pairs * KS * n_mtiles > D.kpart_tiles) --KS;
+    if (KS < 2) return hipSuccess;
+    f32x4 *kpart = (f32x4 *)(c.ws + D.ws_kpart);
+    hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    SPD_TRY(hipGetLastError());
+    hipLaunchKernelGGL((k_mid_finish<Epi>), dim3((n_pairs + 3) / 4, n_mtiles), dim3(256), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
+    *done = true;
+    return hipGetLastError();
+}
+
 constexpr int SKINNY_MAX_MTILES = 32;      // beyond 512 tokens the LDS-tiled GEMM re-reads the weights less often
 
 template <class Epi>
@@ -1696,11 +1871,15 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     int qkv_slices = 1;
     bool fused_q = false, gather_q = false;
     if (gemv_slices(qkv_pairs, D.h / 32) > 1) {
-        // decode: about 240 workgroups of 16 waves; 17 .. 512 tokens: about 320 of 8 waves; at most
-        // SPD_MAX_QKV_SLICES slices and at least two k-tiles per wave
+        // decode: about 240 workgroups of 16 waves; 17 .. 512 tokens: one round of workgroups of 8 waves
+        // (two fit a compute unit with up to 4 m-tiles each, one beyond, because of the LDS they reduce
+        // through); at most SPD_MAX_QKV_SLICES slices and at least two k-tiles per wave
         const bool dec = c.q_len == 1 && n_mtiles == 1;
-        const int want = ((dec ? 240 : 320) + qkv_pairs - 1) / qkv_pairs, wv = dec ? QKV_SLICE_W : SKINNY_W;
-        qkv_slices = want < 2 ? 2 : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
+        const int zgroups = n_mtiles <= 4 ? 1 : (n_mtiles + 7) / 8;
+        const int room = dec ? 240 : (n_mtiles <= 4 ? 480 : 250);
+        const int want = dec ? (room + qkv_pairs - 1) / qkv_pairs : room / (qkv_pairs * zgroups);
+        const int wv = dec ? QKV_SLICE_W : SKINNY_W;
+        qkv_slices = want < 2 ? (dec ? 2 : 1) : (want > SPD_MAX_QKV_SLICES ? SPD_MAX_QKV_SLICES : want);
         if (qkv_slices > D.h / 32 / (2 * wv)) qkv_slices = D.h / 32 / (2 * wv);
         while (qkv_slices > 1 && (size_t)qkv_slices * 16 * n_mtiles * D.nqkv > (size_t)SPD_MAX_KPART * 512) --qkv_slices;
         // (a decode step of any batch size lets the attention kernel add the slices)
@@ -1884,12 +2063,18 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             const __bf16 *wd = (const __bf16 *)(w + D.w_gud), *xlo = xhat + D.pl_x;
             SPD_TRY(c.split ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
                             : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
-        } else if (D.gud_cols && M <= 16 * SKINNY_MAX_MTILES) {
-            e1.cols = D.gud_cols;
-            SPD_TRY(launch_skinny<0>(c, c.split, (const __bf16 *)(w + D.w_gud), xhat, D.pl_x, D.gud_groups, D.h / 32, 1,
-                                     D.gud_cols, e1));
         } else {
-            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+            bool mid = false;
+            if (!c.split) SPD_TRY(launch_mid(c, (const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, e1, &mid));
+            if (mid) {
+                // done
+            } else if (D.gud_cols && M <= 16 * SKINNY_MAX_MTILES) {
+                e1.cols = D.gud_cols;
+                SPD_TRY(launch_skinny<0>(c, c.split, (const __bf16 *)(w + D.w_gud), xhat, D.pl_x, D.gud_groups, D.h / 32, 1,
+                                         D.gud_cols, e1));
+            } else {
+                SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+            }
         }
     }
 
