@@ -954,33 +954,55 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
 }
 
 // Adds the KS partial tiles of (pair, m-tile) in slice order and runs the epilogue; one wave per
-// tile pair, four pairs per workgroup.  grid = (ceil(pairs / 4), m-tiles).
+// pair, the 8 pairs of a k_mid workgroup per workgroup.  grid = (groups of 8 pairs, m-tiles).
+// The norm scale of the m-tile's 16 tokens is computed once per workgroup: thread t adds the
+// partial sums of squares t/16, t/16 + 32, ... of token t%16, then 16 threads add the 32 results
+// in order.
 template <class Epi>
-__global__ void __launch_bounds__(256) k_mid_finish(const f32x4 *__restrict__ kpart, int KS, int n_pairs, int n_mtiles, Epi epi) {
+__global__ void __launch_bounds__(MID_PAIRS * 64) k_mid_finish(const f32x4 *__restrict__ kpart, int KS, int n_pairs, int n_mtiles,
+                                                               Epi epi) {
+    __shared__ float red[32][16];
+    __shared__ float rs_row[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int pair = blockIdx.x * 4 + wave, mt = blockIdx.y;
-    if (pair >= n_pairs) return;
-    const typename Epi::Pre pre = epi.pre(pair, mt, lane);
-    float rs = 1.f;
-    if constexpr (Epi::kNeedsRs) rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, mt * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
-    const f32x4 *src = kpart + (((size_t)pair * KS * n_mtiles + mt) * 2) * 64 + lane;
+    const int pair = blockIdx.x * MID_PAIRS + wave, mt = blockIdx.y;
+    const bool live = pair < n_pairs;
+    typename Epi::Pre pre;
+    if (live) pre = epi.pre(pair, mt, lane);
+    // the first slices are requested before the norm statistics are dealt with
+    const f32x4 *src = kpart + (((size_t)(live ? pair : n_pairs - 1) * KS * n_mtiles + mt) * 2) * 64 + lane;
     const size_t sstr = (size_t)n_mtiles * 128;
-    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-    int sl = 0;
-    for (; sl + 4 <= KS; sl += 4) {
-        f32x4 ta[4], tb[4];
+    f32x4 ta[8], tb[8];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            ta[j] = src[(size_t)(sl + j) * sstr];
-            tb[j] = src[(size_t)(sl + j) * sstr + 64];
+    for (int j = 0; j < 8; ++j) {
+        const int sl = j < KS ? j : KS - 1;
+        ta[j] = src[(size_t)sl * sstr];
+        tb[j] = src[(size_t)sl * sstr + 64];
+    }
+    float rs = 1.f;
+    if constexpr (Epi::kNeedsRs) {
+        const int r = threadIdx.x & 15, part = threadIdx.x >> 4;       // 32 parts
+        float sq = 0.f;
+        for (int c = part; c < epi.nch; c += 32) sq += epi.ss[(size_t)c * epi.m_pad + mt * 16 + r];
+        red[part][r] = sq;
+        __syncthreads();
+        if (threadIdx.x < 16) {
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < 32; ++q) t += red[q][threadIdx.x];
+            rs_row[threadIdx.x] = 1.0f / sqrtf(t / (float)epi.h + epi.eps);
         }
+        __syncthreads();
+        rs = rs_row[lane & 15];
+    }
+    if (!live) return;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j)
+        if (j < KS) {
             a += ta[j];
             b += tb[j];
         }
-    }
-    for (; sl < KS; ++sl) {
+    for (int sl = 8; sl < KS; ++sl) {
         a += src[(size_t)sl * sstr];
         b += src[(size_t)sl * sstr + 64];
     }
@@ -1785,6 +1807,8 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
                  : launch_skinny_mt<8, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
 }
 // 65 .. 128 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel.
+// Used for the gate/up projection only: for the down projection the finishing kernel, which then
+// carries the closing sync point, costs more than the activation traffic it saves (measured).
 // Returns false in *done when the shape is not its kind (the caller then takes the skinny kernel).
 constexpr int MID_MIN_PAIRS = 128;
 template <class Epi>
@@ -1802,7 +1826,7 @@ hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, in
     f32x4 *kpart = (f32x4 *)(c.ws + D.ws_kpart);
     hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
     SPD_TRY(hipGetLastError());
-    hipLaunchKernelGGL((k_mid_finish<Epi>), dim3((n_pairs + 3) / 4, n_mtiles), dim3(256), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
+    hipLaunchKernelGGL((k_mid_finish<Epi>), dim3(groups, n_mtiles), dim3(MID_PAIRS * 64), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
     *done = true;
     return hipGetLastError();
 }
