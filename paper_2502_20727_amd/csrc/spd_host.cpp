@@ -115,8 +115,8 @@ void compute_dims(const spd_config &c, spd_dims &D) {
         D.ws_ss1 = o; o = spd_align256(o + (h / 32) * M * 4);
         D.ws_ss2 = o; o = spd_align256(o + (h / 32) * M * 4);
         D.ws_uhat = o; o = spd_align256(o + 2 * M * f * 2);
-        // partial tiles of the K-sliced launches: the decode sizes always, the 65 .. 128 token kind when calls can be that long
-        D.kpart_tiles = D.max_tokens > 64 ? (size_t)SPD_MID_KPART : (size_t)SPD_MAX_KPART;
+        // partial tiles of the K-sliced launches: the decode sizes always, the 17 .. 128 token kind when calls can be that long
+        D.kpart_tiles = D.max_tokens > 16 ? (size_t)SPD_MID_KPART : (size_t)SPD_MAX_KPART;
         D.ws_kpart = o; o = spd_align256(o + D.kpart_tiles * 512 * 4);
         D.ws_apart = o;
         o = spd_align256(o + (size_t)D.max_batch * D.kv * SPD_MAX_SPLITS * 16 * (D.d + 2) * 4);

@@ -33,7 +33,7 @@ constexpr int SPD_N_COUNTERS = 8192;
 constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of at most this many tokens carry the MLP inputs as hi + lo pairs
 constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
-constexpr int SPD_MID_KPART = 2304 * 8;   // ... and a call of 65 .. 128 tokens (pairs x splits x m-tiles)
+constexpr int SPD_MID_KPART = 2304 * 8;   // ... and a call of 17 .. 128 tokens (pairs x splits x m-tiles)
 
 SPD_HD size_t spd_frag_index(int tile, int ktile, int n_ktiles) {
     return ((size_t)tile * (size_t)n_ktiles + (size_t)ktile) * SPD_FRAG_ELEMS;

@@ -836,7 +836,7 @@ __global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp
 }
 
 // ------------------------------------------------------------------------------------------
-// Projection with many n-tiles for 65 .. 128 tokens ("mid").  In k_skinny every workgroup pulls all
+// Projection with many n-tiles for 17 .. 128 tokens ("mid").  In k_skinny every workgroup pulls all
 // activations of its slice of K through the L2 for only two n-tiles, and from about 64 tokens on
 // that traffic (K x M x 2 B per workgroup), not the weight stream, sets the time.  Here a
 // workgroup owns 8 pairs of n-tiles (wave w: pair 8 * group + w) and one of KS slices of K; all
@@ -853,14 +853,16 @@ constexpr int MID_KB = 2;        // k-tiles per stage
 constexpr int MID_PAIRS = 8;     // pairs of n-tiles per workgroup (one per wave)
 template <int MT>
 struct MidSet {
-    bf16x8 wa[MID_KB], wb[MID_KB], x[MT / 4];
+    bf16x8 wa[MID_KB], wb[MID_KB], x[MT >= 4 ? MT / 4 : 1];
 };
 
 template <int MT>
 __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp, int KT,
                                                         int KS, int n_pairs, int n_mtiles, f32x4 *__restrict__ kpart) {
     __shared__ __attribute__((aligned(1024))) char lds[2 * MT * MID_KB * 1024];
-    constexpr int XPW = MT / 4;           // activation fragments of a stage fetched by one wave
+    // activation fragments of a stage fetched by one wave (with 2 m-tiles there are only 4 fragments: waves
+    // 4 .. 7 fetch and store the same ones again, which keeps the loop free of branches)
+    constexpr int XPW = MT >= 4 ? MT / 4 : 1, NFRAG = MT * MID_KB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int pair = blockIdx.x * MID_PAIRS + wave;
     const bool live = pair < n_pairs;
@@ -880,7 +882,7 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     const bf16x8 *xsrc[XPW];
 #pragma unroll
     for (int i = 0; i < XPW; ++i) {
-        const int mt = (wave * XPW + i) / MID_KB;
+        const int mt = ((wave * XPW + i) % NFRAG) / MID_KB;
         xsrc[i] = (const bf16x8 *)(Xp + spd_frag_index(mt < n_mtiles ? mt : n_mtiles - 1, 0, KT)) + lane;
     }
     f32x4 acc[MT][2];
@@ -891,7 +893,7 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
         const int kt0 = stage_of(st) * MID_KB;
 #pragma unroll
         for (int i = 0; i < XPW; ++i) {
-            const int kt = kt0 + (wave * XPW + i) % MID_KB;
+            const int kt = kt0 + ((wave * XPW + i) % NFRAG) % MID_KB;
             S.x[i] = xsrc[i][(size_t)(kt < KT ? kt : KT - 1) * 64];
         }
 #pragma unroll
@@ -903,7 +905,7 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     };
     auto put = [&](const MidSet<MT> &S, int buf) {
 #pragma unroll
-        for (int i = 0; i < XPW; ++i) *(bf16x8 *)(lds + (buf * MT * MID_KB + wave * XPW + i) * 1024 + lane * 16) = S.x[i];
+        for (int i = 0; i < XPW; ++i) *(bf16x8 *)(lds + (buf * NFRAG + (wave * XPW + i) % NFRAG) * 1024 + lane * 16) = S.x[i];
     };
     auto compute = [&](const MidSet<MT> &S, int buf, int st) {
         const int kt0 = stage_of(st) * MID_KB;
@@ -1020,11 +1022,16 @@ __global__ void __launch_bounds__(256) k_qkv_gather(const float *__restrict__ pa
     if (id >= (int64_t)M * n4) return;
     const int m = (int)(id / n4), col = (int)(id % n4) * 4;
     const float *src = part + (size_t)m * nqkv + col;
-    float4 acc = *(const float4 *)src;
-    for (int s = 1; s < KS; ++s) {
-        const float4 v = *(const float4 *)(src + (size_t)s * m_pad * nqkv);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
+    // all slices are requested before the first is added (KS <= SPD_MAX_QKV_SLICES)
+    float4 sl[SPD_MAX_QKV_SLICES];
+#pragma unroll
+    for (int s = 0; s < SPD_MAX_QKV_SLICES; ++s) sl[s] = *(const float4 *)(src + (size_t)(s < KS ? s : KS - 1) * m_pad * nqkv);
+    float4 acc = sl[0];
+#pragma unroll
+    for (int s = 1; s < SPD_MAX_QKV_SLICES; ++s)
+        if (s < KS) {
+            acc.x += sl[s].x; acc.y += sl[s].y; acc.z += sl[s].z; acc.w += sl[s].w;
+        }
     const bf16x4 hi = cvt4(acc.x, acc.y, acc.z, acc.w);
     const int qd = q * d, bseq = m / q_len, pos = P.pos[bseq] + (m % q_len);
     if (col < qd) {
@@ -1806,7 +1813,7 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
     return split ? launch_skinny_mt<8, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
                  : launch_skinny_mt<8, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
 }
-// 65 .. 128 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel.
+// 17 .. 128 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel.
 // Used for the gate/up projection only: for the down projection the finishing kernel, which then
 // carries the closing sync point, costs more than the activation traffic it saves (measured).
 // Returns false in *done when the shape is not its kind (the caller then takes the skinny kernel).
@@ -1816,7 +1823,7 @@ hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, in
     const spd_dims &D = *c.D;
     const int n_mtiles = (c.M + 15) / 16;
     *done = false;
-    if (n_mtiles <= 4 || n_mtiles > 8 || n_pairs < MID_MIN_PAIRS) return hipSuccess;
+    if (n_mtiles <= 1 || n_mtiles > 8 || n_pairs < MID_MIN_PAIRS) return hipSuccess;
     const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS, nst = (KT + MID_KB - 1) / MID_KB;
     // one round of workgroups (one fits a compute unit), at least 4 stages per slice
     int KS = 254 / groups;
@@ -1824,7 +1831,12 @@ hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, in
     while (KS > 1 && (size_t)n_pairs * KS * n_mtiles > D.kpart_tiles) --KS;
     if (KS < 2) return hipSuccess;
     f32x4 *kpart = (f32x4 *)(c.ws + D.ws_kpart);
-    hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    if (n_mtiles <= 2)
+        hipLaunchKernelGGL((k_mid<2>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    else if (n_mtiles <= 4)
+        hipLaunchKernelGGL((k_mid<4>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    else
+        hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
     SPD_TRY(hipGetLastError());
     hipLaunchKernelGGL((k_mid_finish<Epi>), dim3(groups, n_mtiles), dim3(MID_PAIRS * 64), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
     *done = true;

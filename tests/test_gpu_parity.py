@@ -142,7 +142,7 @@ NARROW_GU = Workload(name="narrow-gate-up", hidden=256, n_q_heads=4, n_kv_heads=
 
 
 # 2080 FFN columns per rank (130 pairs of gate/up tiles: 17 groups of 8, the last with 2) and 37 k-tiles
-# (19 stages of two, the last with one, in 4 slices of 4 or 5): a call of 65 .. 128 tokens takes the
+# (19 stages of two, the last with one, in 4 slices of 4 or 5): a call of 17 .. 128 tokens takes the
 # gate/up kernel that shares the activations through LDS and cuts K into slices
 WIDE_MID = Workload(name="wide-ffn-mid", hidden=1184, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=4160, n_layers=1,
                     tp=2, dtype=BF16, seed=17, batch=2, q_len=1, ctx=64, mask=(1,))
@@ -152,11 +152,12 @@ WIDE_MID = Workload(name="wide-ffn-mid", hidden=1184, n_q_heads=4, n_kv_heads=2,
 @pytest.mark.parametrize("batch,q_len,positions", [
     (3, 1, [0, 17, 40]),          # decode, ragged contexts, one sequence with a single key
     (2, 7, [0, 5]),               # 14 tokens: a partial m-tile
+    (2, 10, [0, 4]),              # 20 tokens: two m-tiles
     (3, 11, [3, 0, 20]),          # 33 tokens: three m-tiles with a ragged tail
     (1, 40, [8]),                 # one long chunk crossing several key blocks
     (2, 50, [0, 5]),              # 100 tokens: seven m-tiles, the last one ragged
     (3, 50, [0, 5, 14]),          # 150 tokens: the LDS-tiled GEMM with a partly empty workgroup tile
-], ids=["decode", "chunk14", "chunk33", "chunk40", "chunk100", "chunk150"])
+], ids=["decode", "chunk14", "chunk20", "chunk33", "chunk40", "chunk100", "chunk150"])
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
     import torch
