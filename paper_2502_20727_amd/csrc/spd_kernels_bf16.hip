@@ -1807,6 +1807,9 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
                          int KS, int rows, const Epi &epi) {
     const int n_mtiles = (c.M + 15) / 16;
     const __bf16 *Xlo = Xhi + plane;
+    if (n_mtiles <= 2)
+        return split ? launch_skinny_mt<2, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
+                     : launch_skinny_mt<2, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
     if (n_mtiles <= 4)
         return split ? launch_skinny_mt<4, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
                      : launch_skinny_mt<4, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
