@@ -146,6 +146,90 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
     if (ss && g == 0 && chunk * tpw < KT) ss[(size_t)chunk * m_pad + m] = ssum;
 }
 
+// prep for long calls (more than 512 tokens, hidden size a multiple of 256): the same sums in the
+// same order, but every load and store of fp32 data covers 1 KiB of one token's row (a wave per
+// token, lane l at features 4l .. 4l+3 of a chunk of 256) instead of 128-byte pieces of 16 rows, which
+// the HBM serves at a higher rate.  One workgroup per (chunk of 256 features, m-tile); wave w takes
+// tokens w, w+4, w+8, w+12.  The normalised bf16 values are turned into fragments through LDS.
+// Sums of squares: one partial per (chunk, token), as k_prep with 8 k-tiles per wave.
+constexpr int PREP_ROW_PITCH = 256 + 8;      // bf16 elements; the pad spreads the fragment reads over the banks
+__global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
+                                                   size_t slot_stride, float *__restrict__ out,
+                                                   const float *__restrict__ gain, __bf16 *__restrict__ xhat,
+                                                   __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h,
+                                                   int m_pad, const float *__restrict__ bias) {
+    __shared__ __attribute__((aligned(16))) __bf16 tile[2][16][PREP_ROW_PITCH];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x, mt = blockIdx.y, KT = h >> 5;
+    const int col = chunk * 256 + lane * 4;
+    float4 gn = make_float4(0.f, 0.f, 0.f, 0.f), bs = gn;
+    if (xhat) gn = *(const float4 *)(gain + col);
+    if (bias) bs = *(const float4 *)(bias + col);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        // two tokens at a time: their loads are all issued before the first sum
+        float4 p[2][8], b[2];
+        bool valid[2];
+        size_t off[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int m = mt * 16 + wave + 4 * (2 * half + t);
+            valid[t] = m < M;
+            off[t] = (size_t)(valid[t] ? m : M - 1) * h + col;
+        }
+        float4 v[2];
+        v[0] = v[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < n_slots; s0 += 8) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (s0 + j < n_slots) p[t][j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + off[t]);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (s0 + j < n_slots) {
+                        if (s0 + j == 0) v[t] = p[t][j];
+                        else { v[t].x += p[t][j].x; v[t].y += p[t][j].y; v[t].z += p[t][j].z; v[t].w += p[t][j].w; }
+                    }
+        }
+        if (base) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) b[t] = *(const float4 *)(base + off[t]);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) { v[t].x = b[t].x + v[t].x; v[t].y = b[t].y + v[t].y; v[t].z = b[t].z + v[t].z; v[t].w = b[t].w + v[t].w; }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int r = wave + 4 * (2 * half + t);
+            if (bias) { v[t].x += bs.x; v[t].y += bs.y; v[t].z += bs.z; v[t].w += bs.w; }
+            if (!valid[t]) v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (out && valid[t]) *(float4 *)(out + off[t]) = v[t];
+            float sq = v[t].x * v[t].x + v[t].y * v[t].y + v[t].z * v[t].z + v[t].w * v[t].w;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) sq += shfl_xor_f(sq, o);
+            if (ss && lane == 0) ss[(size_t)chunk * m_pad + mt * 16 + r] = sq;
+            if (xhat) {
+                const float q0 = v[t].x * gn.x, q1 = v[t].y * gn.y, q2 = v[t].z * gn.z, q3 = v[t].w * gn.w;
+                const bf16x4 hi = cvt4(q0, q1, q2, q3);
+                *(bf16x4 *)&tile[0][r][lane * 4] = hi;
+                if (xlo) *(bf16x4 *)&tile[1][r][lane * 4] = cvt4_lo(q0, q1, q2, q3, hi);
+            }
+        }
+    }
+    if (!xhat) return;
+    __syncthreads();
+    // fragments 2 * wave and 2 * wave + 1 of the chunk's 8 k-tiles
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        const int kt = 2 * wave + f, r = lane & 15, g = lane >> 4;
+        const size_t fo = spd_frag_index(mt, chunk * 8 + kt, KT) + lane * 8;
+        *(bf16x8 *)(xhat + fo) = *(const bf16x8 *)&tile[0][r][kt * 32 + g * 8];
+        if (xlo) *(bf16x8 *)(xlo + fo) = *(const bf16x8 *)&tile[1][r][kt * 32 + g * 8];
+    }
+}
+
 // The sum over the ranks at a sync point, for one rank whose own partial is still in registers:
 // out = base + (slot_0 + ... + slot_tp-1) [+ bias], the own partial standing in for slot `rank`.
 // both halves of a tile at once, eight slots at a time: all 16 loads of a round (and the two base
@@ -1885,8 +1969,12 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     if (n_slots == 0 && out == base && !bias) out = nullptr;   // nothing to rewrite
     if (!spd_profile::enabled(SPD_STAGE_PREP)) return hipSuccess;
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
-    hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                       (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
+    if (tpw == 8 && D.h % 256 == 0)
+        hipLaunchKernelGGL(k_prep_rows, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
+                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
+    else
+        hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
+                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
     return hipGetLastError();
 }
 

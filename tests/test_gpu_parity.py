@@ -198,6 +198,30 @@ def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
     case.close()
 
 
+@pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
+@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
+def test_bf16_long_call_small_shape(gpu, flag, split):
+    """More than 512 tokens in one call on a small shape, all ranks: the launch shapes of the long
+    prefill (LDS-tiled GEMM, key-split attention, row-wise norm preparation) with a ragged last
+    m-tile, every output element checked."""
+    import torch
+    w = SMALL
+    batch, q_len, positions = 3, 181, [0, 0, 0]          # 543 tokens = 33 m-tiles + 15 rows
+    M = batch * q_len
+    case = Case(w, gpu, ranks=range(w.tp), positions=positions, max_ctx=192, max_tokens=M, act_split=split)
+    X = inputs.hidden_states(w, M)
+    slots = torch.zeros((w.tp, M, w.hidden), dtype=torch.float32, device=gpu)
+    say(f"long call on the small shape: {M} tokens flag={flag} split={split}")
+    out = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
+    B.spd_block_forward(case.dev.ctx, 0, flag, B.SPD_ALL_RANKS, case.dev.weights[0], case.dev.kv[0], positions, batch,
+                        q_len, case.to_dev(X), slots, out, case.dev.workspace)
+    torch.cuda.synchronize()
+    want, _ = O.block_all_ranks(case.sh, X, case.shards[0], case.caches[0], positions, batch, q_len, flag, {})
+    err = assert_close(out.cpu().numpy(), want, w, "long call block output")
+    say(f"  block output max err {err:.2e} (max |oracle| {np.max(np.abs(want)):.2f})")
+    case.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # block with bias in the output projection (Sec. 4.1.2): both paths, both block kinds
 # ------------------------------------------------------------------------------------------------
