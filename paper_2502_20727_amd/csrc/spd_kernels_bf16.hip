@@ -149,82 +149,103 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 // prep for long calls (more than 512 tokens, hidden size a multiple of 256): the same sums in the
 // same order, but every load and store of fp32 data covers 1 KiB of one token's row (a wave per
 // token, lane l at features 4l .. 4l+3 of a chunk of 256) instead of 128-byte pieces of 16 rows, which
-// the HBM serves at a higher rate.  One workgroup per (chunk of 256 features, m-tile); wave w takes
+// the HBM serves at a higher rate.  One workgroup per (NP chunks of 256 features, m-tile); wave w takes
 // tokens w, w+4, w+8, w+12.  The normalised bf16 values are turned into fragments through LDS.
 // Sums of squares: one partial per (chunk, token), as k_prep with 8 k-tiles per wave.
-constexpr int PREP_ROW_PITCH = 256 + 8;      // bf16 elements; the pad spreads the fragment reads over the banks
+template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
                                                    const float *__restrict__ gain, __bf16 *__restrict__ xhat,
                                                    __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h,
                                                    int m_pad, const float *__restrict__ bias) {
-    __shared__ __attribute__((aligned(16))) __bf16 tile[2][16][PREP_ROW_PITCH];
+    constexpr int PITCH = NP * 256 + 8;      // bf16 elements; the pad spreads the fragment reads over the banks
+    __shared__ __attribute__((aligned(16))) __bf16 tile[2][16][PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int chunk = blockIdx.x, mt = blockIdx.y, KT = h >> 5;
-    const int col = chunk * 256 + lane * 4;
-    float4 gn = make_float4(0.f, 0.f, 0.f, 0.f), bs = gn;
-    if (xhat) gn = *(const float4 *)(gain + col);
-    if (bias) bs = *(const float4 *)(bias + col);
+    const int chunk0 = blockIdx.x * NP, mt = blockIdx.y, KT = h >> 5;
+    const int col = chunk0 * 256 + lane * 4;           // piece q: + 256 q
+    float4 gn[NP], bs[NP];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        // two tokens at a time: their loads are all issued before the first sum
-        float4 p[2][8], b[2];
-        bool valid[2];
-        size_t off[2];
+    for (int q = 0; q < NP; ++q) {
+        gn[q] = bs[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (xhat) gn[q] = *(const float4 *)(gain + col + 256 * q);
+        if (bias) bs[q] = *(const float4 *)(bias + col + 256 * q);
+    }
+    constexpr int TB = NP == 1 ? 4 : 1;      // tokens whose loads are in flight together
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int m = mt * 16 + wave + 4 * (2 * half + t);
+    for (int it = 0; it < 4 / TB; ++it) {
+        float4 p[TB][NP][8], b[TB][NP], v[TB][NP];
+        bool valid[TB];
+        size_t off[TB];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            const int m = mt * 16 + wave + 4 * (TB * it + t);
             valid[t] = m < M;
             off[t] = (size_t)(valid[t] ? m : M - 1) * h + col;
+#pragma unroll
+            for (int q = 0; q < NP; ++q) v[t][q] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        float4 v[2];
-        v[0] = v[1] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int s0 = 0; s0 < n_slots; s0 += 8) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < TB; ++t)
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if (s0 + j < n_slots) p[t][j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + off[t]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                    for (int q = 0; q < NP; ++q)
+                        if (s0 + j < n_slots) p[t][q][j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + off[t] + 256 * q);
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (s0 + j < n_slots) {
-                        if (s0 + j == 0) v[t] = p[t][j];
-                        else { v[t].x += p[t][j].x; v[t].y += p[t][j].y; v[t].z += p[t][j].z; v[t].w += p[t][j].w; }
-                    }
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int q = 0; q < NP; ++q)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (s0 + j < n_slots) {
+                            const float4 a = p[t][q][j];
+                            if (s0 + j == 0) v[t][q] = a;
+                            else { v[t][q].x += a.x; v[t][q].y += a.y; v[t][q].z += a.z; v[t][q].w += a.w; }
+                        }
         }
         if (base) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) b[t] = *(const float4 *)(base + off[t]);
+            for (int t = 0; t < TB; ++t)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) { v[t].x = b[t].x + v[t].x; v[t].y = b[t].y + v[t].y; v[t].z = b[t].z + v[t].z; v[t].w = b[t].w + v[t].w; }
+                for (int q = 0; q < NP; ++q) b[t][q] = *(const float4 *)(base + off[t] + 256 * q);
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int q = 0; q < NP; ++q) {
+                    v[t][q].x = b[t][q].x + v[t][q].x; v[t][q].y = b[t][q].y + v[t][q].y;
+                    v[t][q].z = b[t][q].z + v[t][q].z; v[t][q].w = b[t][q].w + v[t][q].w;
+                }
         }
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int r = wave + 4 * (2 * half + t);
-            if (bias) { v[t].x += bs.x; v[t].y += bs.y; v[t].z += bs.z; v[t].w += bs.w; }
-            if (!valid[t]) v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (out && valid[t]) *(float4 *)(out + off[t]) = v[t];
-            float sq = v[t].x * v[t].x + v[t].y * v[t].y + v[t].z * v[t].z + v[t].w * v[t].w;
+        for (int t = 0; t < TB; ++t) {
+            const int r = wave + 4 * (TB * it + t);
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) sq += shfl_xor_f(sq, o);
-            if (ss && lane == 0) ss[(size_t)chunk * m_pad + mt * 16 + r] = sq;
-            if (xhat) {
-                const float q0 = v[t].x * gn.x, q1 = v[t].y * gn.y, q2 = v[t].z * gn.z, q3 = v[t].w * gn.w;
-                const bf16x4 hi = cvt4(q0, q1, q2, q3);
-                *(bf16x4 *)&tile[0][r][lane * 4] = hi;
-                if (xlo) *(bf16x4 *)&tile[1][r][lane * 4] = cvt4_lo(q0, q1, q2, q3, hi);
+            for (int q = 0; q < NP; ++q) {
+                float4 u = v[t][q];
+                if (bias) { u.x += bs[q].x; u.y += bs[q].y; u.z += bs[q].z; u.w += bs[q].w; }
+                if (!valid[t]) u = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (out && valid[t]) *(float4 *)(out + off[t] + 256 * q) = u;
+                float sq = u.x * u.x + u.y * u.y + u.z * u.z + u.w * u.w;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) sq += shfl_xor_f(sq, o);
+                if (ss && lane == 0) ss[(size_t)(chunk0 + q) * m_pad + mt * 16 + r] = sq;
+                if (xhat) {
+                    const float q0 = u.x * gn[q].x, q1 = u.y * gn[q].y, q2 = u.z * gn[q].z, q3 = u.w * gn[q].w;
+                    const bf16x4 hi = cvt4(q0, q1, q2, q3);
+                    *(bf16x4 *)&tile[0][r][256 * q + lane * 4] = hi;
+                    if (xlo) *(bf16x4 *)&tile[1][r][256 * q + lane * 4] = cvt4_lo(q0, q1, q2, q3, hi);
+                }
             }
         }
     }
     if (!xhat) return;
     __syncthreads();
-    // fragments 2 * wave and 2 * wave + 1 of the chunk's 8 k-tiles
+    // wave w writes fragments 2 NP w .. 2 NP w + 2 NP - 1 of the workgroup's 8 NP k-tiles
 #pragma unroll
-    for (int f = 0; f < 2; ++f) {
-        const int kt = 2 * wave + f, r = lane & 15, g = lane >> 4;
-        const size_t fo = spd_frag_index(mt, chunk * 8 + kt, KT) + lane * 8;
+    for (int f = 0; f < 2 * NP; ++f) {
+        const int kt = 2 * NP * wave + f, r = lane & 15, g = lane >> 4;
+        const size_t fo = spd_frag_index(mt, chunk0 * 8 + kt, KT) + lane * 8;
         *(bf16x8 *)(xhat + fo) = *(const bf16x8 *)&tile[0][r][kt * 32 + g * 8];
         if (xlo) *(bf16x8 *)(xlo + fo) = *(const bf16x8 *)&tile[1][r][kt * 32 + g * 8];
     }
@@ -1969,8 +1990,9 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     if (n_slots == 0 && out == base && !bias) out = nullptr;   // nothing to rewrite
     if (!spd_profile::enabled(SPD_STAGE_PREP)) return hipSuccess;
     spd_profile::scope prof(SPD_STAGE_PREP, c.s);
+    // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
     if (tpw == 8 && D.h % 256 == 0)
-        hipLaunchKernelGGL(k_prep_rows, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
+        hipLaunchKernelGGL(k_prep_rows<1>, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
                            (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
     else
         hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,

@@ -198,14 +198,19 @@ def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
     case.close()
 
 
+SMALL_H512 = Workload(name="small-bf16-h512", hidden=512, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=832, n_layers=1,
+                      tp=4, dtype=BF16, seed=18, batch=3, q_len=1, ctx=64, mask=(1,))
+
+
+@pytest.mark.parametrize("w", [SMALL, SMALL_H512], ids=lambda w: w.name)
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 @pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
-def test_bf16_long_call_small_shape(gpu, flag, split):
+def test_bf16_long_call_small_shape(gpu, w, flag, split):
     """More than 512 tokens in one call on a small shape, all ranks: the launch shapes of the long
     prefill (LDS-tiled GEMM, key-split attention, row-wise norm preparation) with a ragged last
-    m-tile, every output element checked."""
+    m-tile, every output element checked (hidden size 256 and 512: one and two pieces of 256 features per
+    workgroup of the row-wise preparation)."""
     import torch
-    w = SMALL
     batch, q_len, positions = 3, 181, [0, 0, 0]          # 543 tokens = 33 m-tiles + 15 rows
     M = batch * q_len
     case = Case(w, gpu, ranks=range(w.tp), positions=positions, max_ctx=192, max_tokens=M, act_split=split)
