@@ -1221,6 +1221,9 @@ struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per comp
 struct GemmMid {      // 4 waves, 256 x 128, steps of 32: 48 KiB of LDS, two or three workgroups per compute unit
     static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2;
 };
+struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
+    static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
+};
 
 template <class Epi, class G>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
@@ -1359,6 +1362,11 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
     // both shapes measure the same on the 70B shard (the big one is ahead by 1-3 % on QKV and down);
     // the mid one also takes an odd number of k-tiles
     if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid>(c, Wp, Xp, n_pairs, KT, epi);
+    // fewer 256 x 256 tiles than compute units (the QKV projection of a shard): 128 x 384 tiles when they
+    // fill one round better
+    const int n_mtiles = (c.M + 15) / 16;
+    const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
+    if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall>(c, Wp, Xp, n_pairs, KT, epi);
     return launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi);
 }
 
