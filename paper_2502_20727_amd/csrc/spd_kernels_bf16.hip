@@ -1221,13 +1221,17 @@ struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per comp
 struct GemmMid {      // 4 waves, 256 x 128, steps of 32: 48 KiB of LDS, two or three workgroups per compute unit
     static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2;
 };
+struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile (96 KiB of LDS: still one workgroup per compute unit)
+    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 4, KPS = 2, MINB = 1;
+};
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
     static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
 };
 
 template <class Epi, class G>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
-                                                                   int KT, int n_ntiles, int n_mtiles, int TN, Epi epi) {
+                                                                   int KT, int n_ntiles, int n_mtiles, int TN, int tile0, int msub,
+                                                                   Epi epi) {
     constexpr int GL_WN = G::WN, GL_WM = G::WM, GL_TI = G::TI, GL_TJ = G::TJ, KPS = G::KPS;
     constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // tiles per workgroup
     constexpr int GL_STAGE = (GL_BN + GL_BM) * KPS * 1024;
@@ -1236,8 +1240,11 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wn = wave % GL_WN, wm = wave / GL_WN;
-    const int tn = blockIdx.x % TN, tm = blockIdx.x / TN;
-    const int nt0 = tn * GL_BN, mt0 = tm * GL_BM;
+    // tiles are numbered along N first; a launch covers the tiles from `tile0` on, each cut into `msub`
+    // workgroup tiles along M (1, or 2 for the launch that finishes a ragged last round with half tiles)
+    const int tid = tile0 + (int)blockIdx.x / msub, sub = (int)blockIdx.x % msub;
+    const int tn = tid % TN, tm = tid / TN;
+    const int nt0 = tn * GL_BN, mt0 = (tm * msub + sub) * GL_BM;
     f32x4 acc[GL_TI][GL_TJ];
 #pragma unroll
     for (int i = 0; i < GL_TI; ++i)
@@ -1342,8 +1349,11 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
 }
 
 template <class G, class Epi>
-hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
-    constexpr int BN = G::WN * G::TI, BM = G::WM * G::TJ, STAGE = (BN + BM) * G::KPS * 1024;
+hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi,
+                               int tile0 = 0, int msub = 1, int n_wgs = -1) {
+    // with msub = 2 the tiles are counted in the shape of twice G's height (GemmHalf finishing a GemmBig launch)
+    constexpr int BN = G::WN * G::TI, STAGE = (BN + G::WM * G::TJ) * G::KPS * 1024;
+    const int BM = G::WM * G::TJ * msub;
     static bool attr_set = false;       // the attribute is per kernel instantiation; setting it twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
@@ -1352,8 +1362,9 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     }
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
     const int TN = (n_ntiles + BN - 1) / BN, TM = (n_mtiles + BM - 1) / BM;
-    hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(TN * TM), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
-                       n_mtiles, TN, epi);
+    if (n_wgs < 0) n_wgs = (TN * TM - tile0) * msub;
+    hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
+                       n_mtiles, TN, tile0, msub, epi);
     return hipGetLastError();
 }
 
@@ -1367,6 +1378,14 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
     const int n_mtiles = (c.M + 15) / 16;
     const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
     if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall>(c, Wp, Xp, n_pairs, KT, epi);
+    // a last round that would occupy at most half of the compute units runs as twice as many half tiles
+    // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)
+    const int rem = big % 256;
+    if (big > 256 && rem > 0 && rem <= 128) {
+        const hipError_t e = launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi, 0, 1, big - rem);
+        if (e != hipSuccess) return e;
+        return launch_gemm_lds_cfg<GemmHalf>(c, Wp, Xp, n_pairs, KT, epi, big - rem, 2, 2 * rem);
+    }
     return launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi);
 }
 
