@@ -31,7 +31,10 @@ import numpy as np
 # FETCH_SIZE counts 2 KiB per unit on this device (a 1 GiB copy reads 524300), WRITE_SIZE 1 KiB.
 MEASURED_TRAFFIC = {
     "llama2-70b-tp8-decode-b16-ctx4096": (59518 * 2 + 320) * 1024,        # 122.2 MB vs 117.9 MB algorithmic
-    "llama2-70b-tp8-prefill-b4x2048": (1078690 * 2 + 57344) * 1024,       # 2.27 GB: tiles re-read past the L2
+    # the two launches of the stage (256x256 tiles + the half tiles of the last round): 2.16 GB, tiles re-read past the L2
+    "llama2-70b-tp8-prefill-b4x2048": ((863671 + 163777) * 2 + 49152 + 8192) * 1024,
+    # k_mid + k_mid_finish: 206 MB (weights once, 29 MB of K-slice partials written and read back) vs 120.5 MB algorithmic
+    "llama2-70b-tp8-prefill-b1x128": ((67432 + 16676) * 2 + 32256 + 896) * 1024,
 }
 
 
@@ -286,7 +289,7 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
     if M_tok > 512:
-        roof["kernel"] = "k_gemm_lds<EpiGU,GemmBig>"
+        roof["kernel"] = "k_gemm_lds<EpiGU,GemmBig> (+ GemmHalf for a ragged last round of tiles)"
     elif M_tok > 16 and M_tok <= 128 and w.ffn_per_rank // 16 >= 128:
         roof["kernel"] = "k_mid<MT> + k_mid_finish<EpiGU>"      # the stage is these two launches
     elif M_tok > 16:
