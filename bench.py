@@ -290,7 +290,7 @@ def main():
     roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
     if M_tok > 512:
         roof["kernel"] = "k_gemm_lds<EpiGU,GemmBig> (+ GemmHalf for a ragged last round of tiles)"
-    elif M_tok > 16 and M_tok <= 128 and w.ffn_per_rank // 16 >= 128:
+    elif M_tok > 16 and w.ffn_per_rank // 16 >= 128:
         roof["kernel"] = "k_mid<MT> + k_mid_finish<EpiGU>"      # the stage is these two launches
     elif M_tok > 16:
         roof["kernel"] = "k_skinny<8,MT,*,0,EpiGU>"

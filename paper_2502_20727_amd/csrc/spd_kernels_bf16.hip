@@ -941,7 +941,7 @@ __global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp
 }
 
 // ------------------------------------------------------------------------------------------
-// Projection with many n-tiles for 17 .. 128 tokens ("mid").  In k_skinny every workgroup pulls all
+// Projection with many n-tiles for 17 .. 512 tokens ("mid").  In k_skinny every workgroup pulls all
 // activations of its slice of K through the L2 for only two n-tiles, and from about 64 tokens on
 // that traffic (K x M x 2 B per workgroup), not the weight stream, sets the time.  Here a
 // workgroup owns 8 pairs of n-tiles (wave w: pair 8 * group + w) and one of KS slices of K; all
@@ -972,11 +972,11 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     int pair = blockIdx.x * MID_PAIRS + wave;
     const bool live = pair < n_pairs;
     if (!live) pair = n_pairs - 1;        // a spare wave repeats the last pair and drops the result
-    const int ks = blockIdx.y;
+    const int ks = blockIdx.y, mt0 = blockIdx.z * MT;            // grid.z: groups of MT m-tiles (calls of more than 16 MT tokens)
     const int nst = (KT + MID_KB - 1) / MID_KB;                  // stages in all of K
     const int sb0 = (int)(((long)ks * nst) / KS), sb1 = (int)(((long)(ks + 1) * nst) / KS);
     const int ns = sb1 - sb0;                                    // >= 1: the launcher keeps KS <= nst
-    const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)ns);
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u + blockIdx.z * 7u) % (unsigned)ns);
     auto stage_of = [&](int st) {
         st = st < ns ? st : ns - 1;
         st += rot;
@@ -987,7 +987,7 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     const bf16x8 *xsrc[XPW];
 #pragma unroll
     for (int i = 0; i < XPW; ++i) {
-        const int mt = ((wave * XPW + i) % NFRAG) / MID_KB;
+        const int mt = mt0 + ((wave * XPW + i) % NFRAG) / MID_KB;
         xsrc[i] = (const bf16x8 *)(Xp + spd_frag_index(mt < n_mtiles ? mt : n_mtiles - 1, 0, KT)) + lane;
     }
     f32x4 acc[MT][2];
@@ -1053,8 +1053,8 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     if (!live) return;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-        if (m >= n_mtiles) break;
-        f32x4 *dst = kpart + ((((size_t)pair * KS + ks) * n_mtiles + m) * 2) * 64 + lane;
+        if (mt0 + m >= n_mtiles) break;
+        f32x4 *dst = kpart + ((((size_t)pair * KS + ks) * n_mtiles + mt0 + m) * 2) * 64 + lane;
         dst[0] = acc[m][0];
         dst[64] = acc[m][1];
     }
@@ -1948,37 +1948,39 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
     return split ? launch_skinny_mt<8, true, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi)
                  : launch_skinny_mt<8, false, MODE>(c, Wp, Xhi, Xlo, n_groups, KT, KS, n_mtiles, rows, epi);
 }
-// 17 .. 128 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel.
+// 17 .. 512 tokens, activations not split, at least 128 pairs: the mid kernel and its finishing kernel
+// (beyond 128 tokens in groups of 8 m-tiles, every group streaming the weights again).
 // Used for the gate/up projection only: for the down projection the finishing kernel, which then
 // carries the closing sync point, costs more than the activation traffic it saves (measured).
 // Returns false in *done when the shape is not its kind (the caller then takes the skinny kernel).
+constexpr int SKINNY_MAX_MTILES = 32;      // beyond 512 tokens the LDS-tiled GEMM re-reads the weights less often
 constexpr int MID_MIN_PAIRS = 128;
 template <class Epi>
 hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, int n_pairs, int KT, const Epi &epi, bool *done) {
     const spd_dims &D = *c.D;
     const int n_mtiles = (c.M + 15) / 16;
     *done = false;
-    if (n_mtiles <= 1 || n_mtiles > 8 || n_pairs < MID_MIN_PAIRS) return hipSuccess;
+    if (n_mtiles <= 1 || n_mtiles > SKINNY_MAX_MTILES || n_pairs < MID_MIN_PAIRS) return hipSuccess;
     const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS, nst = (KT + MID_KB - 1) / MID_KB;
+    const int MT = n_mtiles <= 2 ? 2 : (n_mtiles <= 4 ? 4 : 8), zg = (n_mtiles + MT - 1) / MT;
     // one round of workgroups (one fits a compute unit), at least 4 stages per slice
-    int KS = 254 / groups;
+    int KS = 254 / (groups * zg);
     if (KS > nst / 4) KS = nst / 4;
     while (KS > 1 && (size_t)n_pairs * KS * n_mtiles > D.kpart_tiles) --KS;
     if (KS < 2) return hipSuccess;
     f32x4 *kpart = (f32x4 *)(c.ws + D.ws_kpart);
-    if (n_mtiles <= 2)
-        hipLaunchKernelGGL((k_mid<2>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
-    else if (n_mtiles <= 4)
-        hipLaunchKernelGGL((k_mid<4>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    if (MT == 2)
+        hipLaunchKernelGGL((k_mid<2>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    else if (MT == 4)
+        hipLaunchKernelGGL((k_mid<4>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
     else
-        hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+        hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
     SPD_TRY(hipGetLastError());
     hipLaunchKernelGGL((k_mid_finish<Epi>), dim3(groups, n_mtiles), dim3(MID_PAIRS * 64), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
     *done = true;
     return hipGetLastError();
 }
 
-constexpr int SKINNY_MAX_MTILES = 32;      // beyond 512 tokens the LDS-tiled GEMM re-reads the weights less often
 
 template <class Epi>
 hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
