@@ -1982,14 +1982,28 @@ hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, in
 }
 
 
+// Number of m-tiles up to which a projection with few n-tiles stays in the skinny kernel beyond
+// SKINNY_MAX_MTILES: the LDS-tiled GEMM of such a projection has far fewer tiles than there are compute
+// units and takes the time of one full tile whatever the call size, the skinny kernel's time grows with
+// the call.  Both estimates are fits to measurements on the 70B shard (QKV: 180 us in the GEMM from 768
+// to 8192 tokens, 43 us in the skinny kernel at 512).
+inline int skinny_limit(int n_pairs, int KT, int n_mtiles) {
+    const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
+    const int tiles = big < tall && tall <= 256 ? tall : big;
+    if (tiles >= 128) return SKINNY_MAX_MTILES;
+    const double t_gemm = (double)((tiles + 255) / 256) * (KT / 2) * 1.45 + 10.0;            // us
+    const double t_skinny = 7.7e-6 * n_pairs * KT * (16.0 * n_mtiles) + 5.0;
+    return t_skinny < t_gemm ? n_mtiles : SKINNY_MAX_MTILES;
+}
+
 template <class Epi>
 hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
-                       const Epi &epi) {
+                       const Epi &epi, int skinny_max = SKINNY_MAX_MTILES) {
     const int n_mtiles = (c.M + 15) / 16;
     const __bf16 *Xlo = Xhi + plane;
     if (n_mtiles == 1)
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
-    if (n_mtiles <= SKINNY_MAX_MTILES) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
+    if (n_mtiles <= skinny_max) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
     if (!split && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
     constexpr int MT = 4, W = 4;
     const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
@@ -2097,7 +2111,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
         if (spd_profile::enabled(SPD_STAGE_QKV)) {
             spd_profile::scope prof(SPD_STAGE_QKV, c.s);
-            SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1));
+            SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
+                                skinny_limit(D.nqkv / 32, D.h / 32, n_mtiles)));
         }
     }
 
