@@ -86,7 +86,8 @@ void compute_dims(const spd_config &c, spd_dims &D) {
         const int pairs = D.f_pad / 16;
         const int want = 256 * ((pairs + 255) / 256);
         const int c = (D.f_pad + want - 1) / want;
-        if (pairs >= 192 && want != pairs && c < 16) {
+        // (from 64 tile pairs on: below that the K-sliced launch of the 16-column tiles does as well)
+        if (pairs >= 64 && want != pairs && c < 16) {
             D.gud_cols = c;
             D.gud_groups = (D.f_pad + c - 1) / c;
             D.w_gud = o;

@@ -2261,7 +2261,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             if (!c.split) SPD_TRY(launch_mid(c, (const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, e1, &mid));
             if (mid) {
                 // done
-            } else if (D.gud_cols && M <= 16 * SKINNY_MAX_MTILES) {
+            } else if (D.gud_cols && D.f_pad / 16 >= 192 && M <= 16 * SKINNY_MAX_MTILES) {
                 e1.cols = D.gud_cols;
                 SPD_TRY(launch_skinny<0>(c, c.split, (const __bf16 *)(w + D.w_gud), xhat, D.pl_x, D.gud_groups, D.h / 32, 1,
                                          D.gud_cols, e1));
