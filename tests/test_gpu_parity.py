@@ -156,7 +156,7 @@ WIDE_MID = Workload(name="wide-ffn-mid", hidden=1184, n_q_heads=4, n_kv_heads=2,
     (3, 11, [3, 0, 20]),          # 33 tokens: three m-tiles with a ragged tail
     (1, 40, [8]),                 # one long chunk crossing several key blocks
     (2, 50, [0, 5]),              # 100 tokens: seven m-tiles, the last one ragged
-    (3, 50, [0, 5, 14]),          # 150 tokens: the LDS-tiled GEMM with a partly empty workgroup tile
+    (3, 50, [0, 5, 14]),          # 150 tokens: two groups of 8 m-tiles per projection, the second one partly empty
 ], ids=["decode", "chunk14", "chunk20", "chunk33", "chunk40", "chunk100", "chunk150"])
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 def test_bf16_small_all_ranks(gpu, w, batch, q_len, positions, flag):
