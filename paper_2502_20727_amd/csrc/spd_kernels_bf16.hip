@@ -1215,23 +1215,31 @@ __global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, 
 // wave owns 4 n-tiles x 8 m-tiles (128 accumulator registers).  One barrier per step.
 // ------------------------------------------------------------------------------------------
 // Tile shapes.  WN x WM waves, each TI n-tiles x TJ m-tiles; KPS k-tiles per step.
+// BLK: the tiles are numbered block by block, blocks of 4 (along N) x 8 (along M) tiles, and the blocks are
+// dealt to the 8 XCDs in turn (workgroup b runs on XCD b % 8), so that the 32 tiles an XCD has in flight use
+// 4 + 8 operand panels through its L2 instead of the 16-17 of a row-major numbering.
 struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per compute unit (128 KiB of LDS)
     static constexpr int WN = 4, WM = 2, TI = 4, TJ = 8, KPS = 2, MINB = 1;
+    static constexpr bool BLK = true;
 };
 struct GemmMid {      // 4 waves, 256 x 128, steps of 32: 48 KiB of LDS, two or three workgroups per compute unit
     static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2;
+    static constexpr bool BLK = false;
 };
 struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile (96 KiB of LDS: still one workgroup per compute unit)
     static constexpr int WN = 4, WM = 2, TI = 4, TJ = 4, KPS = 2, MINB = 1;
+    static constexpr bool BLK = true;
 };
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
     static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
+    static constexpr bool BLK = false;
 };
+constexpr int GEMM_BLK_N = 4, GEMM_BLK_M = 8, GEMM_BLK_TILES = GEMM_BLK_N * GEMM_BLK_M;
 
 template <class Epi, class G>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
-                                                                   int KT, int n_ntiles, int n_mtiles, int TN, int tile0, int msub,
-                                                                   Epi epi) {
+                                                                   int KT, int n_ntiles, int n_mtiles, int TN, int TM, int tile0,
+                                                                   int msub, Epi epi) {
     constexpr int GL_WN = G::WN, GL_WM = G::WM, GL_TI = G::TI, GL_TJ = G::TJ, KPS = G::KPS;
     constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // tiles per workgroup
     constexpr int GL_STAGE = (GL_BN + GL_BM) * KPS * 1024;
@@ -1240,10 +1248,30 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wn = wave % GL_WN, wm = wave / GL_WN;
-    // tiles are numbered along N first; a launch covers the tiles from `tile0` on, each cut into `msub`
-    // workgroup tiles along M (1, or 2 for the launch that finishes a ragged last round with half tiles)
-    const int tid = tile0 + (int)blockIdx.x / msub, sub = (int)blockIdx.x % msub;
-    const int tn = tid % TN, tm = tid / TN;
+    // A launch covers the tiles numbered from `tile0` on, each cut into `msub` workgroup tiles along M (1, or 2
+    // for the launch that finishes a ragged last round with half tiles; TN x TM counts the uncut tiles).
+    int tn, tm, sub = 0;
+    if constexpr (G::BLK) {
+        int t;
+        if (msub == 1) {
+            // workgroup b = 8 q + x: XCD x works through the blocks x, x + 8, ... (tile0 is a multiple of 8 blocks)
+            const int x = (int)blockIdx.x & 7, q = (int)blockIdx.x >> 3;
+            t = tile0 + ((q / GEMM_BLK_TILES) * 8 + x) * GEMM_BLK_TILES + q % GEMM_BLK_TILES;
+        } else {
+            t = tile0 + (int)blockIdx.x / msub;
+            sub = (int)blockIdx.x % msub;
+        }
+        const int nbn = (TN + GEMM_BLK_N - 1) / GEMM_BLK_N, blk = t / GEMM_BLK_TILES, j = t % GEMM_BLK_TILES;
+        tn = (blk % nbn) * GEMM_BLK_N + j % GEMM_BLK_N;
+        tm = (blk / nbn) * GEMM_BLK_M + j / GEMM_BLK_N;
+        if (tn >= TN || tm >= TM) return;        // a block that sticks out of the matrix (whole workgroup, before any barrier)
+    } else {
+        // numbered along N first
+        const int t = tile0 + (int)blockIdx.x / msub;
+        sub = (int)blockIdx.x % msub;
+        tn = t % TN;
+        tm = t / TN;
+    }
     const int nt0 = tn * GL_BN, mt0 = (tm * msub + sub) * GL_BM;
     f32x4 acc[GL_TI][GL_TJ];
 #pragma unroll
@@ -1362,9 +1390,16 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     }
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
     const int TN = (n_ntiles + BN - 1) / BN, TM = (n_mtiles + BM - 1) / BM;
-    if (n_wgs < 0) n_wgs = (TN * TM - tile0) * msub;
+    if (n_wgs < 0) {
+        if (G::BLK) {       // whole rounds of 8 blocks: workgroups of blocks past the last one exit at once
+            const int nblk = ((TN + GEMM_BLK_N - 1) / GEMM_BLK_N) * ((TM + GEMM_BLK_M - 1) / GEMM_BLK_M);
+            n_wgs = ((nblk + 7) / 8) * 8 * GEMM_BLK_TILES;
+        } else {
+            n_wgs = (TN * TM - tile0) * msub;
+        }
+    }
     hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
-                       n_mtiles, TN, tile0, msub, epi);
+                       n_mtiles, TN, TM, tile0, msub, epi);
     return hipGetLastError();
 }
 
@@ -1380,11 +1415,14 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
     if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall>(c, Wp, Xp, n_pairs, KT, epi);
     // a last round that would occupy at most half of the compute units runs as twice as many half tiles
     // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)
-    const int rem = big % 256;
-    if (big > 256 && rem > 0 && rem <= 128) {
-        const hipError_t e = launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi, 0, 1, big - rem);
+    // (counted in blocks of 32 tiles, the unit the tiles are numbered in: 8 blocks make a round)
+    const int nblk = (((2 * n_pairs + 15) / 16 + GEMM_BLK_N - 1) / GEMM_BLK_N) * (((n_mtiles + 15) / 16 + GEMM_BLK_M - 1) / GEMM_BLK_M);
+    const int remb = nblk % 8;
+    if (nblk > 8 && remb > 0 && remb <= 4) {
+        const int full = (nblk - remb) * GEMM_BLK_TILES;
+        const hipError_t e = launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi, 0, 1, full);
         if (e != hipSuccess) return e;
-        return launch_gemm_lds_cfg<GemmHalf>(c, Wp, Xp, n_pairs, KT, epi, big - rem, 2, 2 * rem);
+        return launch_gemm_lds_cfg<GemmHalf>(c, Wp, Xp, n_pairs, KT, epi, full, 2, 2 * remb * GEMM_BLK_TILES);
     }
     return launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi);
 }

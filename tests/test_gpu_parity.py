@@ -202,14 +202,15 @@ SMALL_H512 = Workload(name="small-bf16-h512", hidden=512, n_q_heads=8, n_kv_head
                       tp=4, dtype=BF16, seed=18, batch=3, q_len=1, ctx=64, mask=(1,))
 
 
-@pytest.mark.parametrize("w", [SMALL, SMALL_H512], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL, SMALL_H512, SMALL_MHA], ids=lambda w: w.name)
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 @pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
 def test_bf16_long_call_small_shape(gpu, w, flag, split):
     """More than 512 tokens in one call on a small shape, all ranks: the launch shapes of the long
     prefill (LDS-tiled GEMM, key-split attention, row-wise norm preparation) with a ragged last
     m-tile, every output element checked (hidden size 256 and 512: one and two pieces of 256 features per
-    workgroup of the row-wise preparation)."""
+    workgroup of the row-wise preparation; the 128-wide shape takes the 256 x 256 tiles with their block-wise
+    numbering, most of whose blocks stick out of so small a matrix)."""
     import torch
     batch, q_len, positions = 3, 181, [0, 0, 0]          # 543 tokens = 33 m-tiles + 15 rows
     M = batch * q_len
