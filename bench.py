@@ -33,7 +33,7 @@ MEASURED_TRAFFIC = {
     "llama2-70b-tp8-decode-b16-ctx4096": (59518 * 2 + 320) * 1024,        # 122.2 MB vs 117.9 MB algorithmic
     # the two launches of the stage (256x256 tiles + the half tiles of the last round): 1.59 GB, every XCD's L2
     # fetching the operand panels of its own tiles
-    "llama2-70b-tp8-prefill-b4x2048": ((614637 + 135301) * 2 + 49152 + 8192) * 1024,
+    "llama2-70b-tp8-prefill-b4x2048": ((614644 + 135299) * 2 + 49152 + 8192) * 1024,
     # k_mid + k_mid_finish: 206 MB (weights once, 29 MB of K-slice partials written and read back) vs 120.5 MB algorithmic
     "llama2-70b-tp8-prefill-b1x128": ((67432 + 16676) * 2 + 32256 + 896) * 1024,
 }
