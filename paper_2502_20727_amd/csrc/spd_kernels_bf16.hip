@@ -152,6 +152,12 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 // the HBM serves at a higher rate.  One workgroup per (NP chunks of 256 features, m-tile); wave w takes
 // tokens w, w+4, w+8, w+12.  The normalised bf16 values are turned into fragments through LDS.
 // Sums of squares: one partial per (chunk, token), as k_prep with 8 k-tiles per wave.
+// streaming 16-byte load (data that is read once)
+__device__ __forceinline__ float4 ldnt4(const float *p) {
+    const f32x4 v = __builtin_nontemporal_load((const f32x4 *)p);
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
@@ -191,7 +197,7 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
                 for (int j = 0; j < 8; ++j)
 #pragma unroll
                     for (int q = 0; q < NP; ++q)
-                        if (s0 + j < n_slots) p[t][q][j] = *(const float4 *)(slots + (size_t)(s0 + j) * slot_stride + off[t] + 256 * q);
+                        if (s0 + j < n_slots) p[t][q][j] = ldnt4(slots + (size_t)(s0 + j) * slot_stride + off[t] + 256 * q);
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
@@ -208,7 +214,7 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
-                for (int q = 0; q < NP; ++q) b[t][q] = *(const float4 *)(base + off[t] + 256 * q);
+                for (int q = 0; q < NP; ++q) b[t][q] = ldnt4(base + off[t] + 256 * q);
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
