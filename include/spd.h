@@ -287,6 +287,17 @@ int spd_profile_disable(void);
  * operation.  Process-wide; SPD_EINVAL for other values. */
 int spd_profile_only(int32_t stage);
 
+/* ---------------------------------------------------------------- launch order of the GEMM tiles (test aid)
+ * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
+ * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number
+ * tile0, spd_gemm_launch_size() is the number of workgroups launched and spd_gemm_tile_of() tells which tile
+ * workgroup b takes: 0 and (*tn, *tm), or 1 when b is a spare workgroup that takes none; SPD_EINVAL for
+ * arguments out of range or NULL pointers.  Host only; exists so that the order can be checked exhaustively
+ * without a GPU. */
+int spd_gemm_launch_size(int32_t n_tiles);
+int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, int32_t tile0, int32_t n_tiles, int32_t b,
+                     int32_t *tn, int32_t *tm);
+
 #ifdef __cplusplus
 }
 #endif

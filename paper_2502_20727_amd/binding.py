@@ -91,6 +91,8 @@ _PROTOS = {
     "spd_profile_read": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_profile_disable": (C.c_int, []),
     "spd_profile_only": (C.c_int, [C.c_int32]),
+    "spd_gemm_launch_size": (C.c_int, [C.c_int32]),
+    "spd_gemm_tile_of": (C.c_int, [C.c_int32] * 7 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
 }
 EXPORTS = tuple(_PROTOS)
 STAGES = {"prep": 0, "qkv": 1, "attn": 2, "o": 3, "gateup": 4, "down": 5}
@@ -338,6 +340,24 @@ def spd_profile_read():
 
 def spd_profile_only(stage: int) -> None:
     _check(lib().spd_profile_only(stage), "spd_profile_only")
+
+
+def spd_gemm_launch_size(n_tiles: int) -> int:
+    """Workgroups launched for `n_tiles` tiles of the GEMM's tile order."""
+    n = lib().spd_gemm_launch_size(n_tiles)
+    if n < 0:
+        _check(n, "spd_gemm_launch_size")
+    return n
+
+
+def spd_gemm_tile_of(TN: int, TM: int, rn: int, rm: int, tile0: int, n_tiles: int, b: int):
+    """(tn, tm) of the tile that workgroup `b` takes, or None for a spare workgroup."""
+    tn, tm = C.c_int32(), C.c_int32()
+    rc = lib().spd_gemm_tile_of(TN, TM, rn, rm, tile0, n_tiles, b, C.byref(tn), C.byref(tm))
+    if rc == 1:
+        return None
+    _check(rc, "spd_gemm_tile_of")
+    return tn.value, tm.value
 
 
 def spd_profile_disable() -> None:

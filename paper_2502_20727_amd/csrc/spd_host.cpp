@@ -514,3 +514,25 @@ int spd_kv_unpack(const spd_ctx *ctx, const void *cache_host, int32_t batch, int
 }
 
 }  // extern "C"
+
+extern "C" int spd_gemm_launch_size(int32_t n_tiles) {
+    if (n_tiles < 0) return SPD_EINVAL;
+    return spd_tile_launch_size(n_tiles);
+}
+
+extern "C" int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, int32_t tile0, int32_t n_tiles, int32_t b,
+                                int32_t *tn, int32_t *tm) {
+    if (!tn || !tm || TN <= 0 || TM <= 0 || rn <= 0 || rm <= 0 || tile0 < 0 || n_tiles < 0 || b < 0) return SPD_EINVAL;
+    if ((int64_t)tile0 + n_tiles > (int64_t)TN * TM || b >= spd_tile_launch_size(n_tiles)) return SPD_EINVAL;
+    spd_tile_order o;
+    o.TN = TN;
+    o.TM = TM;
+    spd_pick_block(TN, TM, rn, rm, o.bn, o.bm);
+    const int idx = spd_tile_deal(b, n_tiles);
+    if (idx < 0) return 1;
+    int a, m;
+    spd_tile_at(o, tile0 + idx, a, m);
+    *tn = a;
+    *tm = m;
+    return 0;
+}

@@ -69,6 +69,67 @@ SPD_HD size_t spd_vcache_off(int pos, int dcol, int d) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Order of the tiles of the LDS-tiled GEMM.  Every XCD has its own L2 and workgroup b of a launch
+// runs on XCD b % 8, so the tiles are put in an order in which neighbours share operand panels
+// (blocks of bn x bm tiles, block rows along N first, a block's tiles along N first; blocks at the
+// edges are narrower or shorter) and every XCD works on runs of 32 consecutive tiles of that
+// order: the tiles an XCD has in flight then form about one block and fetch bn + bm panels through
+// its L2 (256 x 256 tiles, blocks of 4 x 8: 12 panels instead of the 16-17 of a row-major numbering
+// with the workgroups dealt round-robin, which cost the gate/up launch of the 70B shard 2.16 instead
+// of 1.59 GB of fetches).
+// ------------------------------------------------------------------------------------------
+struct spd_tile_order {
+    int TN, TM, bn, bm;
+};
+// tile number idx of the order -> tile coordinates
+SPD_HD void spd_tile_at(const spd_tile_order &o, int idx, int &tn, int &tm) {
+    const int row_tiles = o.TN * o.bm, nbm = (o.TM + o.bm - 1) / o.bm, nbn = (o.TN + o.bn - 1) / o.bn;
+    int bj = idx / row_tiles;
+    bj = bj < nbm - 1 ? bj : nbm - 1;
+    const int rest = o.TM - bj * o.bm, hgt = o.bm < rest ? o.bm : rest;
+    const int r1 = idx - bj * row_tiles;
+    int bi = r1 / (o.bn * hgt);
+    bi = bi < nbn - 1 ? bi : nbn - 1;
+    const int restn = o.TN - bi * o.bn, w = o.bn < restn ? o.bn : restn;
+    const int r2 = r1 - bi * o.bn * hgt;
+    tn = bi * o.bn + r2 % w;
+    tm = bj * o.bm + r2 / w;
+}
+// Workgroup b = 8 q + x of a launch of n_tiles tiles runs on XCD x.  Whole rounds of 256 tiles: the XCDs
+// take the runs of 32 consecutive tiles in turn, so that the eight runs in flight are neighbours too (the
+// epilogues of a round then write whole rows of the output between them; handing each XCD a far-apart
+// eighth of the order cost the O projection 20 %).  The ragged rest: eight equal shares.  Returns the
+// tile's number in [0, n_tiles), or -1 for a spare workgroup of a ragged share.
+SPD_HD int spd_tile_deal(int b, int n_tiles) {
+    const int full = n_tiles & ~255;
+    if (b < full) {
+        const int x = b & 7, q = b >> 3;
+        return (((q >> 5) << 3) + x) * 32 + (q & 31);
+    }
+    const int x = (b - full) & 7, q = (b - full) >> 3, share = (n_tiles - full + 7) >> 3;
+    const int idx = full + x * share + q;
+    return (q >= share || idx >= n_tiles) ? -1 : idx;
+}
+SPD_HD int spd_tile_launch_size(int n_tiles) { return (n_tiles & ~255) + (((n_tiles & 255) + 7) / 8) * 8; }
+// block shape for tiles of rn x rm rows: at most 32 tiles, the fewest panel rows per tile in flight
+inline void spd_pick_block(int TN, int TM, int rn, int rm, int &bn, int &bm) {
+    static const int cand[][2] = {{4, 8}, {8, 4}, {5, 6}, {6, 5}, {3, 10}, {10, 3}, {2, 16}, {16, 2}, {1, 32}, {32, 1}};
+    double best = 1e30;
+    bn = 1;
+    bm = 1;
+    for (const auto &cd : cand) {
+        const int a = cd[0] < TN ? cd[0] : TN, b = cd[1] < TM ? cd[1] : TM;
+        // panel rows per tile; blocks of fewer than 32 tiles drift against the 32 tiles an XCD has in flight
+        const double cost = (double)(a * rn + b * rm) / (double)(a * b) * (32.0 / (double)(a * b));
+        if (cost < best) {
+            best = cost;
+            bn = a;
+            bm = b;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Derived dimensions of one rank's share, and byte offsets of everything the library lays out.
 // ------------------------------------------------------------------------------------------
 struct spd_dims {

@@ -1233,39 +1233,6 @@ struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
     static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
 };
-// Order of the tiles.  Every XCD has its own L2 and workgroup b of a launch runs on XCD b % 8, so the tiles
-// are put in an order in which neighbours share operand panels (blocks of bn x bm tiles, block rows along N
-// first, a block's tiles along N first; blocks at the edges are narrower or shorter) and every XCD works on
-// runs of 32 consecutive tiles of that order: the tiles an XCD has in flight then form about one block and fetch
-// bn + bm panels through its L2 (256 x 256 tiles, blocks of 4 x 8: 12 panels instead of the 16-17 of a row-major numbering
-// with the workgroups dealt round-robin, which cost the gate/up launch 2.16 instead of 1.59 GB of fetches).
-struct spd_tile_order {
-    int TN, TM, bn, bm;
-};
-__device__ __forceinline__ void tile_at(const spd_tile_order &o, int idx, int &tn, int &tm) {
-    const int row_tiles = o.TN * o.bm, nbm = (o.TM + o.bm - 1) / o.bm, nbn = (o.TN + o.bn - 1) / o.bn;
-    int bj = idx / row_tiles;
-    bj = bj < nbm - 1 ? bj : nbm - 1;
-    const int r1 = idx - bj * row_tiles, hgt = min(o.bm, o.TM - bj * o.bm);
-    int bi = r1 / (o.bn * hgt);
-    bi = bi < nbn - 1 ? bi : nbn - 1;
-    const int r2 = r1 - bi * o.bn * hgt, w = min(o.bn, o.TN - bi * o.bn);
-    tn = bi * o.bn + r2 % w;
-    tm = bj * o.bm + r2 / w;
-}
-// block shape for tiles of rn x rm rows: at most 32 tiles, the fewest panel rows per tile in flight
-inline void pick_block(int TN, int TM, int rn, int rm, int &bn, int &bm) {
-    static const int cand[][2] = {{4, 8}, {8, 4}, {5, 6}, {6, 5}, {3, 10}, {10, 3}, {2, 16}, {16, 2}, {1, 32}, {32, 1}};
-    double best = 1e30;
-    bn = 1; bm = 1;
-    for (const auto &cd : cand) {
-        const int a = cd[0] < TN ? cd[0] : TN, b = cd[1] < TM ? cd[1] : TM;
-        // panel rows per tile; blocks of fewer than 32 tiles drift against the 32 tiles an XCD has in flight
-        const double cost = (double)(a * rn + b * rm) / (double)(a * b) * (32.0 / (double)(a * b));
-        if (cost < best) { best = cost; bn = a; bm = b; }
-    }
-}
-
 template <class Epi, class G>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
                                                                    int KT, int n_ntiles, int n_mtiles, spd_tile_order ord, int tile0,
@@ -1284,24 +1251,13 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     {
         int idx;
         if (msub == 1) {
-            // workgroup b = 8 q + x runs on XCD x.  Whole rounds of 256 tiles: the XCDs take the groups of 32
-            // consecutive tiles in turn, so that the eight groups in flight are neighbours too (the epilogues
-            // of a round then write whole rows of the output between them; handing each XCD a far-apart
-            // eighth of the order cost the O projection 20 %).  The ragged rest: eight equal shares.
-            const int full = n_tiles & ~255, b = (int)blockIdx.x;
-            if (b < full) {
-                const int x = b & 7, q = b >> 3;
-                idx = (((q >> 5) << 3) + x) * 32 + (q & 31);
-            } else {
-                const int x = (b - full) & 7, q = (b - full) >> 3, share = (n_tiles - full + 7) >> 3;
-                idx = full + x * share + q;
-                if (q >= share || idx >= n_tiles) return;    // whole workgroup, before any barrier
-            }
+            idx = spd_tile_deal((int)blockIdx.x, n_tiles);
+            if (idx < 0) return;                 // spare workgroup of a ragged share (whole workgroup, before any barrier)
         } else {
             idx = (int)blockIdx.x / msub;
             sub = (int)blockIdx.x % msub;
         }
-        tile_at(ord, tile0 + idx, tn, tm);
+        spd_tile_at(ord, tile0 + idx, tn, tm);
     }
     const int nt0 = tn * GL_BN, mt0 = (tm * msub + sub) * GL_BM;
     f32x4 acc[GL_TI][GL_TJ];
@@ -1423,10 +1379,10 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     spd_tile_order ord;
     ord.TN = (n_ntiles + BN - 1) / BN;
     ord.TM = (n_mtiles + BM - 1) / BM;
-    pick_block(ord.TN, ord.TM, BN * 16, BM * 16, ord.bn, ord.bm);
+    spd_pick_block(ord.TN, ord.TM, BN * 16, BM * 16, ord.bn, ord.bm);
     if (n_tiles < 0) n_tiles = ord.TN * ord.TM - tile0;
     // msub = 1: whole rounds of 256, then eight equal shares (the spare workgroups of a ragged share exit at once)
-    const int n_wgs = msub == 1 ? (n_tiles & ~255) + (((n_tiles & 255) + 7) / 8) * 8 : n_tiles * msub;
+    const int n_wgs = msub == 1 ? spd_tile_launch_size(n_tiles) : n_tiles * msub;
     hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
                        n_mtiles, ord, tile0, n_tiles, msub, epi);
     return hipGetLastError();

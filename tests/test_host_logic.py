@@ -391,3 +391,62 @@ def test_inputs_are_counter_based():
     assert not (bits & 0xFFFF).any()                                   # bf16-representable
     x = inputs.normal((200000,), 1, inputs.T_MISC)
     assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.01
+
+
+# ------------------------------------------------------------------------------------------------
+# launch order of the GEMM tiles: every tile exactly once, for whole and ragged grids, for the launch
+# pair that finishes a ragged last round with half tiles, and runs of neighbours per XCD
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("TN,TM,rn,rm", [(28, 32, 256, 256), (32, 32, 256, 256), (1, 3, 256, 256), (5, 9, 256, 256),
+                                         (10, 22, 128, 384), (7, 33, 256, 256), (56, 3, 128, 384), (3, 2, 128, 384),
+                                         (40, 40, 256, 256), (1, 1, 256, 256), (9, 29, 256, 128)])
+def test_gemm_tile_order_covers_every_tile_once(TN, TM, rn, rm):
+    total = TN * TM
+    # the launch plan of the library: one launch, or whole rounds + a second launch over the rest (that one
+    # walks its tiles one after the other in the library; any dealing of the same set covers the same tiles)
+    rem = total % 256
+    plans = [[(0, total)]]
+    if total > 256 and 0 < rem <= 128:
+        plans.append([(0, total - rem), (total - rem, rem)])
+    for plan in plans:
+        seen = {}
+        for li, (tile0, n_tiles) in enumerate(plan):
+            n_wgs = B.spd_gemm_launch_size(n_tiles)
+            assert n_wgs % 8 == 0 and n_tiles <= n_wgs < n_tiles + 64
+            spare = 0
+            for b in range(n_wgs):
+                t = B.spd_gemm_tile_of(TN, TM, rn, rm, tile0, n_tiles, b)
+                if t is None:
+                    spare += 1
+                    continue
+                assert 0 <= t[0] < TN and 0 <= t[1] < TM
+                assert t not in seen, (t, b, seen[t])
+                seen[t] = (li, b)
+            assert spare == n_wgs - n_tiles
+        assert len(seen) == total
+
+
+def test_gemm_tile_order_keeps_an_xcd_on_neighbours():
+    """Gate/up of the 70B shard (28 x 32 tiles of 256 x 256): the 32 tiles an XCD has in flight in a round
+    form one block of 4 x 8, i.e. 12 operand panels, and the eight blocks of a round are consecutive."""
+    TN, TM, n = 28, 32, 768
+    for rnd in range(3):
+        blocks = []
+        for x in range(8):
+            tiles = [B.spd_gemm_tile_of(TN, TM, 256, 256, 0, n, rnd * 256 + 8 * q + x) for q in range(32)]
+            ns, ms = {t[0] for t in tiles}, {t[1] for t in tiles}
+            assert len(ns) == 4 and len(ms) == 8 and len(set(tiles)) == 32
+            blocks.append((min(ms) // 8, min(ns) // 4))
+        order = [bm * 7 + bn for bm, bn in blocks]
+        assert order == list(range(order[0], order[0] + 8))
+
+
+def test_gemm_tile_order_rejects():
+    assert B.lib().spd_gemm_launch_size(-1) == B.SPD_EINVAL
+    import ctypes as C
+    tn, tm = C.c_int32(), C.c_int32()
+    f = B.lib().spd_gemm_tile_of
+    assert f(4, 4, 256, 256, 0, 16, 16, C.byref(tn), C.byref(tm)) == B.SPD_EINVAL      # workgroup past the launch
+    assert f(4, 4, 256, 256, 8, 16, 0, C.byref(tn), C.byref(tm)) == B.SPD_EINVAL       # more tiles than the matrix has
+    assert f(0, 4, 256, 256, 0, 0, 0, C.byref(tn), C.byref(tm)) == B.SPD_EINVAL
+    assert f(4, 4, 256, 256, 0, 16, 0, None, C.byref(tm)) == B.SPD_EINVAL
