@@ -31,6 +31,23 @@ __device__ __forceinline__ bf16x4 cvt4_lo(float a, float b, float c, float d, bf
     return cvt4(a - (float)hi[0], b - (float)hi[1], c - (float)hi[2], d - (float)hi[3]);
 }
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
+// Sum / maximum over the four lanes l, l^16, l^32, l^48 (the lanes that share a token or an attention column),
+// left in all four.  gfx950's row swaps (v_permlane16_swap: the odd 16-lane rows of one operand against the even
+// rows of the other; v_permlane32_swap: the same for the halves) do it in the vector ALU; with both operands the
+// same register the two results hold "my row pair's even row" and "its odd row".  The additions are those of
+// x += shfl_xor(x, 16); x += shfl_xor(x, 32) in the same order (fp addition commutes), so the bits are the same.
+__device__ __forceinline__ float quad_sum(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float s = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+__device__ __forceinline__ float quad_max(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float s = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
 
 // sum of ss[c][m] over c = start, start + stride, ... < nch, in that order; the loads are issued
 // eight at a time so that their latencies overlap
@@ -1443,7 +1460,7 @@ __device__ __forceinline__ void load_kv(KVFrags<DT> &f, const __bf16 *__restrict
 
 // one 32-key block: keys [vb*32, vb*32+32) of one (sequence, KV head); n_keys_col = number of
 // keys column lane%16 may attend (causal), 0 for a padding column
-template <int DT>
+template <int DT, bool LAZY = false>      // LAZY: the running output is rescaled only when some column's maximum moved
 __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__restrict__ qf, const KVFrags<DT> &f, int vb,
                                            int n_keys_col, float scale, int lane) {
     // qf[0 .. DT/2) are the hi halves of the query fragments, qf[DT/2 .. DT) the lo halves
@@ -1464,8 +1481,7 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
         s1[i] = (key0 + 16 + i < n_keys_col) ? s1[i] * scale : -INFINITY;
         mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
     }
-    mx = fmaxf(mx, shfl_xor_f(mx, 16));
-    mx = fmaxf(mx, shfl_xor_f(mx, 32));
+    mx = quad_max(mx);
     const float m_new = fmaxf(st.m, mx);
     // every key of this block masked for this column and nothing seen before: keep the state
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -1477,8 +1493,7 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
         p1[i] = __expf(s1[i] - m_use);
         ps += p0[i] + p1[i];
     }
-    ps += shfl_xor_f(ps, 16);
-    ps += shfl_xor_f(ps, 32);
+    ps = quad_sum(ps);
     st.l = st.l * alpha + ps;
     st.m = m_new;
     bf16x8 pb, pl;      // probabilities as hi + lo pairs
@@ -1489,9 +1504,14 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
         pl[i] = (__bf16)(p0[i] - (float)pb[i]);
         pl[4 + i] = (__bf16)(p1[i] - (float)pb[4 + i]);
     }
+    // (a factor of exactly 1 changes nothing: skipping the multiplication when no column of the wave needs it
+    // gives the same bits; in a causal prefill the maxima settle after the first blocks)
+    if (!LAZY || __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) st.o[dt] *= alpha;
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-        st.o[dt] *= alpha;
         st.o[dt] = MFMA(f.v[dt], pb, st.o[dt]);
         st.o[dt] = MFMA(f.v[dt], pl, st.o[dt]);
     }
@@ -1805,7 +1825,7 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
         KVFrags<DT> f;
         load_kv<DT>(f, kbase, vbase, vb, d, lane);
 #pragma unroll
-        for (int c = 0; c < CT; ++c) attn_block<DT>(st[c], qf[c], f, vb, nk[c], scale, lane);
+        for (int c = 0; c < CT; ++c) attn_block<DT, true>(st[c], qf[c], f, vb, nk[c], scale, lane);
     }
     // partial states to LDS
 #pragma unroll
