@@ -108,28 +108,24 @@ def stage_time(torch, B, shard, w, mask, positions, x, slots, out, stage, reps):
     one pair of events.  Returns (launches, mean microseconds per launch of the stage).
     """
     stream = torch.cuda.current_stream()
-    B.spd_profile_only(B.STAGES[stage])
-    try:
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                B.spd_model_forward(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots,
-                                    out, shard.workspace)
-        stream.wait_stream(side)
-        torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            B.spd_model_forward_staged(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots,
+                                       out, shard.workspace, stage_mask=1 << B.STAGES[stage])
+    stream.wait_stream(side)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
         graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        per_launch_us = e0.elapsed_time(e1) * 1e3 / (reps * w.n_layers)
-    finally:
-        B.spd_profile_only(-1)
+    e1.record()
+    torch.cuda.synchronize()
+    per_launch_us = e0.elapsed_time(e1) * 1e3 / (reps * w.n_layers)
     return reps * w.n_layers, per_launch_us
 
 

@@ -129,8 +129,8 @@ typedef struct spd_taps {
  * counts or ffn, n_q_heads not a multiple of n_kv_heads, max_batch > SPD_MAX_BATCH,
  * max_ctx not a multiple of 32.  SPD_EUNSUPPORTED: n_kv_heads < tp_degree (a KV head
  * shared by several ranks); unknown dtype; for SPD_BF16: hidden or head_dim not a
- * multiple of 32, ffn / tp_degree not a multiple of 16, more than 16 query heads per
- * KV head.  act_split outside its three values, o_bias outside {0, 1}: SPD_EINVAL. */
+ * multiple of 32, head_dim above 128, ffn / tp_degree not a multiple of 16, more than 16
+ * query heads per KV head.  act_split outside its three values, o_bias outside {0, 1}: SPD_EINVAL. */
 int spd_create(const spd_config *cfg, spd_ctx **out);
 void spd_destroy(spd_ctx *ctx);
 int spd_get_config(const spd_ctx *ctx, spd_config *out);
@@ -183,7 +183,7 @@ int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *de
  * mlp_of_rank[r] (a permutation of 0 .. tp_degree-1; partition m = FFN columns [m*f, m*f+f)).
  * Either array may be NULL = identity; with both NULL this is spd_pack_shard().  How the
  * grouping and the matching are found (attention scores and MLP output norms on calibration
- * data, Eq. 1 and 2) is outside this library.  SPD_EINVAL if an array is not a permutation. */
+ * data, Eq. 2 and 3) is outside this library.  SPD_EINVAL if an array is not a permutation. */
 int spd_pack_shard_grouped(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, const int32_t *kv_heads,
                            const int32_t *mlp_of_rank, void *packed_host);
 /* Same, from matrices that already are one rank's slices. */
@@ -258,45 +258,6 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
                       const int32_t *positions, int32_t batch, int32_t q_len,
                       const float *x_in, float *slots, float *x_out, void *workspace,
                       void *stream, int64_t *n_rank_sums);
-
-/* ---------------------------------------------------------------- stage timing (benchmarks)
- * The stages of a block as the library launches them.  While timing is enabled for a
- * stage, every forward call brackets each launch of that stage with a pair of HIP events
- * on the call's stream (so the call must not be under stream capture).  The events are
- * process-wide state, created by spd_profile_enable(): not for concurrent use. */
-#define SPD_STAGE_PREP 0    /* rank-sum + first-norm elementwise work */
-#define SPD_STAGE_QKV 1     /* QKV projection + rotary + cache append */
-#define SPD_STAGE_ATTN 2    /* attention over the KV cache (all its kernels) */
-#define SPD_STAGE_O 3       /* O projection + residual fold */
-#define SPD_STAGE_GATEUP 4  /* gate/up projection + SwiGLU */
-#define SPD_STAGE_DOWN 5    /* down projection + partial-sum fold */
-#define SPD_N_STAGES 6
-
-/* Start timing `stage` with room for `max_records` launches (older records are kept until
- * spd_profile_disable()).  SPD_EINVAL for an unknown stage or max_records <= 0. */
-int spd_profile_enable(int32_t stage, int32_t max_records);
-/* Waits for the recorded events, then returns the number of launches timed and their mean
- * and minimum duration in microseconds (any pointer may be NULL).  Resets the record count. */
-int spd_profile_read(int32_t *n_records, double *mean_us, double *min_us);
-/* Stops timing and destroys the events. */
-int spd_profile_disable(void);
-/* Benchmark aid: while `stage` is selected (0 .. SPD_N_STAGES-1) forward calls launch ONLY the
- * kernels of that stage and skip everything else, so that a whole-model call becomes a train
- * of launches of one kernel over every layer's distinct weights (its inputs are whatever an
- * earlier full call left in the workspace; the outputs are meaningless).  -1 restores normal
- * operation.  Process-wide; SPD_EINVAL for other values. */
-int spd_profile_only(int32_t stage);
-
-/* ---------------------------------------------------------------- launch order of the GEMM tiles (test aid)
- * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
- * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number
- * tile0, spd_gemm_launch_size() is the number of workgroups launched and spd_gemm_tile_of() tells which tile
- * workgroup b takes: 0 and (*tn, *tm), or 1 when b is a spare workgroup that takes none; SPD_EINVAL for
- * arguments out of range or NULL pointers.  Host only; exists so that the order can be checked exhaustively
- * without a GPU. */
-int spd_gemm_launch_size(int32_t n_tiles);
-int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, int32_t tile0, int32_t n_tiles, int32_t b,
-                     int32_t *tn, int32_t *tm);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,70 @@
+/*
+ * spd_testing.h - test and benchmark aids of the SPD library.  Nothing here is part of the
+ * product boundary (spd.h); the symbols live in the same shared library so that benchmarks and
+ * tests can look inside a forward call without a second build.
+ *
+ * Nothing in this header keeps process-wide state: stage selection and timing are arguments of
+ * the call they apply to.
+ */
+#ifndef SPD_TESTING_H
+#define SPD_TESTING_H
+
+#include "spd.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---------------------------------------------------------------- stages of a block
+ * The stages of a decoder block as the library launches them (Sec. 3 / Sec. 4.1.1 name the
+ * operations; the cut into launches is the library's). */
+#define SPD_STAGE_PREP 0    /* rank-sum + first-norm elementwise work */
+#define SPD_STAGE_QKV 1     /* QKV projection + rotary + cache append */
+#define SPD_STAGE_ATTN 2    /* attention over the KV cache (all its kernels) */
+#define SPD_STAGE_O 3       /* O projection + residual fold */
+#define SPD_STAGE_GATEUP 4  /* gate/up projection + SwiGLU */
+#define SPD_STAGE_DOWN 5    /* down projection + partial-sum fold */
+#define SPD_N_STAGES 6
+#define SPD_ALL_STAGES ((1u << SPD_N_STAGES) - 1u)
+
+/* A timer for one stage: every launch of that stage inside a call it is handed to is bracketed by
+ * a pair of HIP events on the call's stream (so that call must not be under stream capture).
+ * Holds room for max_records launches; further launches go untimed.  One timer serves one call at
+ * a time.  SPD_EINVAL: unknown stage, max_records <= 0, NULL; SPD_EHIP: event creation failed. */
+typedef struct spd_stage_timer spd_stage_timer;
+int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out);
+/* Waits for the recorded events, returns the number of launches timed and their mean and minimum
+ * duration in microseconds (any pointer may be NULL), and resets the record count. */
+int spd_stage_timer_read(spd_stage_timer *timer, int32_t *n_records, double *mean_us, double *min_us);
+void spd_stage_timer_destroy(spd_stage_timer *timer);
+
+/* spd_model_forward() with two more arguments:
+ *   stage_mask  bit s set = the kernels of stage s are launched.  SPD_ALL_STAGES is the ordinary
+ *               call.  With a single bit a whole-model call becomes a train of launches of one
+ *               stage's kernel over every layer's distinct weights (its inputs are whatever an
+ *               earlier full call left in the workspace, its outputs are meaningless): the way to
+ *               time a kernel on its own without the whole layer fitting a cache.
+ *   timer       NULL, or a timer whose stage's launches are to be bracketed by events.
+ * SPD_EINVAL for bits beyond SPD_ALL_STAGES; otherwise as spd_model_forward(). */
+int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
+                             const void *const *layer_weights, void *const *layer_kv,
+                             const int32_t *positions, int32_t batch, int32_t q_len,
+                             const float *x_in, float *slots, float *x_out, void *workspace,
+                             void *stream, int64_t *n_rank_sums, uint32_t stage_mask,
+                             spd_stage_timer *timer);
+
+/* ---------------------------------------------------------------- launch order of the GEMM tiles
+ * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
+ * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number
+ * tile0, spd_gemm_launch_size() is the number of workgroups launched and spd_gemm_tile_of() tells which tile
+ * workgroup b takes: 0 and (*tn, *tm), or 1 when b is a spare workgroup that takes none; SPD_EINVAL for
+ * arguments out of range or NULL pointers.  Host only; exists so that the order can be checked exhaustively
+ * without a GPU. */
+int spd_gemm_launch_size(int32_t n_tiles);
+int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, int32_t tile0, int32_t n_tiles, int32_t b,
+                     int32_t *tn, int32_t *tm);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_TESTING_H */

@@ -1,4 +1,4 @@
-"""ctypes binding of the SPD C ABI (include/spd.h): same names, argument marshalling only.
+"""ctypes binding of the SPD C ABI (include/spd.h, include/spd_testing.h): same names, argument marshalling only.
 
 Every step of the decoder-block path runs inside the HIP library; this module turns NumPy
 arrays / torch tensors / Python ints into the pointers and sizes the C calls take and turns
@@ -87,15 +87,18 @@ _PROTOS = {
     "spd_model_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.POINTER(C.c_int64)]),
-    "spd_profile_enable": (C.c_int, [C.c_int32, C.c_int32]),
-    "spd_profile_read": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
-    "spd_profile_disable": (C.c_int, []),
-    "spd_profile_only": (C.c_int, [C.c_int32]),
+    "spd_model_forward_staged": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.POINTER(C.c_int64), C.c_uint32, C.c_void_p]),
+    "spd_stage_timer_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
+    "spd_stage_timer_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "spd_stage_timer_destroy": (None, [C.c_void_p]),
     "spd_gemm_launch_size": (C.c_int, [C.c_int32]),
     "spd_gemm_tile_of": (C.c_int, [C.c_int32] * 7 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
 }
 EXPORTS = tuple(_PROTOS)
 STAGES = {"prep": 0, "qkv": 1, "attn": 2, "o": 3, "gateup": 4, "down": 5}
+SPD_ALL_STAGES = (1 << len(STAGES)) - 1
 
 
 def lib():
@@ -327,19 +330,37 @@ def spd_model_forward(ctx: int, spd_mask: Sequence[int], rank: int, layer_weight
     return syncs.value
 
 
-def spd_profile_enable(stage: int, max_records: int) -> None:
-    _check(lib().spd_profile_enable(stage, max_records), "spd_profile_enable")
+def spd_model_forward_staged(ctx: int, spd_mask: Sequence[int], rank: int, layer_weights: Sequence, layer_kv: Sequence,
+                             positions: Sequence[int], batch: int, q_len: int, x_in, slots, x_out, workspace,
+                             stage_mask: int = SPD_ALL_STAGES, timer: Optional[int] = None, stream=None) -> int:
+    mask = np.ascontiguousarray(spd_mask, dtype=np.uint8)
+    n = len(layer_weights)
+    wp = (C.c_void_p * n)(*[_ptr(t) for t in layer_weights])
+    kp = (C.c_void_p * n)(*[_ptr(t) for t in layer_kv])
+    syncs = C.c_int64(0)
+    _check(lib().spd_model_forward_staged(ctx, mask.ctypes.data, rank, C.cast(wp, C.c_void_p), C.cast(kp, C.c_void_p),
+                                          C.cast(_i32(positions), C.c_void_p), batch, q_len, _ptr(x_in), _ptr(slots),
+                                          _ptr(x_out), _ptr(workspace), _stream_ptr(stream), C.byref(syncs),
+                                          int(stage_mask), timer),
+           "spd_model_forward_staged")
+    return syncs.value
 
 
-def spd_profile_read():
+def spd_stage_timer_create(stage: int, max_records: int) -> int:
+    out = C.c_void_p()
+    _check(lib().spd_stage_timer_create(stage, max_records, C.byref(out)), "spd_stage_timer_create")
+    return out.value
+
+
+def spd_stage_timer_read(timer: int):
     """(launches timed, mean microseconds, min microseconds) since the last read."""
     n, mean, mn = C.c_int32(), C.c_double(), C.c_double()
-    _check(lib().spd_profile_read(C.byref(n), C.byref(mean), C.byref(mn)), "spd_profile_read")
+    _check(lib().spd_stage_timer_read(timer, C.byref(n), C.byref(mean), C.byref(mn)), "spd_stage_timer_read")
     return n.value, mean.value, mn.value
 
 
-def spd_profile_only(stage: int) -> None:
-    _check(lib().spd_profile_only(stage), "spd_profile_only")
+def spd_stage_timer_destroy(timer: int) -> None:
+    lib().spd_stage_timer_destroy(timer)
 
 
 def spd_gemm_launch_size(n_tiles: int) -> int:
@@ -358,10 +379,6 @@ def spd_gemm_tile_of(TN: int, TM: int, rn: int, rm: int, tile0: int, n_tiles: in
         return None
     _check(rc, "spd_gemm_tile_of")
     return tn.value, tm.value
-
-
-def spd_profile_disable() -> None:
-    _check(lib().spd_profile_disable(), "spd_profile_disable")
 
 
 # --------------------------------------------------------------------------- device-memory plumbing

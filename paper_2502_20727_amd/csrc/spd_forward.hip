@@ -1,9 +1,9 @@
 // Device-facing entry points of the C ABI: argument checks on the host, then the sequence
 // of kernel launches that makes up one rank's share of a TP or SPD decoder block.
-#include <cstring>
-#include <vector>
-
 #include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
 
 #include "spd_internal.h"
 
@@ -43,6 +43,8 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->M = batch * q_len;
     c->ws = (char *)workspace;
     c->taps = nullptr;
+    c->stages = SPD_ALL_STAGES;
+    c->timer = nullptr;
     c->max_pos_end = 0;
     c->split_all = D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_ALWAYS;
     c->split = c->split_all || (D.dtype == SPD_BF16 && ctx->cfg.act_split == SPD_SPLIT_AUTO && c->M <= SPD_AUTO_SPLIT_TOKENS);
@@ -181,13 +183,17 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
     return SPD_OK;
 }
 
-int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
-                      void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
-                      float *slots, float *x_out, void *workspace, void *stream, int64_t *n_rank_sums) {
+int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
+                             void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len,
+                             const float *x_in, float *slots, float *x_out, void *workspace, void *stream,
+                             int64_t *n_rank_sums, uint32_t stage_mask, spd_stage_timer *timer) {
     spd_call c;
     const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, workspace, &c, stream);
     if (rc != SPD_OK) return rc;
     if (!spd_mask || !layer_weights || !layer_kv) return SPD_EINVAL;
+    if (stage_mask & ~SPD_ALL_STAGES) return SPD_EINVAL;
+    c.stages = stage_mask;
+    c.timer = timer;
     const spd_dims &D = ctx->D;
     const int L = ctx->cfg.n_layers;
     for (int l = 0; l < L; ++l) {
@@ -219,7 +225,7 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
         } else if (bf) {
             SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0, bias));
             c.nch1 = spd_bf16::prep_chunks(c);
-        } else if (spd_profile::enabled(SPD_STAGE_PREP)) {
+        } else if (c.on(SPD_STAGE_PREP)) {
             SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s, bias, D.h));
         }
         syncs += 1;
@@ -229,84 +235,64 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
     return SPD_OK;
 }
 
+int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
+                      void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
+                      float *slots, float *x_out, void *workspace, void *stream, int64_t *n_rank_sums) {
+    return spd_model_forward_staged(ctx, spd_mask, rank, layer_weights, layer_kv, positions, batch, q_len, x_in, slots, x_out,
+                                    workspace, stream, n_rank_sums, SPD_ALL_STAGES, nullptr);
+}
+
 const char *spd_last_hip_error(void) { return g_hip_msg; }
 
 }  // extern "C"
 
 // ------------------------------------------------------------------------------------------
-// stage timing
+// stage timers (spd_testing.h)
 // ------------------------------------------------------------------------------------------
-namespace {
-struct ProfileState {
-    int stage = -1;
-    int cap = 0, n = 0;
-    std::vector<hipEvent_t> start, stop;
-} g_prof;
-}  // namespace
-
-namespace {
-int g_only_stage = -1;
-}
-
-namespace spd_profile {
-bool enabled(int stage) { return g_only_stage < 0 || g_only_stage == stage; }
-void begin(int stage, hipStream_t s) {
-    if (stage != g_prof.stage || g_prof.n >= g_prof.cap) return;
-    (void)hipEventRecord(g_prof.start[g_prof.n], s);
-}
-void end(int stage, hipStream_t s) {
-    if (stage != g_prof.stage || g_prof.n >= g_prof.cap) return;
-    (void)hipEventRecord(g_prof.stop[g_prof.n], s);
-    ++g_prof.n;
-}
-}  // namespace spd_profile
-
 extern "C" {
 
-int spd_profile_only(int32_t stage) {
-    if (stage < -1 || stage >= SPD_N_STAGES) return SPD_EINVAL;
-    g_only_stage = stage;
-    return SPD_OK;
+void spd_stage_timer_destroy(spd_stage_timer *t) {
+    if (!t) return;
+    for (auto e : t->start) (void)hipEventDestroy(e);
+    for (auto e : t->stop) (void)hipEventDestroy(e);
+    delete t;
 }
 
-int spd_profile_disable(void) {
-    for (auto e : g_prof.start) (void)hipEventDestroy(e);
-    for (auto e : g_prof.stop) (void)hipEventDestroy(e);
-    g_prof.start.clear();
-    g_prof.stop.clear();
-    g_prof.stage = -1;
-    g_prof.cap = g_prof.n = 0;
-    return SPD_OK;
-}
-
-int spd_profile_enable(int32_t stage, int32_t max_records) {
-    if (stage < 0 || stage >= SPD_N_STAGES || max_records <= 0) return SPD_EINVAL;
-    spd_profile_disable();
-    g_prof.start.resize(max_records);
-    g_prof.stop.resize(max_records);
+int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out) {
+    if (!out || stage < 0 || stage >= SPD_N_STAGES || max_records <= 0) return SPD_EINVAL;
+    *out = nullptr;
+    spd_stage_timer *t = new (std::nothrow) spd_stage_timer();
+    if (!t) return SPD_EINVAL;
+    t->stage = stage;
     for (int i = 0; i < max_records; ++i) {
-        SPD_HIP(hipEventCreate(&g_prof.start[i]));
-        SPD_HIP(hipEventCreate(&g_prof.stop[i]));
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            if (a) (void)hipEventDestroy(a);
+            spd_stage_timer_destroy(t);
+            std::snprintf(g_hip_msg, sizeof(g_hip_msg), "hipEventCreate failed in spd_stage_timer_create");
+            return SPD_EHIP;
+        }
+        t->start.push_back(a);
+        t->stop.push_back(b);
     }
-    g_prof.cap = max_records;
-    g_prof.n = 0;
-    g_prof.stage = stage;
+    *out = t;
     return SPD_OK;
 }
 
-int spd_profile_read(int32_t *n_records, double *mean_us, double *min_us) {
+int spd_stage_timer_read(spd_stage_timer *t, int32_t *n_records, double *mean_us, double *min_us) {
+    if (!t) return SPD_EINVAL;
     double sum = 0.0, mn = 1e30;
-    for (int i = 0; i < g_prof.n; ++i) {
-        SPD_HIP(hipEventSynchronize(g_prof.stop[i]));
+    for (int i = 0; i < t->n; ++i) {
+        SPD_HIP(hipEventSynchronize(t->stop[i]));
         float ms = 0.f;
-        SPD_HIP(hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]));
+        SPD_HIP(hipEventElapsedTime(&ms, t->start[i], t->stop[i]));
         sum += (double)ms * 1000.0;
         if ((double)ms * 1000.0 < mn) mn = (double)ms * 1000.0;
     }
-    if (n_records) *n_records = g_prof.n;
-    if (mean_us) *mean_us = g_prof.n ? sum / g_prof.n : 0.0;
-    if (min_us) *min_us = g_prof.n ? mn : 0.0;
-    g_prof.n = 0;
+    if (n_records) *n_records = t->n;
+    if (mean_us) *mean_us = t->n ? sum / t->n : 0.0;
+    if (min_us) *min_us = t->n ? mn : 0.0;
+    t->n = 0;
     return SPD_OK;
 }
 

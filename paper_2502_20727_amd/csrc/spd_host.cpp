@@ -201,7 +201,7 @@ int spd_create(const spd_config *cfg, spd_ctx **out) {
     if (c.dtype == SPD_BF16) {
         if (c.hidden % 32 || c.head_dim % 32 || (c.ffn / c.tp_degree) % 16) return SPD_EUNSUPPORTED;
         if ((c.n_q_heads / c.n_kv_heads) > 16) return SPD_EUNSUPPORTED;
-        if (c.head_dim > 256) return SPD_EUNSUPPORTED;
+        if (c.head_dim > 128) return SPD_EUNSUPPORTED;        // the attention kernels exist for 32, 64, 96 and 128
     } else {
         if (c.head_dim > 256 || c.max_ctx > 8192) return SPD_EUNSUPPORTED;
     }

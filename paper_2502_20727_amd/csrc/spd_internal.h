@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "spd.h"
+#include "spd_testing.h"
 
 #define SPD_HD __host__ __device__ __forceinline__
 
@@ -165,6 +166,15 @@ struct spd_positions {
 
 inline size_t spd_align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Stage selection and timing of one call (test and benchmark aid, declared in spd_testing.h): a call
+// launches the stages whose bit is set in `stages`; with a timer, every launch of the timer's stage is
+// bracketed by a pair of events on the call's stream.  Both travel with the call, nothing is global.
+struct spd_stage_timer {
+    int stage = -1;
+    int n = 0;
+    std::vector<hipEvent_t> start, stop;
+};
+
 // ------------------------------------------------------------------------------------------
 // Launchers (defined next to their kernels).  All enqueue on `s` and return a hipError_t.
 // ------------------------------------------------------------------------------------------
@@ -179,20 +189,27 @@ struct spd_call {
     int nch1;                 // number of sum-of-squares partials per token waiting in ss1
     char *ws;                 // workspace
     const spd_taps *taps;
+    uint32_t stages;          // bit s set: the kernels of stage s are launched (all set in an ordinary call)
+    spd_stage_timer *timer;   // NULL, or the timer that brackets the launches of its stage
+    bool on(int stage) const { return (stages >> stage) & 1u; }
 };
-
-// stage timing: brackets a launch with events when spd_profile_enable() selected the stage
-namespace spd_profile {
-bool enabled(int stage);      // false while another stage is selected by spd_profile_only()
-void begin(int stage, hipStream_t s);
-void end(int stage, hipStream_t s);
-struct scope {
-    int stage;
-    hipStream_t s;
-    scope(int st, hipStream_t str) : stage(st), s(str) { begin(stage, s); }
-    ~scope() { end(stage, s); }
-};
+inline void spd_stage_begin(const spd_call &c, int stage) {
+    spd_stage_timer *t = c.timer;
+    if (t && t->stage == stage && t->n < (int)t->start.size()) (void)hipEventRecord(t->start[t->n], c.s);
 }
+inline void spd_stage_end(const spd_call &c, int stage) {
+    spd_stage_timer *t = c.timer;
+    if (t && t->stage == stage && t->n < (int)t->start.size()) {
+        (void)hipEventRecord(t->stop[t->n], c.s);
+        ++t->n;
+    }
+}
+struct spd_stage_scope {
+    const spd_call &c;
+    int stage;
+    spd_stage_scope(const spd_call &call, int st) : c(call), stage(st) { spd_stage_begin(c, stage); }
+    ~spd_stage_scope() { spd_stage_end(c, stage); }
+};
 
 namespace spd_common {
 // out = base + (slot_0 + ... ) [+ bias[i % h] when bias is given]

@@ -11,6 +11,8 @@
 // "Split" activations: an activation buffer may carry a second plane holding, for every
 // element, the bf16 rounding error of the first plane (x = hi + lo up to 2^-17 relative).
 // Contractions then run over both planes.
+#include <mutex>
+
 #include "spd_internal.h"
 
 namespace {
@@ -1386,12 +1388,13 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     // with msub = 2 the tiles are counted in the shape of twice G's height (GemmHalf finishing a GemmBig launch)
     constexpr int BN = G::WN * G::TI, STAGE = (BN + G::WM * G::TJ) * G::KPS * 1024;
     const int BM = G::WM * G::TJ * msub;
-    static bool attr_set = false;       // the attribute is per kernel instantiation; setting it twice is harmless
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // the attribute is per kernel instantiation: set once, whichever thread comes first
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
     spd_tile_order ord;
     ord.TN = (n_ntiles + BN - 1) / BN;
@@ -1963,13 +1966,13 @@ template <int MT, bool SPLIT, int MODE, class Epi>
 hipError_t launch_skinny_mt(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, const __bf16 *Xlo, int n_groups, int KT,
                             int KS, int n_mtiles, int rows, const Epi &epi) {
     constexpr int lds = SKINNY_W * MT * 2 * 1024;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_skinny<SKINNY_W, MT, SPLIT, MODE, Epi>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute((const void *)k_skinny<SKINNY_W, MT, SPLIT, MODE, Epi>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL((k_skinny<SKINNY_W, MT, SPLIT, MODE, Epi>), dim3(n_groups, KS, (n_mtiles + MT - 1) / MT), dim3(SKINNY_W * 64),
                        lds, c.s, Wp, Xhi, Xlo, KT, KS, n_mtiles, rows, epi);
     return hipGetLastError();
@@ -2071,8 +2074,8 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     __bf16 *xlo = (want_xhat && (which ? c.split : c.split_all)) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base && !bias) out = nullptr;   // nothing to rewrite
-    if (!spd_profile::enabled(SPD_STAGE_PREP)) return hipSuccess;
-    spd_profile::scope prof(SPD_STAGE_PREP, c.s);
+    if (!c.on(SPD_STAGE_PREP)) return hipSuccess;
+    spd_stage_scope prof(c, SPD_STAGE_PREP);
     // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
     if (tpw == 8 && D.h % 256 == 0)
         hipLaunchKernelGGL(k_prep_rows<1>, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
@@ -2127,8 +2130,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e1.ss = (const float *)(c.ws + D.ws_ss1);
         e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
         e1.part = qkvp; e1.P = c.pos;
-        if (spd_profile::enabled(SPD_STAGE_QKV)) {
-            spd_profile::scope prof(SPD_STAGE_QKV, c.s);
+        if (c.on(SPD_STAGE_QKV)) {
+            spd_stage_scope prof(c, SPD_STAGE_QKV);
             if (n_mtiles == 1) {
                 SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
                                            qkv_slices, e1));
@@ -2149,16 +2152,16 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e1.ss = (const float *)(c.ws + D.ws_ss1);
         e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
         e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
-        if (spd_profile::enabled(SPD_STAGE_QKV)) {
-            spd_profile::scope prof(SPD_STAGE_QKV, c.s);
+        if (c.on(SPD_STAGE_QKV)) {
+            spd_stage_scope prof(c, SPD_STAGE_QKV);
             SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
                                 skinny_limit(D.nqkv / 32, D.h / 32, n_mtiles)));
         }
     }
 
     const int DT = D.d / 16;
-    spd_profile::begin(SPD_STAGE_ATTN, c.s);
-    if (!spd_profile::enabled(SPD_STAGE_ATTN)) {
+    spd_stage_begin(c, SPD_STAGE_ATTN);
+    if (!c.on(SPD_STAGE_ATTN)) {
         // skipped
     } else if (c.q_len == 1) {
         // key blocks per workgroup (4 waves, so multiples of 4): the number of rounds the launch takes
@@ -2206,11 +2209,12 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
 #define SPD_PREFILL(DTV)                                                                                                   \
     {                                                                                                                      \
         constexpr int lds = 4 * CT * DTV * 64 * 16 + 4 * CT * 2 * 16 * 4;                                                  \
-        static bool attr_set = false;                                                                                      \
-        if (!attr_set) {                                                                                                   \
-            SPD_TRY(hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); \
-            attr_set = true;                                                                                               \
-        }                                                                                                                  \
+        static std::once_flag once;                                                                                        \
+        static hipError_t attr_err = hipSuccess;                                                                           \
+        std::call_once(once, [] {                                                                                          \
+            attr_err = hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
+        });                                                                                                                \
+        SPD_TRY(attr_err);                                                                                                 \
         hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
                            D.q, D.kv, D.max_ctx);                                                                          \
     }
@@ -2224,7 +2228,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
 #undef SPD_PREFILL
         SPD_TRY(hipGetLastError());
     }
-    spd_profile::end(SPD_STAGE_ATTN, c.s);
+    spd_stage_end(c, SPD_STAGE_ATTN);
 
     const bool fuse_mid = mid && !spd && M <= 16 * SKINNY_MAX_MTILES;
     if (mid_done) *mid_done = fuse_mid;
@@ -2236,8 +2240,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
         e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
     };
-    if (spd_profile::enabled(SPD_STAGE_O)) {
-        spd_profile::scope prof(SPD_STAGE_O, c.s);
+    if (c.on(SPD_STAGE_O)) {
+        spd_stage_scope prof(c, SPD_STAGE_O);
         const __bf16 *wo = (const __bf16 *)(w + D.w_o);
         if (fuse_mid) {
             // the weight-streaming kernels only
@@ -2288,8 +2292,8 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
     e1.nch = ss_per_pair ? D.h / 32 : prep_nch(D.h, M);
     e1.ss = (const float *)(c.ws + D.ws_ss2);
     e1.uhat = uhat; e1.ulo = ulo;
-    if (spd_profile::enabled(SPD_STAGE_GATEUP)) {
-        spd_profile::scope prof(SPD_STAGE_GATEUP, c.s);
+    if (c.on(SPD_STAGE_GATEUP)) {
+        spd_stage_scope prof(c, SPD_STAGE_GATEUP);
         if (D.gud_cols && M <= 16) {
             // decode: the copy with narrow column groups, one workgroup per group
             e1.cols = D.gud_cols;
@@ -2331,8 +2335,8 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             }
         }
     };
-    if (spd_profile::enabled(SPD_STAGE_DOWN)) {
-        spd_profile::scope prof(SPD_STAGE_DOWN, c.s);
+    if (c.on(SPD_STAGE_DOWN)) {
+        spd_stage_scope prof(c, SPD_STAGE_DOWN);
         if (do_fuse) {
             EpiDownT<true> e2;
             fill(e2);

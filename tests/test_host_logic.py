@@ -1,4 +1,4 @@
-"""CPU-only checks of the C-ABI library: it loads, exports what include/spd.h declares, rejects
+"""CPU-only checks of the C-ABI library: it loads, exports what include/*.h declare, rejects
 bad arguments before touching a device, indexes ranks and counts sync points bit-exactly,
 and its packers are lossless permutations.  No compute call is made here."""
 import ctypes as C
@@ -22,9 +22,15 @@ SMALL_F32 = workloads.Workload(name="small-f32", hidden=48, n_q_heads=6, n_kv_he
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "spd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spd_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(spd_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
