@@ -31,7 +31,8 @@
  *  - The caller owns every buffer.  Forward calls allocate nothing, free nothing and never
  *    synchronise; they only enqueue kernels on `stream` (a hipStream_t passed as void*,
  *    NULL = the default stream).  spd_workspace_init() is the only call that copies from
- *    host memory to the device.
+ *    host memory to the device (spd_block_forward_static() does the same copy by itself
+ *    when it has to, see there).
  *  - "device" pointers must be device memory of the current HIP device; "host" pointers
  *    are ordinary host memory.  Buffers must be 256-byte aligned.
  *  - Tokens of a call are ordered [batch][q_len]; token b*q_len + t sits at position
@@ -57,6 +58,7 @@ extern "C" {
 #define SPD_EINVAL (-1)       /* NULL pointer, bad shape, rank, batch, position or mask value */
 #define SPD_EUNSUPPORTED (-2) /* a valid request this build does not implement (see spd_create) */
 #define SPD_EHIP (-3)         /* a HIP call or kernel launch reported an error */
+#define SPD_ETOOBIG (-4)      /* spd_block_forward_static(): the configuration's workspace exceeds the static scratch */
 
 #define SPD_ALL_RANKS (-1)
 #define SPD_MAX_BATCH 64
@@ -204,9 +206,8 @@ int spd_kv_unpack(const spd_ctx *ctx, const void *cache_host, int32_t batch, int
 /* The KV cache must be zero-filled once before its first use (positions that were never
  * written are read as padding of the last key block and multiplied by a zero weight).
  *
- * Prepares a workspace (device, workspace_bytes): uploads the rotary table and clears the
- * library's counters.  Call once per workspace before the first forward; synchronises
- * the stream before returning. */
+ * Prepares a workspace (device, workspace_bytes): uploads the rotary table.  Call once per
+ * workspace before the first forward; synchronises the stream before returning. */
 int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream);
 
 /* out = base + (slot[0] + slot[1] + ... + slot[n_slots-1]): the partials are summed in
@@ -243,6 +244,27 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
                       const void *packed_weights, void *kv_cache, const int32_t *positions,
                       int32_t batch, int32_t q_len, const float *x_in, float *slots,
                       float *x_out, void *workspace, void *stream, const spd_taps *taps);
+
+/* spd_block_forward() for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results without `workspace`: the scratch the kernels need (partial tiles,
+ * packed activations, norm statistics, the rotary table) lives in a device array inside the
+ * library, SPD_STATIC_WORKSPACE_BYTES large, which every GPU the library runs on holds until the
+ * process ends.  The call allocates and frees nothing.
+ *  - SPD_ETOOBIG if spd_get_sizes(ctx).workspace_bytes exceeds SPD_STATIC_WORKSPACE_BYTES (64 MiB:
+ *    the LLaMA2 shards fit with max_tokens up to 128, long prefills do not); nothing is launched then.
+ *  - The first call on a device looks the array up; the first call with a context other than the
+ *    one that used the array last uploads that context's rotary table (a host-to-device copy and a
+ *    synchronisation of `stream`: make that call outside stream capture).  Later calls only
+ *    enqueue kernels.
+ *  - All calls on one GPU share the one array: calls that overlap in time on one GPU (two streams,
+ *    two threads) race.  Nothing else in the array needs to start at a known value, so a call may
+ *    follow one of any other size. */
+#define SPD_STATIC_WORKSPACE_BYTES (64u << 20)
+int spd_block_forward_static(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank,
+                             const void *packed_weights, void *kv_cache, const int32_t *positions,
+                             int32_t batch, int32_t q_len, const float *x_in, float *slots,
+                             float *x_out, void *stream, const spd_taps *taps);
 
 /* All blocks in order; block l is an SPD block iff spd_mask[l] == 1 (the per-layer outcome
  * of Alg. 1; every other value than 0 or 1 is SPD_EINVAL).

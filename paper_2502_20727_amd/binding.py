@@ -16,7 +16,8 @@ from . import build
 from .workloads import Workload
 
 SPD_F32, SPD_BF16 = 0, 1
-SPD_OK, SPD_EINVAL, SPD_EUNSUPPORTED, SPD_EHIP = 0, -1, -2, -3
+SPD_OK, SPD_EINVAL, SPD_EUNSUPPORTED, SPD_EHIP, SPD_ETOOBIG = 0, -1, -2, -3, -4
+SPD_STATIC_WORKSPACE_BYTES = 64 << 20
 SPD_ALL_RANKS = -1
 SPD_MAX_BATCH = 64
 
@@ -84,6 +85,9 @@ _PROTOS = {
     "spd_block_forward": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.POINTER(spd_taps)]),
+    "spd_block_forward_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.POINTER(spd_taps)]),
     "spd_model_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.POINTER(C.c_int64)]),
@@ -313,6 +317,18 @@ def spd_block_forward(ctx: int, layer: int, spd_flag: int, rank: int, packed_wei
                                    C.cast(_i32(positions), C.c_void_p), batch, q_len, _ptr(x_in), _ptr(slots),
                                    _ptr(x_out), _ptr(workspace), _stream_ptr(stream),
                                    C.byref(t) if t is not None else None), "spd_block_forward")
+
+
+def spd_block_forward_static(ctx: int, layer: int, spd_flag: int, rank: int, packed_weights, kv_cache,
+                             positions: Sequence[int], batch: int, q_len: int, x_in, slots, x_out,
+                             stream=None, taps: Optional[Dict[str, object]] = None) -> None:
+    t = None
+    if taps:
+        t = spd_taps(*[_ptr(taps.get(n)) for n in ("q", "attn", "y", "u")])
+    _check(lib().spd_block_forward_static(ctx, layer, spd_flag, rank, _ptr(packed_weights), _ptr(kv_cache),
+                                          C.cast(_i32(positions), C.c_void_p), batch, q_len, _ptr(x_in), _ptr(slots),
+                                          _ptr(x_out), _stream_ptr(stream), C.byref(t) if t is not None else None),
+           "spd_block_forward_static")
 
 
 def spd_model_forward(ctx: int, spd_mask: Sequence[int], rank: int, layer_weights: Sequence, layer_kv: Sequence,

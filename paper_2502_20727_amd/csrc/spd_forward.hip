@@ -2,6 +2,7 @@
 // of kernel launches that makes up one rank's share of a TP or SPD decoder block.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -127,36 +128,10 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
     return SPD_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream) {
-    if (!ctx || !workspace || (((uintptr_t)workspace) & 255)) return SPD_EINVAL;
-    clear_stale_hip_error();
-    const spd_dims &D = ctx->D;
-    hipStream_t s = (hipStream_t)stream;
-    char *ws = (char *)workspace;
-    SPD_HIP(hipMemcpyAsync(ws + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
-    SPD_HIP(hipMemcpyAsync(ws + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
-    SPD_HIP(spd_common::fill_zero_u32((uint32_t *)(ws + D.ws_counters), SPD_N_COUNTERS, s));
-    SPD_HIP(hipStreamSynchronize(s));
-    return SPD_OK;
-}
-
-int spd_rank_sum(const spd_ctx *ctx, const float *base, const float *slots, int32_t n_slots, int64_t n_elems,
-                 float *out, void *stream) {
-    if (!ctx || !out || n_slots < 0 || n_elems < 0) return SPD_EINVAL;
-    if (n_slots > 0 && !slots) return SPD_EINVAL;
-    if (n_elems == 0) return SPD_OK;
-    clear_stale_hip_error();
-    SPD_HIP(spd_common::rank_sum(base, slots, n_slots, n_elems, out, (hipStream_t)stream));
-    return SPD_OK;
-}
-
-int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank, const void *packed_weights,
-                      void *kv_cache, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
-                      float *slots, float *x_out, void *workspace, void *stream, const spd_taps *taps) {
+// spd_block_forward() and its variant without allocations differ only in where the workspace comes from
+int block_forward_impl(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank, const void *packed_weights,
+                       void *kv_cache, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
+                       float *slots, float *x_out, void *workspace, void *stream, const spd_taps *taps) {
     spd_call c;
     const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, workspace, &c, stream);
     if (rc != SPD_OK) return rc;
@@ -181,6 +156,39 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
     // the sync point that ends every block, SPD or not
     if (!end_done) SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s, bias, D.h));
     return SPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream) {
+    if (!ctx || !workspace || (((uintptr_t)workspace) & 255)) return SPD_EINVAL;
+    clear_stale_hip_error();
+    const spd_dims &D = ctx->D;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    SPD_HIP(hipMemcpyAsync(ws + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
+    SPD_HIP(hipMemcpyAsync(ws + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
+    SPD_HIP(hipStreamSynchronize(s));
+    return SPD_OK;
+}
+
+int spd_rank_sum(const spd_ctx *ctx, const float *base, const float *slots, int32_t n_slots, int64_t n_elems,
+                 float *out, void *stream) {
+    if (!ctx || !out || n_slots < 0 || n_elems < 0) return SPD_EINVAL;
+    if (n_slots > 0 && !slots) return SPD_EINVAL;
+    if (n_elems == 0) return SPD_OK;
+    clear_stale_hip_error();
+    SPD_HIP(spd_common::rank_sum(base, slots, n_slots, n_elems, out, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank, const void *packed_weights,
+                      void *kv_cache, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
+                      float *slots, float *x_out, void *workspace, void *stream, const spd_taps *taps) {
+    return block_forward_impl(ctx, layer, spd_flag, rank, packed_weights, kv_cache, positions, batch, q_len, x_in, slots,
+                              x_out, workspace, stream, taps);
 }
 
 int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
@@ -245,6 +253,68 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
 const char *spd_last_hip_error(void) { return g_hip_msg; }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// The entry point that allocates nothing: the workspace of spd_block_forward() lives in a
+// file-scope device array instead of caller memory.  Every GPU the library runs on holds its own
+// copy of the array at its own address, looked up once per device with hipGetSymbolAddress() (in
+// host code the array's name is only a stand-in for that address and is never handed to a kernel
+// or a copy).
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SPD_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+struct StaticScratch {
+    void *ptr = nullptr;          // device address of `scratch` on this device
+    uint64_t tables_of = 0;       // id of the context whose rotary table the array holds (0: none)
+};
+std::mutex g_static_mu;
+StaticScratch g_static[MAX_DEVICES];
+}  // namespace
+
+extern "C" int spd_block_forward_static(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32_t rank,
+                                        const void *packed_weights, void *kv_cache, const int32_t *positions,
+                                        int32_t batch, int32_t q_len, const float *x_in, float *slots, float *x_out,
+                                        void *stream, const spd_taps *taps) {
+    if (!ctx) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (D.workspace_bytes > (size_t)SPD_STATIC_WORKSPACE_BYTES) return SPD_ETOOBIG;     // before any device call
+    clear_stale_hip_error();
+    int dev = -1;
+    SPD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return SPD_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticScratch &st = g_static[dev];
+    if (!st.ptr) {
+        void *p = nullptr;
+        SPD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return SPD_EHIP;
+        st.ptr = p;
+    }
+    char *ws = (char *)st.ptr;
+    // every argument check of the ordinary entry point, before the array is touched
+    {
+        spd_call probe;
+        const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, ws, &probe, stream);
+        if (rc != SPD_OK) return rc;
+        if (!packed_weights || !kv_cache || (spd_flag != 0 && spd_flag != 1) || layer < 0 || layer >= ctx->cfg.n_layers)
+            return SPD_EINVAL;
+        if (probe.M == 0) return SPD_OK;
+    }
+    // The array keeps what the last call left.  The only part a forward call reads without having written it
+    // is the rotary table, which belongs to a context: upload it when another context used the array last.
+    if (st.tables_of != ctx->id) {
+        hipStream_t s = (hipStream_t)stream;
+        st.tables_of = 0;
+        SPD_HIP(hipMemcpyAsync(ws + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
+        SPD_HIP(hipMemcpyAsync(ws + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
+        SPD_HIP(hipStreamSynchronize(s));       // the host table may go away with its context
+        st.tables_of = ctx->id;
+    }
+    return block_forward_impl(ctx, layer, spd_flag, rank, packed_weights, kv_cache, positions, batch, q_len, x_in, slots,
+                              x_out, ws, stream, taps);
+}
 
 // ------------------------------------------------------------------------------------------
 // stage timers (spd_testing.h)

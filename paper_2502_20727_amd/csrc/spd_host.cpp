@@ -1,8 +1,9 @@
 // Host side of the SPD library: configuration checks, rank indexing, the sync-point count,
 // and the packers that lay one rank's shard and KV cache out the way the kernels read them.
 // Nothing in this file touches a device.
-#include <cmath>
 #include <algorithm>
+#include <atomic>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -104,7 +105,6 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     o = 0;
     D.ws_cos = o; o = spd_align256(o + (size_t)D.max_ctx * (D.d / 2) * 4);
     D.ws_sin = o; o = spd_align256(o + (size_t)D.max_ctx * (D.d / 2) * 4);
-    D.ws_counters = o; o = spd_align256(o + (size_t)SPD_N_COUNTERS * 4);
     D.ws_y = o; o = spd_align256(o + M * h * 4);
     D.ws_r = o; o = spd_align256(o + M * h * 4);
     if (bf) {
@@ -176,6 +176,7 @@ const char *spd_strerror(int code) {
         case SPD_EINVAL: return "invalid argument";
         case SPD_EUNSUPPORTED: return "unsupported configuration";
         case SPD_EHIP: return "HIP runtime error";
+        case SPD_ETOOBIG: return "configuration needs more workspace than the static scratch of spd_block_forward_static holds";
         default: return "unknown error code";
     }
 }
@@ -207,6 +208,8 @@ int spd_create(const spd_config *cfg, spd_ctx **out) {
     }
     spd_ctx *ctx = new (std::nothrow) spd_ctx();
     if (!ctx) return SPD_EINVAL;
+    static std::atomic<uint64_t> next_id{1};
+    ctx->id = next_id.fetch_add(1);
     ctx->cfg = c;
     compute_dims(c, ctx->D);
     const int half = c.head_dim / 2;

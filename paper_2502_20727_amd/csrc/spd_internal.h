@@ -30,7 +30,6 @@
 
 constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
-constexpr int SPD_N_COUNTERS = 8192;
 constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of at most this many tokens carry the MLP inputs as hi + lo pairs
 constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
@@ -146,7 +145,7 @@ struct spd_dims {
     // KV cache (bytes)
     size_t kv_v, kv_bytes;
     // workspace (bytes)
-    size_t ws_cos, ws_sin, ws_counters, ws_xhat, ws_xhat2, ws_q, ws_ahat, ws_y, ws_r, ws_ss1, ws_ss2, ws_uhat,
+    size_t ws_cos, ws_sin, ws_xhat, ws_xhat2, ws_q, ws_ahat, ws_y, ws_r, ws_ss1, ws_ss2, ws_uhat,
         ws_apart, ws_kpart, ws_qkv, ws_gu, workspace_bytes;
     // bf16 path: every packed activation buffer has a second plane (the "lo" halves) this many
     // elements after the first
@@ -155,6 +154,7 @@ struct spd_dims {
 };
 
 struct spd_ctx {
+    uint64_t id;                             // unique per spd_create() in this process, never 0
     spd_config cfg;
     spd_dims D;
     std::vector<float> rope_cos, rope_sin;   // [max_ctx][d/2], built in double on the host

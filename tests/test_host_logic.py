@@ -42,6 +42,18 @@ def test_library_exports_every_declared_symbol():
     assert sorted(B.EXPORTS) == names          # the binding covers the header, nothing more, nothing less
 
 
+def test_static_entry_point_refuses_a_workspace_that_does_not_fit():
+    """The size check of the entry point without allocations comes before any device call."""
+    ctx = B.spd_create(B.make_config(workloads.LLAMA70B_PREFILL.with_layers(1)))
+    assert B.spd_get_sizes(ctx).workspace_bytes > B.SPD_STATIC_WORKSPACE_BYTES
+    buf = np.zeros(64, np.float32)
+    with pytest.raises(B.SpdError) as e:
+        B.spd_block_forward_static(ctx, 0, 1, 0, buf, buf, [0], 1, 1, buf, buf, buf, stream=0)
+    assert e.value.code == B.SPD_ETOOBIG
+    assert "static" in B.strerror(B.SPD_ETOOBIG)
+    B.spd_destroy(ctx)
+
+
 def test_strerror():
     assert B.strerror(0) == "ok"
     for code in (B.SPD_EINVAL, B.SPD_EUNSUPPORTED, B.SPD_EHIP, -99):
