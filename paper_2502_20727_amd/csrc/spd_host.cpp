@@ -28,6 +28,44 @@ inline float from_bf16(uint16_t b) {
     return v;
 }
 
+// fp32 -> IEEE binary16 bit pattern, round to nearest even (subnormals kept, overflow to infinity)
+inline uint16_t to_f16(float v) {
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    const uint32_t sign = (u >> 16) & 0x8000u;
+    u &= 0x7FFFFFFFu;
+    if (u >= 0x7F800000u) return (uint16_t)(sign | (u > 0x7F800000u ? 0x7E00u : 0x7C00u));   // NaN / infinity
+    if (u >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);                                   // rounds to >= 65520: infinity
+    if (u < 0x38800000u) {                            // below 2^-14: a multiple of 2^-24
+        if (u < 0x33000000u) return (uint16_t)sign;   // below 2^-25: zero (2^-25 itself ties to even = 0)
+        const int e = (int)(u >> 23);                 // biased exponent, 102 .. 112
+        const uint32_t m = (u & 0x7FFFFFu) | 0x800000u;
+        const int shift = 126 - e;                    // 14 .. 24: value = m * 2^(e-150), unit 2^-24
+        const uint32_t q = m >> shift, rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+        return (uint16_t)(sign | (q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u)));
+    }
+    const uint32_t q = (u - 0x38000000u) >> 13, rem = u & 0x1FFFu;      // rebias 127 -> 15, drop 13 mantissa bits
+    return (uint16_t)(sign | (q + ((rem > 0x1000u || (rem == 0x1000u && (q & 1u))) ? 1u : 0u)));
+}
+inline float from_f16(uint16_t b) {
+    const uint32_t sign = (uint32_t)(b & 0x8000u) << 16, e = (b >> 10) & 0x1Fu, m = b & 0x3FFu;
+    float v;
+    if (e == 0) {
+        v = std::ldexp((float)m, -24);
+    } else if (e == 31) {
+        const uint32_t u = 0x7F800000u | (m << 13);
+        std::memcpy(&v, &u, 4);
+    } else {
+        const uint32_t u = ((e + 112u) << 23) | (m << 13);
+        std::memcpy(&v, &u, 4);
+    }
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    u |= sign;
+    std::memcpy(&v, &u, 4);
+    return v;
+}
+
 template <class F>
 void parallel_for(int n, F f) {
     int nt = (int)std::thread::hardware_concurrency();
@@ -95,6 +133,16 @@ void compute_dims(const spd_config &c, spd_dims &D) {
             o = spd_align256(o + (size_t)D.gud_groups * (h / 32) * 2 * 64 * c);
         }
     }
+    // Calls of more than 16 tokens contract fp16 operands: a second copy of the four matrices, in the same
+    // fragment order, holds round_fp16(2^k w) with one k per matrix and layer, next to the four factors 2^-k
+    if (bf && c.max_tokens > SPD_AUTO_SPLIT_TOKENS) {
+        D.has16 = 1;
+        D.w16_scale = o; o = spd_align256(o + 4 * 4);
+        D.w16_qkv = o; o = spd_align256(o + h * (size_t)D.nqkv * 2);
+        D.w16_o = o; o = spd_align256(o + qd * h * 2);
+        D.w16_g = o; o = spd_align256(o + 2 * h * f * 2);
+        D.w16_d = o; o = spd_align256(o + f * h * 2);
+    }
     D.weight_bytes = o;
 
     const size_t kvn = (size_t)D.max_batch * D.kv * D.max_ctx * D.d;
@@ -147,6 +195,30 @@ bool pack_frags(uint16_t *dst, int n_tiles, int k_tiles, Src src) {
     for (int b : bad)
         if (b) return false;
     return true;
+}
+
+// The fp16 copy of a packed bf16 matrix, fragment by fragment (same order): element = round_fp16(2^k w).
+// k is the largest power of two that keeps the matrix's largest magnitude at or below 2^15 (half of fp16's
+// range), which puts bf16's 8 significant bits of every weight down to 2^-29 of that largest magnitude inside
+// fp16's 11; smaller weights land on fp16's subnormal grid (error at most 2^-25 / 2^k).  Returns 2^-k.
+float pack_f16_copy(uint16_t *dst, const uint16_t *src_bf16, size_t n_elems) {
+    float mx = 0.f;
+    for (size_t i = 0; i < n_elems; ++i) mx = std::max(mx, std::fabs(from_bf16(src_bf16[i])));
+    int k = 0;
+    if (mx > 0.f && std::isfinite(mx)) {
+        int e;
+        std::frexp(mx, &e);                       // mx = m 2^e, m in [0.5, 1)
+        k = 15 - e;                               // mx 2^k < 2^15
+        if (k > 60) k = 60;
+        if (k < -60) k = -60;
+    }
+    const float up = std::ldexp(1.0f, k);
+    const int chunks = (int)((n_elems + 65535) / 65536);
+    parallel_for(chunks, [&](int ch) {
+        const size_t a = (size_t)ch * 65536, b = std::min(n_elems, a + 65536);
+        for (size_t i = a; i < b; ++i) dst[i] = to_f16(from_bf16(src_bf16[i]) * up);
+    });
+    return std::ldexp(1.0f, -k);
 }
 
 template <class Dst>
@@ -356,7 +428,15 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
     ok &= pack_frags((uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r) {
         return k < f ? w->wd[(size_t)k * w->ld_d + nt * 16 + r] : 0.0f;
     });
-    return ok ? SPD_OK : SPD_EINVAL;   // a weight that is not a bf16 value
+    if (!ok) return SPD_EINVAL;        // a weight that is not a bf16 value
+    if (D.has16) {
+        float *sc = (float *)(base + D.w16_scale);
+        sc[0] = pack_f16_copy((uint16_t *)(base + D.w16_qkv), (const uint16_t *)(base + D.w_qkv), (size_t)h * D.nqkv);
+        sc[1] = pack_f16_copy((uint16_t *)(base + D.w16_o), (const uint16_t *)(base + D.w_o), (size_t)qd * h);
+        sc[2] = pack_f16_copy((uint16_t *)(base + D.w16_g), (const uint16_t *)(base + D.w_g), (size_t)2 * h * D.f_pad);
+        sc[3] = pack_f16_copy((uint16_t *)(base + D.w16_d), (const uint16_t *)(base + D.w_d), (size_t)D.f_pad * h);
+    }
+    return SPD_OK;
 }
 
 static bool is_permutation(const int32_t *p, int n) {
@@ -538,4 +618,34 @@ extern "C" int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, 
     *tn = a;
     *tm = m;
     return 0;
+}
+
+// spd_testing.h: how far the fp16 copy of a packed shard is from its bf16 weights
+extern "C" int spd_f16_copy_check(const spd_ctx *ctx, const void *packed_host, double *max_abs_diff, double *max_abs_weight,
+                                  int64_t *n_inexact, int64_t *n_weights) {
+    if (!ctx || !packed_host) return SPD_EINVAL;
+    const spd_dims &D = ctx->D;
+    if (!D.has16) return SPD_EUNSUPPORTED;
+    const char *base = (const char *)packed_host;
+    const float *sc = (const float *)(base + D.w16_scale);
+    const size_t off_b[4] = {D.w_qkv, D.w_o, D.w_g, D.w_d}, off_h[4] = {D.w16_qkv, D.w16_o, D.w16_g, D.w16_d};
+    const size_t n[4] = {(size_t)D.h * D.nqkv, (size_t)D.q * D.d * D.h, (size_t)2 * D.h * D.f_pad, (size_t)D.f_pad * D.h};
+    double worst = 0.0, big = 0.0;
+    int64_t inexact = 0, total = 0;
+    for (int m = 0; m < 4; ++m) {
+        const uint16_t *b = (const uint16_t *)(base + off_b[m]), *hh = (const uint16_t *)(base + off_h[m]);
+        for (size_t i = 0; i < n[m]; ++i) {
+            const double w = (double)from_bf16(b[i]), w16 = (double)from_f16(hh[i]) * (double)sc[m];
+            const double diff = std::fabs(w - w16);
+            if (diff > 0.0) ++inexact;
+            if (diff > worst) worst = diff;
+            if (std::fabs(w) > big) big = std::fabs(w);
+        }
+        total += (int64_t)n[m];
+    }
+    if (max_abs_diff) *max_abs_diff = worst;
+    if (max_abs_weight) *max_abs_weight = big;
+    if (n_inexact) *n_inexact = inexact;
+    if (n_weights) *n_weights = total;
+    return SPD_OK;
 }

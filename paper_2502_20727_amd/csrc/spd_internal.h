@@ -142,6 +142,10 @@ struct spd_dims {
     float eps, rope_base;
     // packed shard (bytes from its start)
     size_t w_g1, w_g2, w_qkv, w_o, w_g, w_u, w_d, weight_bytes;   // w_u: f32 path only (bf16: gate/up interleaved at w_g)
+    // bf16 path with calls of more than 16 tokens: the fp16 copy of the four matrices (same fragment order; element
+    // = round_fp16(2^k w), one k per matrix) and the four factors 2^-k (fp32) that undo it
+    int has16;
+    size_t w16_scale, w16_qkv, w16_o, w16_g, w16_d;
     // KV cache (bytes)
     size_t kv_v, kv_bytes;
     // workspace (bytes)
@@ -184,8 +188,11 @@ struct spd_call {
     int batch, q_len, M;
     spd_positions pos;
     int max_pos_end;          // max over sequences of positions[b] + q_len
-    bool split;               // bf16 path: the MLP's input activations are carried as hi + lo pairs
-    bool split_all;           // ... and so are the attention half's (only when the configuration asks for it)
+    // bf16 path: operand format of the projections and which of their inputs are carried as hi + lo pairs
+    bool f16;                 // a call of more than 16 tokens: fp16 activations against the fp16 copy of the weights
+    bool sp_x;                // first norm's output (input of the QKV projection)
+    bool sp_a;                // attention output (input of the O projection)
+    bool sp_m;                // second norm's output and SwiGLU output (inputs of the MLP's projections)
     int nch1;                 // number of sum-of-squares partials per token waiting in ss1
     char *ws;                 // workspace
     const spd_taps *taps;

@@ -9,8 +9,16 @@
 // straight into the next kernel's fragment layout.
 //
 // "Split" activations: an activation buffer may carry a second plane holding, for every
-// element, the bf16 rounding error of the first plane (x = hi + lo up to 2^-17 relative).
+// element, the rounding error of the first plane (x = hi + lo up to 2^-17 relative).
 // Contractions then run over both planes.
+//
+// Two operand formats.  Calls of at most 16 tokens (the weight-streaming kernel k_gemv) and the
+// attention kernels contract bf16 operands.  Calls of more than 16 tokens contract fp16 operands
+// (v_mfma_f32_16x16x32_f16, same register layout, same rate): their activations are rounded to
+// fp16's 11 significant bits instead of bf16's 8, and their weights come from a second copy of the
+// shard that holds round_fp16(2^k w) with one power of two per matrix, undone in the epilogue
+// (`wsc`).  The fragments of both formats are 16-bit elements in the same order, so everything
+// that only moves data is shared and typed as bf16.
 #include <mutex>
 
 #include "spd_internal.h"
@@ -20,8 +28,37 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16((a), (b), (c), 0, 0, 0)
+// fp16 operands held in registers typed as bf16 (raw 16-bit elements)
+#define MFMA16(a, b, c) \
+    __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, (a)), __builtin_bit_cast(f16x8, (b)), (c), 0, 0, 0)
+
+// Activation element of either format as raw 16 bits typed __bf16.  H: fp16, else bf16.
+template <bool H>
+struct Act {
+    static __device__ __forceinline__ __bf16 one(float v) {
+        if constexpr (H) return __builtin_bit_cast(__bf16, (_Float16)v);
+        else return (__bf16)v;
+    }
+    static __device__ __forceinline__ float back(__bf16 r) {
+        if constexpr (H) return (float)__builtin_bit_cast(_Float16, r);
+        else return (float)r;
+    }
+};
+template <bool H>
+__device__ __forceinline__ bf16x4 cvt4t(float a, float b, float c, float d) {
+    bf16x4 r;
+    r[0] = Act<H>::one(a); r[1] = Act<H>::one(b); r[2] = Act<H>::one(c); r[3] = Act<H>::one(d);
+    return r;
+}
+// rounding error of cvt4t, itself rounded to the same format
+template <bool H>
+__device__ __forceinline__ bf16x4 cvt4t_lo(float a, float b, float c, float d, bf16x4 hi) {
+    return cvt4t<H>(a - Act<H>::back(hi[0]), b - Act<H>::back(hi[1]), c - Act<H>::back(hi[2]), d - Act<H>::back(hi[3]));
+}
 
 __device__ __forceinline__ bf16x4 cvt4(float a, float b, float c, float d) {
     bf16x4 r;
@@ -80,6 +117,7 @@ __device__ __forceinline__ float row_rsqrt(const float *__restrict__ ss, int nch
 // lo plane), and the partial sums of squares of `out` per (k-chunk, token).  One wave per
 // (m-tile, chunk of `tpw` k-tiles); lane l handles token l%16 and 8 consecutive features.
 // ------------------------------------------------------------------------------------------
+template <bool H>      // H: the normalised activations are written as fp16 (calls of more than 16 tokens)
 __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, const float *__restrict__ slots,
                                               int n_slots, size_t slot_stride, float *__restrict__ out,
                                               const float *__restrict__ gain, __bf16 *__restrict__ xhat,
@@ -151,8 +189,8 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float p = v[i] * gg[i];
-                    x[i] = (__bf16)p;
-                    xl[i] = (__bf16)(p - (float)x[i]);
+                    x[i] = Act<H>::one(p);
+                    xl[i] = Act<H>::one(p - Act<H>::back(x[i]));
                 }
             }
             const size_t fo = spd_frag_index(mt, kt, KT) + lane * 8;
@@ -177,7 +215,7 @@ __device__ __forceinline__ float4 ldnt4(const float *p) {
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
-template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
+template <int NP, bool H>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
                                                    const float *__restrict__ gain, __bf16 *__restrict__ xhat,
@@ -257,9 +295,9 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
                 if (ss && lane == 0) ss[(size_t)(chunk0 + q) * m_pad + mt * 16 + r] = sq;
                 if (xhat) {
                     const float q0 = u.x * gn[q].x, q1 = u.y * gn[q].y, q2 = u.z * gn[q].z, q3 = u.w * gn[q].w;
-                    const bf16x4 hi = cvt4(q0, q1, q2, q3);
+                    const bf16x4 hi = cvt4t<H>(q0, q1, q2, q3);
                     *(bf16x4 *)&tile[0][r][256 * q + lane * 4] = hi;
-                    if (xlo) *(bf16x4 *)&tile[1][r][256 * q + lane * 4] = cvt4_lo(q0, q1, q2, q3, hi);
+                    if (xlo) *(bf16x4 *)&tile[1][r][256 * q + lane * 4] = cvt4t_lo<H>(q0, q1, q2, q3, hi);
                 }
             }
         }
@@ -325,11 +363,13 @@ const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_
 // (so that they can be started before the weights are streamed), operator() finishes the tile.
 // kNeedsRs: the tile must be scaled by 1/sqrt(mean(x^2)+eps) of the token, which the caller
 // computes from the partial sums of squares ss[nch][m_pad].
+template <bool H>      // H: fp16 contraction (the weights' power of two is undone here)
 struct EpiQKV {
     static constexpr bool kNeedsRs = true;
     int M, q_len, q, kv, d, h, max_ctx, nch, m_pad;
     float eps;
     const float *ss, *cosT, *sinT;
+    const float *wsc = nullptr;       // NULL, or the factor that undoes the power of two in the fp16 copy of the weights
     __bf16 *qbuf, *qlo, *kc, *vc;     // queries are kept as hi + lo pairs
     spd_positions P;
     struct Pre {
@@ -359,6 +399,7 @@ struct EpiQKV {
         const int bseq = m / q_len, pos = P.pos[bseq] + (m % q_len);
         const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;       // column inside the head
         const int cb = spd_qkv_tile_col0(2 * pair + 1, q, kv, d) - head * d + 4 * g;
+        if constexpr (H) rs *= *wsc;
         a *= rs;
         b *= rs;
         if (head < q + kv) {
@@ -395,15 +436,17 @@ struct EpiQKV {
 // so every slice applies them to its own partial sums and parks the result, fp32, in
 // part[slice][token][column] (columns in natural order: head * d + j).  The attention kernel adds
 // the slices in ascending order, rounds, and appends the new key and value to the cache.
+template <bool H>
 struct EpiQKVPart {
     static constexpr bool kNeedsRs = true;
     int M, q_len, q, kv, d, h, nqkv, nch, m_pad;
     int part_rows;             // token rows per slice of `part`
     float eps;
     const float *ss, *cosT, *sinT;
+    const float *wsc = nullptr;
     float *part;
     spd_positions P;
-    typedef EpiQKV::Pre Pre;
+    typedef typename EpiQKV<H>::Pre Pre;
 
     __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
         Pre p;
@@ -427,6 +470,7 @@ struct EpiQKVPart {
         const int head = (2 * pair) / tph;
         const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) + 4 * g;
         const int cb = spd_qkv_tile_col0(2 * pair + 1, q, kv, d) + 4 * g;
+        if constexpr (H) rs *= *wsc;
         a *= rs;
         b *= rs;
         float4 lo = make_float4(a[0], a[1], a[2], a[3]), hi = make_float4(b[0], b[1], b[2], b[3]);
@@ -441,12 +485,13 @@ struct EpiQKVPart {
     }
 };
 
-template <bool MID>      // MID: the epilogue can also perform the kept attention sync point (spd = 2)
+template <bool MID, bool H>      // MID: the epilogue can also perform the kept attention sync point (spd = 2); H: fp16 activations out
 struct EpiOT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
     const float *bo = nullptr; // bias of the output projection or NULL: part of the SPD block's MLP input (Sec. 4.1.2)
+    const float *wsc = nullptr;
     float *ybuf, *slot, *ss2;
     __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
     // spd = 2: TP block whose kept attention sync point is performed here (one rank, the peers' partial
@@ -486,6 +531,11 @@ struct EpiOT {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const int na = pair * 32 + 4 * g, nb = na + 16;
         const bool valid = m < M;
+        if constexpr (H) {
+            const float sc = *wsc;
+            a *= sc;
+            b *= sc;
+        }
         if (!spd) {
             if (valid) {
                 *(float4 *)(slot + (size_t)m * h + na) = make_float4(a[0], a[1], a[2], a[3]);
@@ -517,15 +567,15 @@ struct EpiOT {
             pa[0] = ra[0] * p.ga.x; pa[1] = ra[1] * p.ga.y; pa[2] = ra[2] * p.ga.z; pa[3] = ra[3] * p.ga.w;
             pb[0] = rb[0] * p.gb.x; pb[1] = rb[1] * p.gb.y; pb[2] = rb[2] * p.gb.z; pb[3] = rb[3] * p.gb.w;
         }
-        const bf16x4 xa = cvt4(pa[0], pa[1], pa[2], pa[3]), xb = cvt4(pb[0], pb[1], pb[2], pb[3]);
+        const bf16x4 xa = cvt4t<H>(pa[0], pa[1], pa[2], pa[3]), xb = cvt4t<H>(pb[0], pb[1], pb[2], pb[3]);
         // the pair's 32 features are k-tile `pair` of the next contraction
         const size_t fo = spd_frag_index(mt, pair, h >> 5);
         const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
         *(bf16x4 *)(xhat2 + fo + ea) = xa;
         *(bf16x4 *)(xhat2 + fo + eb) = xb;
         if (xlo2) {
-            *(bf16x4 *)(xlo2 + fo + ea) = cvt4_lo(pa[0], pa[1], pa[2], pa[3], xa);
-            *(bf16x4 *)(xlo2 + fo + eb) = cvt4_lo(pb[0], pb[1], pb[2], pb[3], xb);
+            *(bf16x4 *)(xlo2 + fo + ea) = cvt4t_lo<H>(pa[0], pa[1], pa[2], pa[3], xa);
+            *(bf16x4 *)(xlo2 + fo + eb) = cvt4t_lo<H>(pb[0], pb[1], pb[2], pb[3], xb);
         }
         float s = 0.f;
 #pragma unroll
@@ -536,12 +586,14 @@ struct EpiOT {
     }
 };
 
+template <bool H>
 struct EpiGU {
     static constexpr bool kNeedsRs = true;
     int M, h, f_pad, nch, m_pad;
     int cols = 16;             // FFN columns per group: 16, or fewer for the decode-only narrow groups
     float eps;
     const float *ss;
+    const float *wsc = nullptr;
     __bf16 *uhat, *ulo;        // ulo may be NULL
     struct Pre {};
 
@@ -550,6 +602,7 @@ struct EpiGU {
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         float o[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (H) rs *= *wsc;
         if (m < M) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -557,10 +610,10 @@ struct EpiGU {
                 o[i] = gt / (1.0f + __expf(-gt)) * up;
             }
         }
-        const bf16x4 u = cvt4(o[0], o[1], o[2], o[3]);
+        const bf16x4 u = cvt4t<H>(o[0], o[1], o[2], o[3]);
         if (cols != 16) {
             // narrow group: rows 4g .. 4g+3 are FFN columns cols*pair + 4g + i, stored one by one
-            const bf16x4 lo = cvt4_lo(o[0], o[1], o[2], o[3], u);
+            const bf16x4 lo = cvt4t_lo<H>(o[0], o[1], o[2], o[3], u);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int col = pair * cols + 4 * g + i;
@@ -575,11 +628,11 @@ struct EpiGU {
         // gate/up pair p covers FFN columns [16p, 16p+16): half of k-tile p/2 of the down projection
         const size_t fo = spd_frag_index(mt, pair >> 1, f_pad >> 5) + spd_frag_elem(r, 16 * (pair & 1) + 4 * g);
         *(bf16x4 *)(uhat + fo) = u;
-        if (ulo) *(bf16x4 *)(ulo + fo) = cvt4_lo(o[0], o[1], o[2], o[3], u);
+        if (ulo) *(bf16x4 *)(ulo + fo) = cvt4t_lo<H>(o[0], o[1], o[2], o[3], u);
     }
 };
 
-template <bool FUSED>
+template <bool FUSED, bool H>
 struct EpiDownT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd;
@@ -589,6 +642,7 @@ struct EpiDownT {
     // inputs).  base == NULL: not fused.
     const float *base, *slots, *g1;
     const float *bias;         // [h] added once after the sum (SPD block with bias) or NULL
+    const float *wsc = nullptr;
     size_t slot_stride;
     int tp, rank, m_pad;
     float *x_out, *ss1;
@@ -619,6 +673,11 @@ struct EpiDownT {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const bool valid = m < M;
         const size_t oa = (size_t)m * h + pair * 32 + 4 * g, ob = oa + 16;
+        if constexpr (H) {
+            const float sc = *wsc;
+            a *= sc;
+            b *= sc;
+        }
         // SPD block: Y_r joins the partial sum before the sync point (Sec. 4.1.1); p.y* are zero otherwise
         const float4 pa = make_float4(a[0] + p.ya.x, a[1] + p.ya.y, a[2] + p.ya.z, a[3] + p.ya.w);
         const float4 pb = make_float4(b[0] + p.yb.x, b[1] + p.yb.y, b[2] + p.yb.z, b[3] + p.yb.w);
@@ -640,14 +699,14 @@ struct EpiDownT {
             qa[0] = xa.x * ga.x; qa[1] = xa.y * ga.y; qa[2] = xa.z * ga.z; qa[3] = xa.w * ga.w;
             qb[0] = xb.x * gb.x; qb[1] = xb.y * gb.y; qb[2] = xb.z * gb.z; qb[3] = xb.w * gb.w;
         }
-        const bf16x4 ha = cvt4(qa[0], qa[1], qa[2], qa[3]), hb = cvt4(qb[0], qb[1], qb[2], qb[3]);
+        const bf16x4 ha = cvt4t<H>(qa[0], qa[1], qa[2], qa[3]), hb = cvt4t<H>(qb[0], qb[1], qb[2], qb[3]);
         const size_t fo = spd_frag_index(mt, pair, h >> 5);
         const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
         *(bf16x4 *)(xhat + fo + ea) = ha;
         *(bf16x4 *)(xhat + fo + eb) = hb;
         if (xlo) {
-            *(bf16x4 *)(xlo + fo + ea) = cvt4_lo(qa[0], qa[1], qa[2], qa[3], ha);
-            *(bf16x4 *)(xlo + fo + eb) = cvt4_lo(qb[0], qb[1], qb[2], qb[3], hb);
+            *(bf16x4 *)(xlo + fo + ea) = cvt4t_lo<H>(qa[0], qa[1], qa[2], qa[3], ha);
+            *(bf16x4 *)(xlo + fo + eb) = cvt4t_lo<H>(qb[0], qb[1], qb[2], qb[3], hb);
         }
         float sq = xa.x * xa.x + xa.y * xa.y + xa.z * xa.z + xa.w * xa.w + xb.x * xb.x + xb.y * xb.y + xb.z * xb.z + xb.w * xb.w;
         sq += shfl_xor_f(sq, 16);
@@ -860,7 +919,7 @@ __global__ void __launch_bounds__(256) k_gemv_finish(const float *__restrict__ k
 }
 
 // ------------------------------------------------------------------------------------------
-// Projection for 17 .. 16*MT tokens per workgroup ("skinny": still bound by streaming the weights).
+// Projection for 17 .. 16*MT tokens per workgroup ("skinny": still bound by streaming the weights); fp16 operands.
 // Like k_gemv, one workgroup per pair of n-tiles (or narrow group) and slice of K, the W waves
 // splitting K; every wave multiplies each weight fragment it streams with MT m-tiles of
 // activations (read through the L2, where they stay resident).  grid = (pairs, KS, groups of MT
@@ -917,11 +976,11 @@ __global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp
     auto consume = [&](const SkinnyBatch<MT, SPLIT> &B) {
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
-            acc[i][0] = MFMA(B.fa, B.fh[i], acc[i][0]);
-            acc[i][1] = MFMA(B.fb, B.fh[i], acc[i][1]);
+            acc[i][0] = MFMA16(B.fa, B.fh[i], acc[i][0]);
+            acc[i][1] = MFMA16(B.fb, B.fh[i], acc[i][1]);
             if (SPLIT) {
-                acc[i][0] = MFMA(B.fa, B.fl[i], acc[i][0]);
-                acc[i][1] = MFMA(B.fb, B.fl[i], acc[i][1]);
+                acc[i][0] = MFMA16(B.fa, B.fl[i], acc[i][0]);
+                acc[i][1] = MFMA16(B.fb, B.fl[i], acc[i][1]);
             }
         }
     };
@@ -1045,8 +1104,8 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 const bf16x8 x = *(const bf16x8 *)(lds + (buf * MT * MID_KB + m * MID_KB + kb) * 1024 + lane * 16);
-                acc[m][0] = MFMA(S.wa[kb], x, acc[m][0]);
-                acc[m][1] = MFMA(S.wb[kb], x, acc[m][1]);
+                acc[m][0] = MFMA16(S.wa[kb], x, acc[m][0]);
+                acc[m][1] = MFMA16(S.wb[kb], x, acc[m][1]);
             }
         }
     };
@@ -1179,59 +1238,6 @@ __global__ void __launch_bounds__(256) k_qkv_gather(const float *__restrict__ pa
 }
 
 // ------------------------------------------------------------------------------------------
-// GEMM for more than 16 tokens, fragments streamed straight from global memory: each wave owns
-// MT m-tiles and one pair of n-tiles and runs the whole K.  grid = (pairs, groups of W*MT m-tiles).
-// ------------------------------------------------------------------------------------------
-template <int MT, int W, bool SPLIT, class Epi>
-__global__ void __launch_bounds__(W * 64) k_gemm(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xhi,
-                                                  const __bf16 *__restrict__ Xlo, int KT, int n_mtiles, Epi epi) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int pair = blockIdx.x;
-    const int mt0 = (blockIdx.y * W + wave) * MT;
-    if (mt0 >= n_mtiles) return;
-    f32x4 acc[MT][2];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        acc[i][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        acc[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
-    const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
-    const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
-    const bf16x8 *xp[MT], *xq[MT];
-    bool mv[MT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        mv[i] = (mt0 + i) < n_mtiles;
-        const size_t o = spd_frag_index(mv[i] ? mt0 + i : mt0, 0, KT);
-        xp[i] = (const bf16x8 *)(Xhi + o) + lane;
-        xq[i] = (const bf16x8 *)(Xlo + o) + lane;
-    }
-#pragma unroll 2
-    for (int kt = 0; kt < KT; ++kt) {
-        const bf16x8 fa = wa[(size_t)kt * 64], fb = wb[(size_t)kt * 64];
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            const bf16x8 fx = xp[i][(size_t)kt * 64];
-            acc[i][0] = MFMA(fa, fx, acc[i][0]);
-            acc[i][1] = MFMA(fb, fx, acc[i][1]);
-            if (SPLIT) {
-                const bf16x8 fl = xq[i][(size_t)kt * 64];
-                acc[i][0] = MFMA(fa, fl, acc[i][0]);
-                acc[i][1] = MFMA(fb, fl, acc[i][1]);
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        if (!mv[i]) continue;
-        float rs = 1.f;
-        if constexpr (Epi::kNeedsRs)
-            rs = row_rsqrt(epi.ss, epi.nch, epi.m_pad, (mt0 + i) * 16 + (lane & 15), lane >> 4, epi.h, epi.eps);
-        epi(pair, mt0 + i, acc[i][0], acc[i][1], lane, rs, epi.pre(pair, mt0 + i, lane));
-    }
-}
-
-// ------------------------------------------------------------------------------------------
 // GEMM for prefill-sized calls: a workgroup computes a 256 (output features) x 256 (tokens) tile
 // with 8 waves (or 256 x 128 with 4); both operands are staged through LDS in steps of 64 (or 32)
 // contraction elements, double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
@@ -1252,13 +1258,19 @@ struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
     static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
 };
-template <class Epi, class G>
+// XS: the activations are hi + lo pairs (second plane at Xlo).  A step then covers ONE k-tile: its weight
+// fragments and, per m-tile, the hi and the lo fragment of that k-tile, so the copies and the fragment
+// reads of the weights are shared by both passes and any number of k-tiles will do.
+template <class Epi, class G, bool XS>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
-                                                                   int KT, int n_ntiles, int n_mtiles, spd_tile_order ord, int tile0,
-                                                                   int n_tiles, int msub, Epi epi) {
+                                                                   const __bf16 *__restrict__ Xlo, int KT, int n_ntiles,
+                                                                   int n_mtiles, spd_tile_order ord, int tile0, int n_tiles,
+                                                                   int msub, Epi epi) {
     constexpr int GL_WN = G::WN, GL_WM = G::WM, GL_TI = G::TI, GL_TJ = G::TJ, KPS = G::KPS;
     constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // tiles per workgroup
-    constexpr int GL_STAGE = (GL_BN + GL_BM) * KPS * 1024;
+    constexpr int KW = XS ? 1 : KPS;                                     // weight fragments per tile row and step
+    constexpr int KX = XS ? 2 : KPS;                                     // activation fragments per tile row and step
+    constexpr int GL_STAGE = (GL_BN * KW + GL_BM * KX) * 1024;
     constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
     static_assert((GL_BN + GL_BM) % (GL_WN * GL_WM) == 0 && GL_TI % 2 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -1284,35 +1296,49 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
         for (int j = 0; j < GL_TJ; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    // this wave's share of the copies: GL_FPW tile rows; the KPS k-tiles of a row are contiguous
-    // both in global memory and in LDS.  Rows past the matrix repeat its last tile.
-    const __bf16 *src[GL_FPW];
+    // this wave's share of the copies: GL_FPW tile rows.  Without XS the KPS k-tiles of a row are contiguous
+    // both in global memory and in LDS; with XS an activation row is the hi fragment then the lo fragment of
+    // one k-tile.  Rows past the matrix repeat its last tile.
+    const __bf16 *src[GL_FPW], *src2[GL_FPW];
+    int loff[GL_FPW];
+    bool isx[GL_FPW];
 #pragma unroll
     for (int i = 0; i < GL_FPW; ++i) {
         const int row = wave * GL_FPW + i;
-        if (row < GL_BN) {
+        isx[i] = row >= GL_BN;
+        if (!isx[i]) {
             int t = nt0 + row;
             if (t >= n_ntiles) t = n_ntiles - 1;
-            src[i] = Wp + spd_frag_index(t, 0, KT) + lane * 8;
+            src[i] = src2[i] = Wp + spd_frag_index(t, 0, KT) + lane * 8;
+            loff[i] = row * (KW * 1024);
         } else {
             int t = mt0 + row - GL_BN;
             if (t >= n_mtiles) t = n_mtiles - 1;
             src[i] = Xp + spd_frag_index(t, 0, KT) + lane * 8;
+            src2[i] = XS ? Xlo + spd_frag_index(t, 0, KT) + lane * 8 : src[i];
+            loff[i] = GL_BN * (KW * 1024) + (row - GL_BN) * (KX * 1024);
         }
     }
     auto issue = [&](int stage, int ks) {
 #pragma unroll
         for (int i = 0; i < GL_FPW; ++i) {
-            const __bf16 *g = src[i] + (size_t)ks * (KPS * 512);
-            char *l = lds + stage * GL_STAGE + (wave * GL_FPW + i) * (KPS * 1024);
+            const __bf16 *g = src[i] + (size_t)ks * ((XS ? 1 : KPS) * 512);
+            char *l = lds + stage * GL_STAGE + loff[i];
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                              (__attribute__((address_space(3))) void *)l, 16, 0, 0);
-            if (KPS == 2)
+            if constexpr (XS) {
+                if (isx[i]) {
+                    const __bf16 *g2 = src2[i] + (size_t)ks * 512;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g2,
+                                                     (__attribute__((address_space(3))) void *)(l + 1024), 16, 0, 0);
+                }
+            } else if (KPS == 2) {
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                                  (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
+            }
         }
     };
-    const int nks = KT / KPS;
+    const int nks = XS ? KT : KT / KPS;
     issue(0, 0);
     for (int ks = 0; ks < nks; ++ks) {
         const int cur = ks & 1;
@@ -1323,23 +1349,25 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
         // all fragments of the step are requested first, then the MFMAs run in program order
         // (the scheduling barriers keep the compiler from re-interleaving reads and MFMAs, which
         // would make it wait for the whole LDS queue before every group of MFMAs)
-        bf16x8 a[KPS][GL_TI], b[KPS][GL_TJ];
+        bf16x8 a[KW][GL_TI], b[KX][GL_TJ];
 #pragma unroll
-        for (int kt = 0; kt < KPS; ++kt) {
+        for (int kt = 0; kt < KX; ++kt) {
 #pragma unroll
             for (int j = 0; j < GL_TJ; ++j)
-                b[kt][j] = *(const bf16x8 *)(st + GL_BN * KPS * 1024 + ((wm * GL_TJ + j) * KPS + kt) * 1024 + lane * 16);
+                b[kt][j] = *(const bf16x8 *)(st + GL_BN * KW * 1024 + ((wm * GL_TJ + j) * KX + kt) * 1024 + lane * 16);
+            if (kt < KW) {
 #pragma unroll
-            for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * KPS + kt) * 1024 + lane * 16);
+                for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * KW + kt) * 1024 + lane * 16);
+            }
         }
 #pragma unroll
-        for (int kt = 0; kt < KPS; ++kt)
+        for (int kt = 0; kt < KX; ++kt)
 #pragma unroll
             for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
                 for (int j = 0; j < GL_TJ; ++j) {
-                    acc[i][j] = MFMA(a[kt][i], b[kt][j], acc[i][j]);
-                    if (KPS == 2) __builtin_amdgcn_sched_barrier(0);
+                    acc[i][j] = MFMA16(a[XS ? 0 : kt][i], b[kt][j], acc[i][j]);
+                    if (KX == 2) __builtin_amdgcn_sched_barrier(0);
                 }
     }
     // norm factors of all the wave's m-tiles first, so that their loads are in flight together
@@ -1382,17 +1410,19 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     }
 }
 
-template <class G, class Epi>
-hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi,
-                               int tile0 = 0, int msub = 1, int n_tiles = -1) {
+template <class G, bool XS, class Epi>
+hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, const __bf16 *Xlo, int n_pairs, int KT,
+                               const Epi &epi, int tile0 = 0, int msub = 1, int n_tiles = -1) {
     // with msub = 2 the tiles are counted in the shape of twice G's height (GemmHalf finishing a GemmBig launch)
-    constexpr int BN = G::WN * G::TI, STAGE = (BN + G::WM * G::TJ) * G::KPS * 1024;
+    constexpr int BN = G::WN * G::TI;
+    constexpr int STAGE = (BN * (XS ? 1 : G::KPS) + G::WM * G::TJ * (XS ? 2 : G::KPS)) * 1024;
+    static_assert(2 * STAGE <= 160 * 1024, "two stages must fit the LDS of a compute unit");
     const int BM = G::WM * G::TJ * msub;
     // the attribute is per kernel instantiation: set once, whichever thread comes first
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+        attr_err = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G, XS>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
     });
     if (attr_err != hipSuccess) return attr_err;
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
@@ -1403,30 +1433,33 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     if (n_tiles < 0) n_tiles = ord.TN * ord.TM - tile0;
     // msub = 1: whole rounds of 256, then eight equal shares (the spare workgroups of a ragged share exit at once)
     const int n_wgs = msub == 1 ? spd_tile_launch_size(n_tiles) : n_tiles * msub;
-    hipLaunchKernelGGL((k_gemm_lds<Epi, G>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, KT, n_ntiles,
+    hipLaunchKernelGGL((k_gemm_lds<Epi, G, XS>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, Xlo, KT, n_ntiles,
                        n_mtiles, ord, tile0, n_tiles, msub, epi);
     return hipGetLastError();
 }
 
-template <class Epi>
-hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, int n_pairs, int KT, const Epi &epi) {
+template <bool XS, class Epi>
+hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, const __bf16 *Xlo, int n_pairs, int KT,
+                           const Epi &epi) {
     // both shapes measure the same on the 70B shard (the big one is ahead by 1-3 % on QKV and down);
-    // the mid one also takes an odd number of k-tiles
-    if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid>(c, Wp, Xp, n_pairs, KT, epi);
+    // the mid one also takes an odd number of k-tiles (a step of the split kind is one k-tile anyway)
+    if constexpr (!XS) {
+        if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid, false>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+    }
     // fewer 256 x 256 tiles than compute units (the QKV projection of a shard): 128 x 384 tiles when they
     // fill one round better
     const int n_mtiles = (c.M + 15) / 16;
     const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
-    if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall>(c, Wp, Xp, n_pairs, KT, epi);
+    if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
     // a last round that would occupy at most half of the compute units runs as twice as many half tiles
     // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)
     const int rem = big % 256;
     if (big > 256 && rem > 0 && rem <= 128) {
-        const hipError_t e = launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi, 0, 1, big - rem);
+        const hipError_t e = launch_gemm_lds_cfg<GemmBig, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, big - rem);
         if (e != hipSuccess) return e;
-        return launch_gemm_lds_cfg<GemmHalf>(c, Wp, Xp, n_pairs, KT, epi, big - rem, 2, rem);
+        return launch_gemm_lds_cfg<GemmHalf, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, big - rem, 2, rem);
     }
-    return launch_gemm_lds_cfg<GemmBig>(c, Wp, Xp, n_pairs, KT, epi);
+    return launch_gemm_lds_cfg<GemmBig, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1735,6 +1768,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
 // grid (kv heads, sequences, d/16); thread -> (feature dd, column c).  Every thread reads the
 // running max and sum of its column itself (16 splits at a time, all loads issued together), so
 // the kernel is one memory round trip per 16 splits; the splits are merged in ascending order.
+template <bool H>      // H: the output feeds an fp16 contraction
 __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, int q, int kv, int d, int n_splits) {
     const int kvh = blockIdx.x, b = blockIdx.y;
@@ -1771,9 +1805,9 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
     const float val = num / den;
     const int kidx = (kvh * group + c) * d + dd;
     const size_t o = spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31);
-    const __bf16 hi = (__bf16)val;
+    const __bf16 hi = Act<H>::one(val);
     ahat[o] = hi;
-    if (alo) alo[o] = (__bf16)(val - (float)hi);
+    if (alo) alo[o] = Act<H>::one(val - Act<H>::back(hi));
 }
 
 // Prefill (q_len > 1): grid (groups of CT column tiles, kv heads, sequences), 4 waves.  All four
@@ -1781,7 +1815,7 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
 // among themselves block by block (the latest tokens attend thousands of keys: one wave walking
 // them alone would be the critical path of the launch); their partial states meet in LDS and
 // every wave finishes a quarter of the (tile, 16-feature slice) outputs.
-template <int DT, int CT>
+template <int DT, int CT, bool H>
 __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
                                                       const __bf16 *__restrict__ vc, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, spd_positions P, int q_len, int q, int kv,
@@ -1861,23 +1895,24 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
         const int mt = mrow[c] >> 4, r = mrow[c] & 15;
         const int kidx = hd[c] * d + dt * 16 + 4 * g;
         const float o0 = num[0] * inv, o1 = num[1] * inv, o2 = num[2] * inv, o3 = num[3] * inv;
-        const bf16x4 v = cvt4(o0, o1, o2, o3);
+        const bf16x4 v = cvt4t<H>(o0, o1, o2, o3);
         const size_t o = spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31);
         *(bf16x4 *)(ahat + o) = v;
-        if (alo) *(bf16x4 *)(alo + o) = cvt4_lo(o0, o1, o2, o3, v);
+        if (alo) *(bf16x4 *)(alo + o) = cvt4t_lo<H>(o0, o1, o2, o3, v);
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // taps (tests only): packed bf16 (hi [+ lo]) -> natural fp32
 // ------------------------------------------------------------------------------------------
+template <bool H>
 __global__ void k_unpack_act(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst, int M,
                              int K_packed, int K_out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)M * K_out) return;
     const int m = (int)(i / K_out), k = (int)(i % K_out);
     const size_t o = spd_frag_index(m >> 4, k >> 5, K_packed >> 5) + spd_frag_elem(m & 15, k & 31);
-    dst[i] = (float)src[o] + (lo ? (float)lo[o] : 0.f);
+    dst[i] = Act<H>::back(src[o]) + (lo ? Act<H>::back(lo[o]) : 0.f);
 }
 __global__ void k_bf16_to_f32(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst,
                               int64_t n) {
@@ -2039,22 +2074,22 @@ inline int skinny_limit(int n_pairs, int KT, int n_mtiles) {
     return t_skinny < t_gemm ? n_mtiles : SKINNY_MAX_MTILES;
 }
 
-template <class Epi>
+// Projection of a call of any size.  At most 16 tokens: the weight-streaming kernel on the bf16 weights
+// Wp; beyond that the fp16 kernels on the fp16 copy W16 (skinny up to `skinny_max` m-tiles, the LDS-tiled
+// GEMM beyond).
+template <bool H, class Epi>     // H: a call of more than 16 tokens (fp16 operands), Wp then is the fp16 copy
 hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
                        const Epi &epi, int skinny_max = SKINNY_MAX_MTILES) {
     const int n_mtiles = (c.M + 15) / 16;
     const __bf16 *Xlo = Xhi + plane;
-    if (n_mtiles == 1)
+    if constexpr (!H) {
+        if (n_mtiles != 1) return hipErrorInvalidValue;
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
-    if (n_mtiles <= skinny_max) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
-    if (!split && c.M >= 64) return launch_gemm_lds(c, Wp, Xhi, n_pairs, KT, epi);
-    constexpr int MT = 4, W = 4;
-    const dim3 grid(n_pairs, cdiv(n_mtiles, MT * W));
-    if (split)
-        hipLaunchKernelGGL((k_gemm<MT, W, true, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
-    else
-        hipLaunchKernelGGL((k_gemm<MT, W, false, Epi>), grid, dim3(W * 64), 0, c.s, Wp, Xhi, Xlo, KT, n_mtiles, epi);
-    return hipGetLastError();
+    } else {
+        if (n_mtiles <= skinny_max) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
+        return split ? launch_gemm_lds<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi)
+                     : launch_gemm_lds<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
+    }
 }
 
 // chunking of the sum-of-squares partials written by prep()
@@ -2071,33 +2106,63 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     const spd_dims &D = *c.D;
     const int tpw = prep_tpw(c.M), nch = prep_nch(D.h, c.M);
     __bf16 *xhat = want_xhat ? (__bf16 *)(c.ws + (which ? D.ws_xhat2 : D.ws_xhat)) : nullptr;
-    __bf16 *xlo = (want_xhat && (which ? c.split : c.split_all)) ? xhat + D.pl_x : nullptr;
+    __bf16 *xlo = (want_xhat && (which ? c.sp_m : c.sp_x)) ? xhat + D.pl_x : nullptr;
     float *ss = want_xhat ? (float *)(c.ws + (which ? D.ws_ss2 : D.ws_ss1)) : nullptr;
     if (n_slots == 0 && out == base && !bias) out = nullptr;   // nothing to rewrite
     if (!c.on(SPD_STAGE_PREP)) return hipSuccess;
     spd_stage_scope prof(c, SPD_STAGE_PREP);
     // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
-    if (tpw == 8 && D.h % 256 == 0)
-        hipLaunchKernelGGL(k_prep_rows<1>, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
-    else
-        hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
+    if (tpw == 8 && D.h % 256 == 0) {
+        const dim3 grid(D.h / 256, cdiv(c.M, 16));
+        if (c.f16)
+            hipLaunchKernelGGL((k_prep_rows<1, true>), grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out,
+                               gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
+        else
+            hipLaunchKernelGGL((k_prep_rows<1, false>), grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out,
+                               gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
+    } else {
+        const dim3 grid(cdiv(nch, 4), cdiv(c.M, 16));
+        if (c.f16)
+            hipLaunchKernelGGL(k_prep<true>, grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out, gain, xhat,
+                               xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
+        else
+            hipLaunchKernelGGL(k_prep<false>, grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out, gain, xhat,
+                               xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
+    }
     return hipGetLastError();
 }
 
 int prep_chunks(const spd_call &c) { return prep_nch(c.D->h, c.M); }
 
-hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
-                          const spd_mid_sync *mid, bool *mid_done) {
+namespace {
+// weights of projection `i` (0 QKV, 1 O, 2 gate/up, 3 down) in the operand format of the call, and the
+// factor that undoes the fp16 copy's power of two (NULL for the bf16 weights)
+struct ProjW {
+    const __bf16 *w;
+    const float *wsc;
+};
+inline ProjW proj_weights(const spd_call &c, const char *w, int i) {
+    const spd_dims &D = *c.D;
+    const size_t off_b[4] = {D.w_qkv, D.w_o, D.w_g, D.w_d}, off_h[4] = {D.w16_qkv, D.w16_o, D.w16_g, D.w16_d};
+    ProjW p;
+    p.w = (const __bf16 *)(w + (c.f16 ? off_h[i] : off_b[i]));
+    p.wsc = c.f16 ? (const float *)(w + D.w16_scale) + i : nullptr;
+    return p;
+}
+}  // namespace
+
+template <bool H>
+static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
+                                   const spd_mid_sync *mid, bool *mid_done) {
     const spd_dims &D = *c.D;
     const int M = c.M, qd = D.q * D.d;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat);
     __bf16 *qbuf = (__bf16 *)(c.ws + D.ws_q), *ahat = (__bf16 *)(c.ws + D.ws_ahat);
-    __bf16 *alo = c.split_all ? ahat + D.pl_a : nullptr;
+    __bf16 *alo = c.sp_a ? ahat + D.pl_a : nullptr;
     __bf16 *qlo = qbuf + D.pl_a;
     __bf16 *kc = (__bf16 *)kvc, *vc = (__bf16 *)(kvc + D.kv_v);
     float *ybuf = (float *)(c.ws + D.ws_y);
+    const ProjW wqkv = proj_weights(c, w, 0), wo = proj_weights(c, w, 1);
 
     // K-sliced QKV projections (too few column tiles to occupy the chip) with the linear epilogue:
     //  - a decode step hands the slices to the attention kernel (no second kernel to add them up);
@@ -2124,20 +2189,19 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     }
     float *qkvp = (float *)(c.ws + D.ws_kpart);
     if (fused_q || gather_q) {
-        EpiQKVPart e1;
+        EpiQKVPart<H> e1;
         e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
         e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.part_rows = 16 * n_mtiles; e1.eps = D.eps;
         e1.ss = (const float *)(c.ws + D.ws_ss1);
         e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.wsc = wqkv.wsc;
         e1.part = qkvp; e1.P = c.pos;
         if (c.on(SPD_STAGE_QKV)) {
             spd_stage_scope prof(c, SPD_STAGE_QKV);
-            if (n_mtiles == 1) {
-                SPD_TRY(launch_gemv_sliced(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
-                                           qkv_slices, e1));
+            if constexpr (!H) {
+                SPD_TRY(launch_gemv_sliced(c, c.sp_x, wqkv.w, xhat, D.pl_x, qkv_pairs, D.h / 32, qkv_slices, e1));
             } else {
-                SPD_TRY(launch_skinny<2>(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, qkv_pairs, D.h / 32,
-                                         qkv_slices, 16, e1));
+                SPD_TRY(launch_skinny<2>(c, c.sp_x, wqkv.w, xhat, D.pl_x, qkv_pairs, D.h / 32, qkv_slices, 16, e1));
             }
             if (gather_q) {
                 hipLaunchKernelGGL(k_qkv_gather, dim3(cdiv((int64_t)M * (D.nqkv / 4), 256)), dim3(256), 0, c.s, qkvp, qkv_slices,
@@ -2146,16 +2210,17 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
             }
         }
     } else {
-        EpiQKV e1;
+        EpiQKV<H> e1;
         e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
         e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
         e1.ss = (const float *)(c.ws + D.ws_ss1);
         e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.wsc = wqkv.wsc;
         e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
         if (c.on(SPD_STAGE_QKV)) {
             spd_stage_scope prof(c, SPD_STAGE_QKV);
-            SPD_TRY(launch_proj(c, c.split_all, (const __bf16 *)(w + D.w_qkv), xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
-                                skinny_limit(D.nqkv / 32, D.h / 32, n_mtiles)));
+            SPD_TRY(launch_proj<H>(c, c.sp_x, wqkv.w, xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
+                                   skinny_limit(D.nqkv / 32, D.h / 32, n_mtiles)));
         }
     }
 
@@ -2199,7 +2264,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         }
 #undef SPD_DECODE
         SPD_TRY(hipGetLastError());
-        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch, D.d / 16), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
+        hipLaunchKernelGGL(k_attn_combine<H>, dim3(D.kv, c.batch, D.d / 16), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
                            D.d, splits);
         SPD_TRY(hipGetLastError());
     } else {
@@ -2212,10 +2277,10 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         static std::once_flag once;                                                                                        \
         static hipError_t attr_err = hipSuccess;                                                                           \
         std::call_once(once, [] {                                                                                          \
-            attr_err = hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
+            attr_err = hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT, H>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
         });                                                                                                                \
         SPD_TRY(attr_err);                                                                                                 \
-        hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
+        hipLaunchKernelGGL((k_attn_prefill<DTV, CT, H>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
                            D.q, D.kv, D.max_ctx);                                                                          \
     }
         switch (DT) {
@@ -2236,28 +2301,28 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         e2.M = M; e2.h = D.h; e2.spd = spd; e2.m_pad = D.m_pad;
         e2.x = x; e2.g2 = (const float *)(w + D.w_g2);
         e2.bo = D.o_bias ? (const float *)(w + D.w_bo) : nullptr;
+        e2.wsc = wo.wsc;
         e2.ybuf = ybuf; e2.slot = slot; e2.ss2 = (float *)(c.ws + D.ws_ss2);
         e2.xhat2 = (__bf16 *)(c.ws + D.ws_xhat2);
-        e2.xlo2 = c.split ? e2.xhat2 + D.pl_x : nullptr;
+        e2.xlo2 = c.sp_m ? e2.xhat2 + D.pl_x : nullptr;
     };
     if (c.on(SPD_STAGE_O)) {
         spd_stage_scope prof(c, SPD_STAGE_O);
-        const __bf16 *wo = (const __bf16 *)(w + D.w_o);
         if (fuse_mid) {
             // the weight-streaming kernels only
-            EpiOT<true> e2;
+            EpiOT<true, H> e2;
             fill_o(e2);
             e2.spd = 2;
             e2.slots = mid->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = mid->tp; e2.rank = mid->rank; e2.rbuf = mid->rbuf;
-            if (M <= 16)
-                SPD_TRY(c.split_all ? launch_gemv<true>(c, wo, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2)
-                                    : launch_gemv<false>(c, wo, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2));
+            if constexpr (!H)
+                SPD_TRY(c.sp_a ? launch_gemv<true>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2)
+                               : launch_gemv<false>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2));
             else
-                SPD_TRY(launch_skinny<0>(c, c.split_all, wo, ahat, D.pl_a, D.h / 32, qd / 32, 1, 16, e2));
+                SPD_TRY(launch_skinny<0>(c, c.sp_a, wo.w, ahat, D.pl_a, D.h / 32, qd / 32, 1, 16, e2));
         } else {
-            EpiOT<false> e2;
+            EpiOT<false, H> e2;
             fill_o(e2);
-            SPD_TRY(launch_proj(c, c.split_all, wo, ahat, D.pl_a, D.h / 32, qd / 32, e2));
+            SPD_TRY(launch_proj<H>(c, c.sp_a, wo.w, ahat, D.pl_a, D.h / 32, qd / 32, e2));
         }
     }
 
@@ -2268,7 +2333,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
             SPD_TRY(hipGetLastError());
         }
         if (c.taps->attn) {
-            hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, alo, c.taps->attn, M,
+            hipLaunchKernelGGL(k_unpack_act<H>, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, alo, c.taps->attn, M,
                                qd, qd);
             SPD_TRY(hipGetLastError());
         }
@@ -2277,41 +2342,46 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
     return hipSuccess;
 }
 
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
-                    bool ss_per_pair) {
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
+                          const spd_mid_sync *mid, bool *mid_done) {
+    return c.f16 ? attention_half_t<true>(c, w, kvc, x, spd, slot, mid, mid_done)
+                 : attention_half_t<false>(c, w, kvc, x, spd, slot, mid, mid_done);
+}
+
+template <bool H>
+static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
+                             bool ss_per_pair) {
     const spd_dims &D = *c.D;
     const int M = c.M;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat2);
     __bf16 *uhat = (__bf16 *)(c.ws + D.ws_uhat);
-    __bf16 *ulo = c.split ? uhat + D.pl_u : nullptr;
+    __bf16 *ulo = c.sp_m ? uhat + D.pl_u : nullptr;
+    const ProjW wgu = proj_weights(c, w, 2), wdn = proj_weights(c, w, 3);
 
-    EpiGU e1;
+    EpiGU<H> e1;
     e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.m_pad = D.m_pad; e1.eps = D.eps;
     // SPD block: the O-projection epilogue wrote one partial per pair of n-tiles (h/32 of them);
     // TP block: prep() wrote them after the kept sync point
     e1.nch = ss_per_pair ? D.h / 32 : prep_nch(D.h, M);
     e1.ss = (const float *)(c.ws + D.ws_ss2);
+    e1.wsc = wgu.wsc;
     e1.uhat = uhat; e1.ulo = ulo;
     if (c.on(SPD_STAGE_GATEUP)) {
         spd_stage_scope prof(c, SPD_STAGE_GATEUP);
-        if (D.gud_cols && M <= 16) {
-            // decode: the copy with narrow column groups, one workgroup per group
-            e1.cols = D.gud_cols;
-            const __bf16 *wd = (const __bf16 *)(w + D.w_gud), *xlo = xhat + D.pl_x;
-            SPD_TRY(c.split ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
-                            : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
+        if constexpr (!H) {
+            if (D.gud_cols) {
+                // decode: the copy with narrow column groups, one workgroup per group
+                e1.cols = D.gud_cols;
+                const __bf16 *wd = (const __bf16 *)(w + D.w_gud), *xlo = xhat + D.pl_x;
+                SPD_TRY(c.sp_m ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
+                               : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
+            } else {
+                SPD_TRY(launch_proj<H>(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+            }
         } else {
             bool mid = false;
-            if (!c.split) SPD_TRY(launch_mid(c, (const __bf16 *)(w + D.w_g), xhat, D.f_pad / 16, D.h / 32, e1, &mid));
-            if (mid) {
-                // done
-            } else if (D.gud_cols && D.f_pad / 16 >= 192 && M <= 16 * SKINNY_MAX_MTILES) {
-                e1.cols = D.gud_cols;
-                SPD_TRY(launch_skinny<0>(c, c.split, (const __bf16 *)(w + D.w_gud), xhat, D.pl_x, D.gud_groups, D.h / 32, 1,
-                                         D.gud_cols, e1));
-            } else {
-                SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_g), xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
-            }
+            if (!c.sp_m) SPD_TRY(launch_mid(c, wgu.w, xhat, D.f_pad / 16, D.h / 32, e1, &mid));
+            if (!mid) SPD_TRY(launch_proj<H>(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
         }
     }
 
@@ -2326,39 +2396,45 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
         e2.ybuf = (const float *)(c.ws + D.ws_y); e2.slot = slot;
         e2.base = nullptr; e2.slots = nullptr; e2.g1 = nullptr; e2.bias = nullptr; e2.slot_stride = 0; e2.tp = 0; e2.rank = 0; e2.m_pad = D.m_pad;
         e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
+        e2.wsc = wdn.wsc;
         if (do_fuse) {
             e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp;
             e2.rank = fuse->rank; e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.bias = fuse->bias; e2.ss1 = (float *)(c.ws + D.ws_ss1);
             if (fuse->next_g1) {
                 e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);
-                e2.xlo = c.split_all ? e2.xhat + D.pl_x : nullptr;
+                e2.xlo = c.sp_x ? e2.xhat + D.pl_x : nullptr;
             }
         }
     };
     if (c.on(SPD_STAGE_DOWN)) {
         spd_stage_scope prof(c, SPD_STAGE_DOWN);
         if (do_fuse) {
-            EpiDownT<true> e2;
+            EpiDownT<true, H> e2;
             fill(e2);
-            const __bf16 *wd = (const __bf16 *)(w + D.w_d);
-            if (M <= 16)
-                SPD_TRY(c.split ? launch_gemv<true>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
-                                : launch_gemv<false>(c, wd, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            if constexpr (!H)
+                SPD_TRY(c.sp_m ? launch_gemv<true>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
+                               : launch_gemv<false>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
             else
-                SPD_TRY(launch_skinny<0>(c, c.split, wd, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
+                SPD_TRY(launch_skinny<0>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
         } else {
-            EpiDownT<false> e2;
+            EpiDownT<false, H> e2;
             fill(e2);
-            SPD_TRY(launch_proj(c, c.split, (const __bf16 *)(w + D.w_d), uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            SPD_TRY(launch_proj<H>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
         }
     }
 
     if (c.taps && c.taps->u) {
-        hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, ulo, c.taps->u, M,
+        hipLaunchKernelGGL(k_unpack_act<H>, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, ulo, c.taps->u, M,
                            D.f_pad, D.f);
         SPD_TRY(hipGetLastError());
     }
     return hipSuccess;
+}
+
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
+                    bool ss_per_pair) {
+    return c.f16 ? mlp_half_t<true>(c, w, spd, slot, fuse, fused, ss_per_pair)
+                 : mlp_half_t<false>(c, w, spd, slot, fuse, fused, ss_per_pair);
 }
 
 }  // namespace spd_bf16

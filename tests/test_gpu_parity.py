@@ -204,7 +204,7 @@ SMALL_H512 = Workload(name="small-bf16-h512", hidden=512, n_q_heads=8, n_kv_head
 
 @pytest.mark.parametrize("w", [SMALL, SMALL_H512, SMALL_MHA], ids=lambda w: w.name)
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
-@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
+@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS, B.SPD_SPLIT_NEVER], ids=["default", "all-split", "no-split"])
 def test_bf16_long_call_small_shape(gpu, w, flag, split):
     """More than 512 tokens in one call on a small shape, all ranks: the launch shapes of the long
     prefill (LDS-tiled GEMM, key-split attention, row-wise norm preparation) with a ragged last
@@ -445,13 +445,13 @@ def test_full_size_decode_shapes(gpu, name):
 
 def test_full_size_short_prefill(gpu):
     """LLaMA2-70B shard, one sequence of 128 tokens (the shape of the paper's latency breakdown,
-    Fig. 2), an SPD block then a TP block, every output row checked, with split activations (the
-    2e-2 bound as it stands; a single-pass run of this shape measures 9e-2, see the long prefill)."""
+    Fig. 2), an SPD block then a TP block, every output row checked at the 2e-2 bound as it
+    stands, in the default configuration (the one the bench times)."""
     import torch
     full = workloads.get("70b-prefill-128")
     w = full.with_layers(2).with_mask((1, 0))
     M = full.q_len
-    case = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, full.n_layers - 1], act_split=B.SPD_SPLIT_ALWAYS)
+    case = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, full.n_layers - 1])
     X = inputs.hidden_states(w, M)
     peers = inputs.peer_slots(w, M)
     x, slots = case.to_dev(X), case.to_dev(peers)
@@ -471,20 +471,18 @@ def test_full_size_short_prefill(gpu):
 
 
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
-@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["single-pass", "split"])
+@pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["default", "all-split"])
 def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
-    """LLaMA2-70B shard, 4 x 2048 tokens: the oracle computes sampled output rows one by one.
-
-    With split activations the 2e-2 bound holds as it stands.  The default single-pass bf16
-    contraction rounds every activation that feeds a projection to 8 significant bits; with up
-    to 8192 terms per output and outputs that reach |v| ~ 15 (rms ~ 2.9) that rounding alone
-    exceeds 2e-2, so the single-pass bound adds one bf16 unit in the last place at the largest
-    output magnitude: 2e-2 + ulp_bf16(max |oracle|)."""
+    """LLaMA2-70B shard, 4 x 2048 tokens, the launch configuration the bench times (and, beside
+    it, the one with every projection input split): the oracle computes sampled output rows one
+    by one; the 2e-2 bound as it stands."""
     import torch
     full = workloads.LLAMA70B_PREFILL
     w = full.with_layers(1).with_mask((flag,))
     M = full.batch * full.q_len
-    rows = np.array([0, 1, 15, 16, 17, 255, 256, 2047, 2048, 2049, 3000, 4095, 4096, 5555, 6143, 6144, 8000, 8191])
+    rows = np.unique(np.concatenate([
+        np.array([0, 1, 15, 16, 17, 255, 256, 2047, 2048, 2049, 3000, 4095, 4096, 5555, 6143, 6144, 8000, 8191]),
+        np.random.default_rng(7).choice(M, size=110, replace=False)]))
     X = inputs.hidden_states(w, M)
     peers = inputs.peer_slots(w, M)
     say(f"full-size prefill flag={flag} split={split}")
@@ -500,11 +498,10 @@ def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
     want = O.block_single_rank(case.sh, X, case.shards[0][0], case.caches[0][0], [0] * full.batch, full.batch,
                                full.q_len, flag, 0, peers, rows=rows)
     rms = float(np.sqrt(np.mean(want ** 2)))
-    ulp = 2.0 ** (np.floor(np.log2(np.max(np.abs(want)))) - 7)
-    scale = 1.0 if split == B.SPD_SPLIT_ALWAYS else (2e-2 + ulp) / 2e-2
-    say("  per-row max err:", " ".join(f"{r}:{e:.1e}" for r, e in zip(rows, np.max(np.abs(got - want), axis=1))))
-    err = assert_close(got, want, w, f"prefill rows flag={flag} split={split}", scale=scale)
-    say(f"  sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}, rms {rms:.2f}")
+    worst = np.max(np.abs(got - want), axis=1)
+    say("  largest per-row max err:", " ".join(f"{rows[i]}:{worst[i]:.1e}" for i in np.argsort(worst)[-6:]))
+    err = assert_close(got, want, w, f"prefill rows flag={flag} split={split}")
+    say(f"  {len(rows)} sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}, rms {rms:.2f}")
     # properties that hold at any size: peers' slots untouched; finite everywhere
     assert np.array_equal(slots[5][:64].cpu().numpy(), peers[5][:64])
     assert bool(torch.isfinite(slots[0]).all())
