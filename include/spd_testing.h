@@ -38,20 +38,22 @@ int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer *
 int spd_stage_timer_read(spd_stage_timer *timer, int32_t *n_records, double *mean_us, double *min_us);
 void spd_stage_timer_destroy(spd_stage_timer *timer);
 
-/* spd_model_forward() with two more arguments:
+/* spd_model_forward() with three more arguments:
  *   stage_mask  bit s set = the kernels of stage s are launched.  SPD_ALL_STAGES is the ordinary
  *               call.  With a single bit a whole-model call becomes a train of launches of one
  *               stage's kernel over every layer's distinct weights (its inputs are whatever an
  *               earlier full call left in the workspace, its outputs are meaningless): the way to
  *               time a kernel on its own without the whole layer fitting a cache.
  *   timer       NULL, or a timer whose stage's launches are to be bracketed by events.
+ *   layer_out   NULL, or device fp32 [n_layers][batch*q_len, hidden]: receives every block's output (a
+ *               device-to-device copy after each block), so that a test can check a deep model block by block.
  * SPD_EINVAL for bits beyond SPD_ALL_STAGES; otherwise as spd_model_forward(). */
 int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
                              const void *const *layer_weights, void *const *layer_kv,
                              const int32_t *positions, int32_t batch, int32_t q_len,
                              const float *x_in, float *slots, float *x_out, void *workspace,
                              void *stream, int64_t *n_rank_sums, uint32_t stage_mask,
-                             spd_stage_timer *timer);
+                             spd_stage_timer *timer, float *layer_out);
 
 /* ---------------------------------------------------------------- the fp16 copy of the weights
  * A bf16 context that takes calls of more than 16 tokens keeps, in every packed shard, a second copy of

@@ -93,7 +93,7 @@ _PROTOS = {
                                     C.c_void_p, C.POINTER(C.c_int64)]),
     "spd_model_forward_staged": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                           C.c_void_p, C.POINTER(C.c_int64), C.c_uint32, C.c_void_p]),
+                                           C.c_void_p, C.POINTER(C.c_int64), C.c_uint32, C.c_void_p, C.c_void_p]),
     "spd_stage_timer_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "spd_stage_timer_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_stage_timer_destroy": (None, [C.c_void_p]),
@@ -350,7 +350,8 @@ def spd_model_forward(ctx: int, spd_mask: Sequence[int], rank: int, layer_weight
 
 def spd_model_forward_staged(ctx: int, spd_mask: Sequence[int], rank: int, layer_weights: Sequence, layer_kv: Sequence,
                              positions: Sequence[int], batch: int, q_len: int, x_in, slots, x_out, workspace,
-                             stage_mask: int = SPD_ALL_STAGES, timer: Optional[int] = None, stream=None) -> int:
+                             stage_mask: int = SPD_ALL_STAGES, timer: Optional[int] = None, stream=None,
+                             layer_out=None) -> int:
     mask = np.ascontiguousarray(spd_mask, dtype=np.uint8)
     n = len(layer_weights)
     wp = (C.c_void_p * n)(*[_ptr(t) for t in layer_weights])
@@ -359,7 +360,7 @@ def spd_model_forward_staged(ctx: int, spd_mask: Sequence[int], rank: int, layer
     _check(lib().spd_model_forward_staged(ctx, mask.ctypes.data, rank, C.cast(wp, C.c_void_p), C.cast(kp, C.c_void_p),
                                           C.cast(_i32(positions), C.c_void_p), batch, q_len, _ptr(x_in), _ptr(slots),
                                           _ptr(x_out), _ptr(workspace), _stream_ptr(stream), C.byref(syncs),
-                                          int(stage_mask), timer),
+                                          int(stage_mask), timer, _ptr(layer_out)),
            "spd_model_forward_staged")
     return syncs.value
 

@@ -203,7 +203,7 @@ int spd_block_forward(const spd_ctx *ctx, int32_t layer, int32_t spd_flag, int32
 int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank, const void *const *layer_weights,
                              void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len,
                              const float *x_in, float *slots, float *x_out, void *workspace, void *stream,
-                             int64_t *n_rank_sums, uint32_t stage_mask, spd_stage_timer *timer) {
+                             int64_t *n_rank_sums, uint32_t stage_mask, spd_stage_timer *timer, float *layer_out) {
     spd_call c;
     const int rc = check_call(ctx, rank, positions, batch, q_len, x_in, slots, x_out, workspace, &c, stream);
     if (rc != SPD_OK) return rc;
@@ -247,6 +247,8 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
         }
         syncs += 1;
         x = x_out;
+        if (layer_out)       // test tap: every block's output
+            SPD_HIP(hipMemcpyAsync(layer_out + (size_t)l * c.M * D.h, x_out, (size_t)c.M * D.h * 4, hipMemcpyDeviceToDevice, c.s));
     }
     if (n_rank_sums) *n_rank_sums = syncs;
     return SPD_OK;
@@ -256,7 +258,7 @@ int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
                       void *const *layer_kv, const int32_t *positions, int32_t batch, int32_t q_len, const float *x_in,
                       float *slots, float *x_out, void *workspace, void *stream, int64_t *n_rank_sums) {
     return spd_model_forward_staged(ctx, spd_mask, rank, layer_weights, layer_kv, positions, batch, q_len, x_in, slots, x_out,
-                                    workspace, stream, n_rank_sums, SPD_ALL_STAGES, nullptr);
+                                    workspace, stream, n_rank_sums, SPD_ALL_STAGES, nullptr, nullptr);
 }
 
 const char *spd_last_hip_error(void) { return g_hip_msg; }

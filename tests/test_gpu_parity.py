@@ -253,17 +253,26 @@ def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
     peers = inputs.peer_slots(w, M) if mode == "one-rank" else np.zeros((w.tp, M, w.hidden), np.float32)
     slots = case.to_dev(peers).reshape(w.tp, M, w.hidden)
     out = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
-    syncs = B.spd_model_forward(case.dev.ctx, w.mask, case.dev.rank_arg(), case.dev.weights, case.dev.kv, positions,
-                                batch, q_len, case.to_dev(X), slots, out, case.dev.workspace)
+    taps = torch.zeros((w.n_layers, M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward_staged(case.dev.ctx, w.mask, case.dev.rank_arg(), case.dev.weights, case.dev.kv,
+                                       positions, batch, q_len, case.to_dev(X), slots, out, case.dev.workspace,
+                                       layer_out=taps)
     torch.cuda.synchronize()
     assert syncs == 4
-    if mode == "all-ranks":
-        want, _ = O.model_all_ranks(case.sh, X, case.shards, case.caches, positions, batch, q_len, w.mask)
-    else:
-        want = O.model_single_rank(case.sh, X, [s[0] for s in case.shards], [c[0] for c in case.caches], positions,
-                                   batch, q_len, w.mask, 1, peers.astype(np.float64))
-    err = assert_close(out.cpu().numpy(), want, w, f"{w.name} {mode}", scale=3.0 if w.dtype == BF16 else 1.0)
-    say(f"  max err {err:.2e} (max |oracle| {np.max(np.abs(want)):.2f})")
+    got = taps.cpu().numpy()
+    assert np.array_equal(got[-1], out.cpu().numpy())
+    # block by block, the oracle's block fed the same input as the library's: the bound as it stands
+    worst = 0.0
+    o_slots = peers.astype(np.float64)
+    for l in range(w.n_layers):
+        x_in = X if l == 0 else got[l - 1]
+        if mode == "all-ranks":
+            want, _ = O.block_all_ranks(case.sh, x_in, case.shards[l], case.caches[l], positions, batch, q_len, w.mask[l])
+        else:
+            want = O.block_single_rank(case.sh, x_in, case.shards[l][0], case.caches[l][0], positions, batch, q_len,
+                                       w.mask[l], 1, o_slots)
+        worst = max(worst, assert_close(got[l], want, w, f"{w.name} {mode} block {l}"))
+    say(f"  worst block max err {worst:.2e}")
     case.close()
 
 
@@ -413,7 +422,8 @@ def test_edge_cases(gpu):
 
 
 # ------------------------------------------------------------------------------------------------
-# full-size shapes, in the launch configuration the bench times (2 layers each: one SPD, one TP)
+# full-size shapes through spd_block_forward (2 layers each: the first as an SPD block, the last as a TP block);
+# the call the bench makes, spd_model_forward at full depth, is checked at the end of this file
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["7b-decode", "13b-decode", "70b-decode", "7b-tp4-decode", "13b-tp4-decode"])
 def test_full_size_decode_shapes(gpu, name):
@@ -508,3 +518,62 @@ def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
     del slots
     case.close()
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------------------
+# the call the bench makes: spd_model_forward at full depth with the workload's own mask
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,n_syncs", [("7b-decode", 32), ("13b-decode", 50), ("70b-decode", 96)])
+def test_full_depth_model_forward(gpu, name, n_syncs):
+    """Rank 0's share of the whole model (32 / 40 / 80 blocks, the workload's mask: all SPD, every 4th
+    block synced, SPD on blocks 8..71) through spd_model_forward, the call the bench times, where each
+    block's closing sync point also prepares the next block's first norm.  Every block's output is
+    compared with the oracle's block fed the same input (2e-2 as it stands); the whole chain is compared
+    with the oracle's own chain relative to the output's rms."""
+    import torch
+    w = workloads.get(name)
+    M, positions = w.batch, [w.ctx - 1] * w.batch
+    say(f"full depth {name}: {w.n_layers} blocks, mask sum {sum(w.mask)}, batch {w.batch}, ctx {w.ctx}")
+    dev = B.DeviceShard(w, [0], gpu)
+    n_pre = w.ctx - 1
+    for l in range(w.n_layers):
+        dev.load_layer(l, [inputs.layer_shard(w, l, 0)])
+        dev.load_kv(l, [inputs.kv_prefill(w, l, 0, w.batch, n_pre)])
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    x, slots = torch.from_numpy(X).to(gpu), torch.from_numpy(peers).to(gpu)
+    out = torch.empty_like(x)
+    taps = torch.zeros((w.n_layers, M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward_staged(dev.ctx, w.mask, 0, dev.weights, dev.kv, positions, w.batch, 1, x, slots, out,
+                                       dev.workspace, layer_out=taps)
+    torch.cuda.synchronize()
+    assert syncs == B.spd_sync_count(dev.ctx, w.mask) == n_syncs
+    got = taps.cpu().numpy()
+    assert np.array_equal(got[-1], out.cpu().numpy())
+    dev.close()
+    del dev, taps
+    torch.cuda.empty_cache()
+
+    sh = oracle_shapes(w)
+    mc = (w.ctx + 31) // 32 * 32
+    o_slots = peers.astype(np.float64)
+    chain = X.astype(np.float64)
+    worst, worst_l = 0.0, -1
+    for l in range(w.n_layers):
+        shard = inputs.layer_shard(w, l, 0)
+        k, v = inputs.kv_prefill(w, l, 0, w.batch, n_pre)
+        cache = O.KVCache(w.batch, w.kv_per_rank, mc, w.head_dim, storage=cache_storage(w))
+        cache.fill(k, v)
+        x_in = X if l == 0 else got[l - 1]
+        want = O.block_single_rank(sh, x_in, shard, cache.copy(), positions, w.batch, 1, int(w.mask[l]), 0, o_slots)
+        err = assert_close(got[l], want, w, f"{name} block {l} (mask {w.mask[l]})")
+        if err > worst:
+            worst, worst_l = err, l
+        chain = O.block_single_rank(sh, chain, shard, cache, positions, w.batch, 1, int(w.mask[l]), 0, o_slots)
+    rms = float(np.sqrt(np.mean(chain ** 2)))
+    e2e = float(np.max(np.abs(got[-1] - chain)))
+    say(f"  worst block {worst_l}: max err {worst:.2e}; end to end: max err {e2e:.2e}, output rms {rms:.2f}, "
+        f"relative {e2e / rms:.2e}")
+    # errors of the blocks add up along the chain (each at most 2e-2, amplified or damped by what follows):
+    # the end-to-end figure is reported relative to the output's rms and bounded by the sum of the per-block bounds
+    assert e2e <= 2e-2 * w.n_layers * max(1.0, rms)

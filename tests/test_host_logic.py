@@ -324,6 +324,35 @@ def test_pack_with_output_bias(w):
     B.spd_destroy(ctx)
 
 
+def test_fp16_copy_of_the_weights_reproduces_them():
+    """A bf16 context that takes calls of more than 16 tokens keeps an fp16 copy round_fp16(2^k w) of the four
+    matrices.  With one power of two per matrix every weight within 2^-29 of the largest is reproduced bit for
+    bit; whatever is smaller lands on fp16's subnormal grid, at most 2^-25 / 2^k = 2^-40 max|w| away."""
+    w = SMALL_BF16
+    ctx = B.spd_create(B.make_config(w, max_tokens=64))
+    shard = inputs.layer_shard(w, 0, 1)
+    diff, big, inexact, n = B.spd_f16_copy_check(ctx, B.spd_pack_shard_local(ctx, shard))
+    assert n >= sum(shard[k].size for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"))
+    assert inexact == 0 and diff == 0.0 and big > 0.0
+    # a dynamic range no fp16 scale can hold: the large entries stay exact, the tiny ones move by < 2^-40 max|w|
+    for k in ("wq", "wd"):
+        a = shard[k]
+        a.flat[0] = np.float32(64.0)
+        a.flat[1] = np.float32(2.0 ** -40)            # a bf16 value 46 binades below the largest
+        a.flat[2] = np.float32(1.5 * 2.0 ** -60)
+    diff, big, inexact, n = B.spd_f16_copy_check(ctx, B.spd_pack_shard_local(ctx, shard))
+    assert big == 64.0 and 1 <= inexact <= 4
+    assert 0.0 < diff <= 2.0 ** -40 * big
+    B.spd_destroy(ctx)
+    # a context for calls of at most 16 tokens keeps no such copy (and its shard is that much smaller)
+    small = B.spd_create(B.make_config(w, max_tokens=16))
+    with pytest.raises(B.SpdError) as e:
+        B.spd_f16_copy_check(small, np.zeros(B.spd_get_sizes(small).weight_bytes, np.uint8))
+    assert e.value.code == B.SPD_EUNSUPPORTED
+    assert B.spd_get_sizes(small).weight_bytes < B.spd_get_sizes(B.spd_create(B.make_config(w, max_tokens=64))).weight_bytes
+    B.spd_destroy(small)
+
+
 def test_pack_rejects_values_that_are_not_bf16():
     w = SMALL_BF16
     ctx = B.spd_create(B.make_config(w))
