@@ -4,18 +4,23 @@
 A step is one pass of one tensor-parallel rank's share of the WHOLE model (every decoder
 block: norm, QKV + rotary + cache append, attention, O projection with the SPD or TP
 residual wiring, norm, SwiGLU MLP, rank-sums) over one batch of synthetic tokens, all
-inputs resident in HBM.  The headline value is microseconds per layer per rank shard with
-the workload's SPD mask; the same model is also timed with every sync point kept.
+inputs resident in HBM, replayed from a HIP graph.
 
-  python bench.py [--workload 70b-decode|7b-decode|13b-decode|70b-prefill] [--steps K] [--warmup W]
+  python bench.py                      the LLaMA2-70B shard: decode (batch 16, context 4096) is the headline
+                                       `value`; the prefill of 4 x 2048 tokens on the same resident model is
+                                       reported beside it in `prefill`
+  python bench.py --workload NAME      one workload only (7b-decode, 13b-decode, 70b-decode, 70b-prefill,
+                                       70b-prefill-128, 7b-tp4-decode, 13b-tp4-decode)
 
-Prints ONE JSON line: metric, value (us per layer of one rank's shard), roofline of the dominant kernel, CPU oracle baseline.
+Prints ONE JSON line: metric, value (us per layer of one rank's shard), roofline of the dominant
+kernel, CPU oracle baseline.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -25,29 +30,66 @@ if ROOT not in sys.path:
 
 import numpy as np
 
-
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (summaries and the copy-kernel calibration are under profiles/); None = not measured.
-# FETCH_SIZE counts 2 KiB per unit on this device (a 1 GiB copy reads 524300), WRITE_SIZE 1 KiB.
-MEASURED_TRAFFIC = {
-    "llama2-70b-tp8-decode-b16-ctx4096": (59518 * 2 + 320) * 1024,        # 122.2 MB vs 117.9 MB algorithmic
-    # the two launches of the stage (256x256 tiles + the half tiles of the last round): 1.59 GB, every XCD's L2
-    # fetching the operand panels of its own tiles
-    "llama2-70b-tp8-prefill-b4x2048": ((614644 + 135299) * 2 + 49152 + 8192) * 1024,
-    # k_mid + k_mid_finish: 206 MB (weights once, 29 MB of K-slice partials written and read back) vs 120.5 MB algorithmic
-    "llama2-70b-tp8-prefill-b1x128": ((67432 + 16676) * 2 + 32256 + 896) * 1024,
-}
+HBM_PEAK = 8.0e12          # B/s, MI355X
+MFMA_PEAK = 2.5e15         # flop/s, dense bf16 / fp16
 
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
-def build_model(w, dev, B, inputs, positions):
-    """Upload every layer's rank-0 shard and a pre-filled KV cache."""
+# ------------------------------------------------------------------------------------------------
+# HBM traffic per launch, read from the committed rocprofv3 counter summary (never typed in here)
+# ------------------------------------------------------------------------------------------------
+def measured_traffic(workload: str, stage: str, kernel: str):
+    """Bytes per launch of `stage` of `workload` from profiles/hbm_traffic__*.txt, or (None, why).
+
+    The summary carries one line per measured stage:
+      TRAFFIC workload=<name> stage=<stage> kernel=<label> fetch=<FETCH_SIZE> write=<WRITE_SIZE> fetch_kib=<f> write_kib=<f>
+    (counter averages per dispatch and what one counter unit is worth, from the copy calibration in the
+    same file).  The figure is only used if the kernel it was measured on is the kernel launched now."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None, "no profiles/ folder"
+    for fn in sorted(os.listdir(pdir)):
+        if not fn.startswith("hbm_traffic") or not fn.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, fn)):
+            if not line.startswith("TRAFFIC "):
+                continue
+            kv = dict(re.findall(r"(\w+)=(\"[^\"]*\"|\S+)", line))
+            kv = {k: v.strip('"') for k, v in kv.items()}
+            if kv.get("workload") != workload or kv.get("stage") != stage:
+                continue
+            if kv.get("kernel") != kernel:
+                return None, f"profiles/{fn} holds {kv.get('kernel')!r} for this stage, the kernel launched is {kernel!r}"
+            b = float(kv["fetch"]) * float(kv["fetch_kib"]) * 1024 + float(kv["write"]) * float(kv["write_kib"]) * 1024
+            return int(b), f"profiles/{fn}"
+    return None, "no TRAFFIC line for this workload and stage"
+
+
+def stage_kernel(w, stage: str) -> str:
+    """Label of the kernel(s) the library launches for `stage` at this call size (mirrors its dispatch)."""
+    M = w.batch * w.q_len
+    f_pairs = (w.ffn_per_rank + 31) // 32 * 32 // 16
+    if stage == "gateup":
+        if M > 512:
+            return "k_gemm_lds<EpiGU<true>,GemmBig,false>+k_gemm_lds<EpiGU<true>,GemmHalf,false>"
+        if M > 16 and f_pairs >= 128:
+            return "k_mid<MT>+k_mid_finish<EpiGU<true>>"
+        if M > 16:
+            return "k_skinny<8,MT,false,0,EpiGU<true>>"
+        if f_pairs >= 192 or (f_pairs >= 64 and f_pairs % 256 != 0):
+            return "k_gemv<16,2,true,0,EpiGU<false>>"            # 16-column tiles, or the decode-only copy with narrow groups
+        return "k_gemv<8,2,true,1,EpiGU<false>>+k_gemv_finish"
+    return stage
+
+
+# ------------------------------------------------------------------------------------------------
+def build_model(w, dev, B, inputs, n_pre, max_tokens=None, max_batch=None, max_ctx=None, act_split=0):
+    """Upload every layer's rank-0 shard and a KV cache pre-filled with n_pre positions."""
     t0 = time.time()
-    shard = B.DeviceShard(w, [0], dev)
-    n_pre = max(positions)
+    shard = B.DeviceShard(w, [0], dev, max_tokens=max_tokens, max_batch=max_batch, max_ctx=max_ctx, act_split=act_split)
     last = t0
     for l in range(w.n_layers):
         shard.load_layer(l, [inputs.layer_shard(w, l, 0)])
@@ -58,75 +100,90 @@ def build_model(w, dev, B, inputs, positions):
             last = time.time()
             log(f"  loaded {l + 1}/{w.n_layers} layers")
     log(f"model resident in HBM after {time.time() - t0:.1f} s "
-        f"({w.n_layers * shard.sizes.weight_bytes / 1e9:.2f} GB weights, "
+        f"({w.n_layers * shard.sizes.weight_bytes / 1e9:.2f} GB packed weights, "
         f"{w.n_layers * shard.sizes.kv_bytes / 1e9:.2f} GB KV cache)")
     return shard
 
 
-def time_forward(torch, B, shard, w, mask, positions, x, slots, out, steps, warmup, use_graph):
-    """Median-free simple protocol: `warmup` untimed steps, then exactly `steps` timed ones."""
-    stream = torch.cuda.current_stream()
+class Runner:
+    """One call shape (workload w) on a resident model."""
 
-    def fwd():
-        return B.spd_model_forward(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots,
-                                   out, shard.workspace)
+    def __init__(self, torch, B, shard, w, x, slots, out, positions):
+        self.torch, self.B, self.shard, self.w = torch, B, shard, w
+        self.x, self.slots, self.out, self.positions = x, slots, out, positions
 
-    graph = None
-    if use_graph:
+    def forward(self, mask, stage_mask=None, timer=None):
+        B, s, w = self.B, self.shard, self.w
+        if stage_mask is None and timer is None:
+            return B.spd_model_forward(s.ctx, mask, 0, s.weights, s.kv, self.positions, w.batch, w.q_len, self.x, self.slots,
+                                       self.out, s.workspace)
+        return B.spd_model_forward_staged(s.ctx, mask, 0, s.weights, s.kv, self.positions, w.batch, w.q_len, self.x,
+                                          self.slots, self.out, s.workspace,
+                                          stage_mask=B.SPD_ALL_STAGES if stage_mask is None else stage_mask, timer=timer)
+
+    def capture(self, fn):
+        torch = self.torch
+        stream = torch.cuda.current_stream()
         side = torch.cuda.Stream()
         side.wait_stream(stream)
         with torch.cuda.stream(side):
-            fwd()                                    # warm the code objects outside the capture
+            fn()                                     # warm the code objects outside the capture
             side.synchronize()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=side):
-                fwd()
+                fn()
         stream.wait_stream(side)
         torch.cuda.synchronize()
-    run = graph.replay if graph is not None else fwd
-    for _ in range(warmup):
-        run()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        run()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    dev_ms = e0.elapsed_time(e1)
-    return max(wall_ms, dev_ms) / steps, dev_ms / steps
+        return graph
 
+    def time_forward(self, mask, steps, warmup, use_graph=True):
+        """`warmup` untimed steps, then exactly `steps` timed ones: (ms per step by max(host, device) clock, device ms)."""
+        torch = self.torch
+        run = self.capture(lambda: self.forward(mask)).replay if use_graph else (lambda: self.forward(mask))
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+        return max(wall_ms, dev_ms) / steps, dev_ms / steps
 
-def stage_time(torch, B, shard, w, mask, positions, x, slots, out, stage, reps):
-    """Average duration of ONE launch of a stage's kernel(s), HIP events on the launch stream.
-
-    The library is told to launch only that stage; one whole-model call then is a train of
-    n_layers launches of the same kernel over every layer's distinct weights (no cache reuse).
-    The train is captured into a HIP graph (no launch gaps) and replayed `reps` times between
-    one pair of events.  Returns (launches, mean microseconds per launch of the stage).
-    """
-    stream = torch.cuda.current_stream()
-    side = torch.cuda.Stream()
-    side.wait_stream(stream)
-    with torch.cuda.stream(side):
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            B.spd_model_forward_staged(shard.ctx, mask, 0, shard.weights, shard.kv, positions, w.batch, w.q_len, x, slots,
-                                       out, shard.workspace, stage_mask=1 << B.STAGES[stage])
-    stream.wait_stream(side)
-    torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
+    def stage_train(self, mask, stage, reps):
+        """Mean duration of one launch of a stage, the stage's kernels following each other over every layer's
+        distinct weights (no cache reuse) in a HIP graph: events on the launch stream around `reps` replays."""
+        torch, B = self.torch, self.B
+        graph = self.capture(lambda: self.forward(mask, stage_mask=1 << B.STAGES[stage]))
         graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    per_launch_us = e0.elapsed_time(e1) * 1e3 / (reps * w.n_layers)
-    return reps * w.n_layers, per_launch_us
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * self.w.n_layers)
+
+    def stage_in_model(self, mask, stage, reps):
+        """Mean duration of the stage's launches inside the full forward: the library brackets every launch of the
+        stage with a pair of HIP events on the launch stream (eager launches: events cannot be captured)."""
+        torch, B = self.torch, self.B
+        timer = B.spd_stage_timer_create(B.STAGES[stage], (self.w.n_layers + 1) * reps)
+        try:
+            self.forward(mask)
+            torch.cuda.synchronize()
+            for _ in range(reps):
+                self.forward(mask, timer=timer)
+            torch.cuda.synchronize()
+            n, mean_us, min_us = B.spd_stage_timer_read(timer)
+        finally:
+            B.spd_stage_timer_destroy(timer)
+        return n, mean_us, min_us
 
 
 def algorithmic_work(w):
@@ -185,12 +242,89 @@ def cpu_baseline(w, inputs, positions, X, peers, budget_s=20.0):
         else:
             break                                   # sampled rows cannot feed the next layer
     us = float(np.mean(per_layer)) * 1e6
-    scale = 1.0
     if rows is not None:
-        # the sampled rows cost (rows / tokens) of the per-token work; report the measured time only
         sample += "; time is for the sample, not extrapolated"
-    return dict(value=us * scale, unit="us/layer", cores=int(cores), kind="oracle",
+    return dict(value=us, unit="us/layer", cores=int(cores), kind="oracle",
                 sample=f"rank 0, first {done} layer(s) of {w.name}, {sample}")
+
+
+def measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph=True, synced=True, cpu=True, cpu_budget=20.0):
+    """Everything reported for one call shape on a resident model."""
+    prefill = w.q_len > 1
+    M = w.batch * w.q_len
+    positions = [w.ctx - w.q_len] * w.batch
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    x = torch.from_numpy(X).to(dev)
+    slots = torch.from_numpy(peers).to(dev)
+    out = torch.empty_like(x)
+    r = Runner(torch, B, shard, w, x, slots, out, positions)
+    log(f"workload {w.name}: {w.n_layers} layers, M={M} tokens, ctx {w.ctx}, SPD layers {sum(w.mask)}/{w.n_layers}")
+
+    ms, dev_ms = r.time_forward(w.mask, steps, warmup, use_graph)
+    us_layer = ms * 1e3 / w.n_layers
+    log(f"  mask as given: {ms:.3f} ms/step -> {us_layer:.2f} us/layer")
+    res = dict(workload=w.name, us_per_layer=us_layer, ms_per_step=ms, device_ms_per_step=dev_ms,
+               tokens_per_s=M / (ms * 1e-3), steps=steps, warmup=warmup)
+    if synced:
+        ms_tp, _ = r.time_forward(tuple([0] * w.n_layers), steps, warmup, use_graph)
+        res["us_per_layer_all_synced"] = ms_tp * 1e3 / w.n_layers
+        ones = tuple([1] * w.n_layers)
+        if tuple(w.mask) != ones:
+            ms_all, _ = r.time_forward(ones, steps, warmup, use_graph)
+            res["us_per_layer_all_spd"] = ms_all * 1e3 / w.n_layers
+        else:
+            res["us_per_layer_all_spd"] = us_layer
+        log(f"  all sync points kept: {res['us_per_layer_all_synced']:.2f} us/layer; all SPD: {res['us_per_layer_all_spd']:.2f} us/layer")
+
+    work = algorithmic_work(w)
+    reps = 3 if prefill else 10
+    train, inmodel = {}, {}
+    for st in ("gateup", "down", "qkv", "attn", "o", "prep"):
+        train[st] = round(r.stage_train(w.mask, st, reps if st == "gateup" else max(1, reps // 2)), 2)
+        n, mean_us, min_us = r.stage_in_model(w.mask, st, 2)
+        inmodel[st] = dict(mean_us=round(mean_us, 2), min_us=round(min_us, 2), launches=n)
+    log(f"  us per launch, stage following itself under a HIP graph: {train}")
+    log(f"  us per launch inside the full forward (eager, HIP events): { {k: v['mean_us'] for k, v in inmodel.items()} }")
+
+    # dominant kernel: the gate/up projection + SwiGLU (55 % of the weights, 55 % of the flops); its duration is the
+    # one measured inside the full forward
+    g = inmodel["gateup"]
+    mean_us = g["mean_us"]
+    kernel = stage_kernel(w, "gateup")
+    if M > 512:      # a dense contraction bound by the matrix cores
+        roof = dict(bound="mfma", achieved=work["gateup"]["flops"] / (mean_us * 1e-6) / 1e12, peak=MFMA_PEAK / 1e12,
+                    unit="TFLOP/s")
+    else:            # bound by streaming its weights once from HBM
+        roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=HBM_PEAK / 1e9, unit="GB/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    traffic, src = measured_traffic(w.name, "gateup", kernel)
+    roof.update(traffic=traffic, traffic_source=src, kernel=kernel, stage="gate/up projection + SwiGLU",
+                launches_timed=g["launches"], mean_us=mean_us, min_us=g["min_us"], mean_us_train=train["gateup"],
+                timing="HIP events around every launch of the stage inside the full eager forward; mean_us_train: the "
+                       "stage following itself over all layers in a HIP graph",
+                algorithmic_bytes_per_launch=work["gateup"]["bytes"], algorithmic_flops_per_launch=work["gateup"]["flops"])
+    res["roofline"] = roof
+    res["stage_us_in_model"] = {k: v["mean_us"] for k, v in inmodel.items()}
+    res["stage_us_train"] = train
+    res["whole_layer"] = dict(hbm_GBps=work["bytes"] / (us_layer * 1e-6) / 1e9, hbm_frac=work["bytes"] / (us_layer * 1e-6) / HBM_PEAK,
+                              mfma_TFLOPs=work["flops"] / (us_layer * 1e-6) / 1e12,
+                              mfma_frac=work["flops"] / (us_layer * 1e-6) / MFMA_PEAK,
+                              algorithmic_bytes_per_layer=work["bytes"], algorithmic_flops_per_layer=work["flops"])
+    res["cpu_baseline"] = None
+    if cpu:
+        log("  timing the CPU oracle on a bounded sample ...")
+        res["cpu_baseline"] = cpu_baseline(w, inputs, positions, X, peers, budget_s=cpu_budget)
+        log(f"  oracle: {res['cpu_baseline']['value']:.0f} us/layer on {res['cpu_baseline']['cores']} threads")
+    del x, slots, out
+    return res
+
+
+def config_of(w, use_graph):
+    return {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_len": w.q_len, "ctx": w.ctx,
+            "tp_degree": w.tp, "rank": 0, "spd_layers": int(sum(w.mask)), "launch": "hip-graph" if use_graph else "eager",
+            "operands": "bf16 (MLP inputs as hi+lo pairs)" if w.batch * w.q_len <= 16
+                        else "fp16 activations and fp16-encoded bf16 weights, QKV input as hi+lo pair (act_split AUTO)"}
 
 
 def main():
@@ -198,12 +332,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="70b-decode")
+    ap.add_argument("--workload", default=None, help="one workload only (default: 70B decode headline + 70B prefill)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers than the workload names")
     ap.add_argument("--batch", type=int, default=None, help="exploration: another number of sequences than the workload names")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-synced", action="store_true", help="skip the all-sync-points-kept run")
+    ap.add_argument("--act-split", choices=["auto", "always", "never"], default="auto",
+                    help="exploration: which projection inputs are hi+lo pairs (spd_config.act_split); the figures of "
+                         "record are those of the default, auto")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain copy of MIB MiB (spd_rank_sum with one slot, no base) 10 times: the reference "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -229,106 +366,69 @@ def main():
         print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "bytes_read": n * 4, "bytes_written": n * 4,
                           "kernel": "k_rank_sum4", "launches": 10}))
         return
-    w = workloads.get(args.workload)
-    if args.layers:
-        w = w.with_layers(args.layers)
-    if args.batch:
-        from dataclasses import replace
-        w = replace(w, batch=args.batch, name=f"{w.name}+batch{args.batch}")
-    prefill = w.q_len > 1
-    steps = args.steps if args.steps is not None else (5 if prefill else 50)
-    warmup = args.warmup if args.warmup is not None else (2 if prefill else 10)
+
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()
-    positions = [w.ctx - w.q_len] * w.batch
-    M = w.batch * w.q_len
-    log(f"workload {w.name}: {w.n_layers} layers, M={M} tokens, ctx {w.ctx}, SPD layers {sum(w.mask)}/{w.n_layers}")
-
-    shard = build_model(w, dev, B, inputs, positions)
-    X = inputs.hidden_states(w, M)
-    peers = inputs.peer_slots(w, M)
-    x = torch.from_numpy(X).to(dev)
-    slots = torch.from_numpy(peers).to(dev)
-    out = torch.empty_like(x)
-
     use_graph = not args.no_graph
-    ms_spd, dev_ms_spd = time_forward(torch, B, shard, w, w.mask, positions, x, slots, out, steps, warmup, use_graph)
-    us_layer = ms_spd * 1e3 / w.n_layers
-    log(f"mask as given: {ms_spd:.3f} ms/step -> {us_layer:.2f} us/layer")
+
+    def shaped(w):
+        if args.layers:
+            w = w.with_layers(args.layers)
+        if args.batch:
+            from dataclasses import replace
+            w = replace(w, batch=args.batch, name=f"{w.name}+batch{args.batch}")
+        return w
+
+    def steps_of(w):
+        prefill = w.q_len > 1
+        return (args.steps if args.steps is not None else (5 if prefill else 50),
+                args.warmup if args.warmup is not None else (2 if prefill else 10))
+
     extra = {}
-    if not args.no_synced:
-        zero = tuple([0] * w.n_layers)
-        ms_tp, _ = time_forward(torch, B, shard, w, zero, positions, x, slots, out, steps, warmup, use_graph)
-        extra["us_per_layer_all_synced"] = ms_tp * 1e3 / w.n_layers
-        ones = tuple([1] * w.n_layers)
-        if tuple(w.mask) != ones:
-            ms_all, _ = time_forward(torch, B, shard, w, ones, positions, x, slots, out, steps, warmup, use_graph)
-            extra["us_per_layer_all_spd"] = ms_all * 1e3 / w.n_layers
-        else:
-            extra["us_per_layer_all_spd"] = us_layer
-        log(f"all sync points kept: {extra['us_per_layer_all_synced']:.2f} us/layer; "
-            f"all SPD: {extra['us_per_layer_all_spd']:.2f} us/layer")
-
-    work = algorithmic_work(w)
-    # dominant kernel: the gate/up projection + SwiGLU (55 % of the weights, 55 % of the flops)
-    reps = 3 if prefill else 10
-    n, mean_us = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, "gateup", reps)
-    M_tok = w.batch * w.q_len
-    # beyond 512 tokens the projection is a dense contraction bound by the MFMA pipes (arithmetic intensity
-    # ~ M flop per weight byte); up to there it is bound by streaming its weights once from HBM
-    if M_tok > 512:
-        roof = dict(bound="mfma", achieved=work["gateup"]["flops"] / (mean_us * 1e-6) / 1e12, peak=2500.0,
-                    unit="TFLOP/s")
+    if args.workload:
+        w = shaped(workloads.get(args.workload))
+        shard = build_model(w, dev, B, inputs, n_pre=w.ctx - w.q_len,
+                            act_split={"auto": B.SPD_SPLIT_AUTO, "always": B.SPD_SPLIT_ALWAYS, "never": B.SPD_SPLIT_NEVER}[args.act_split])
+        steps, warmup = steps_of(w)
+        head = measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph, not args.no_synced, not args.no_cpu)
     else:
-        roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=8000.0, unit="GB/s")
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get(w.name)
-    if M_tok > 512:
-        roof["kernel"] = "k_gemm_lds<EpiGU,GemmBig> (+ GemmHalf for a ragged last round of tiles)"
-    elif M_tok > 16 and w.ffn_per_rank // 16 >= 128:
-        roof["kernel"] = "k_mid<MT> + k_mid_finish<EpiGU>"      # the stage is these two launches
-    elif M_tok > 16:
-        roof["kernel"] = "k_skinny<8,MT,*,0,EpiGU>"
-    elif w.ffn_per_rank // 16 >= 192:
-        roof["kernel"] = "k_gemv<16,2,split,0,EpiGU>"
-    else:
-        roof["kernel"] = "k_gemv<8,2,split,1,EpiGU> + k_gemv_finish<EpiGU>"
-    roof["stage"] = "gate/up projection + SwiGLU"
-    roof["launches_timed"] = n
-    roof["mean_us"] = mean_us
-    roof["algorithmic_bytes_per_launch"] = work["gateup"]["bytes"]
-    roof["algorithmic_flops_per_launch"] = work["gateup"]["flops"]
-    stages = {"gateup": round(mean_us, 2)}
-    for st in ("prep", "qkv", "attn", "o", "down"):
-        _, m_us = stage_time(torch, B, shard, w, w.mask, positions, x, slots, out, st, max(1, reps // 2))
-        stages[st] = round(m_us, 2)
-    log(f"mean us per launch of each stage (single-stage launch trains under a HIP graph): {stages}")
+        # one resident LLaMA2-70B shard serves both call shapes: decode first (its cache pre-filled with 4095 positions
+        # of 16 sequences), then the prefill of 4 x 2048 tokens, which overwrites the head of four of those caches
+        w = shaped(workloads.get("70b-decode"))
+        wp = workloads.get("70b-prefill").with_layers(w.n_layers)
+        shard = build_model(w, dev, B, inputs, n_pre=w.ctx - 1, max_tokens=wp.batch * wp.q_len,
+                            max_batch=max(w.batch, wp.batch), max_ctx=max(w.ctx, wp.ctx))
+        steps, warmup = steps_of(w)
+        head = measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph, not args.no_synced, not args.no_cpu)
+        psteps, pwarm = steps_of(wp)
+        pre = measure(torch, B, inputs, shard, wp, dev, psteps, pwarm, use_graph, not args.no_synced, not args.no_cpu,
+                      cpu_budget=10.0)
+        pre["metric"] = "us_per_layer_per_tp_rank_shard"
+        pre["unit"] = "us/layer"
+        pre["value"] = pre["us_per_layer"]
+        pre["dtype"] = "f16"
+        pre["config"] = config_of(wp, use_graph)
+        pre["target"] = "north star: >= 50 % MFMA utilisation over the layer (whole_layer.mfma_frac), i.e. <= 1430 us/layer"
+        extra["prefill"] = pre
 
-    whole = dict(hbm_GBps=work["bytes"] / (us_layer * 1e-6) / 1e9, hbm_frac=work["bytes"] / (us_layer * 1e-6) / 8e12,
-                 mfma_TFLOPs=work["flops"] / (us_layer * 1e-6) / 1e12,
-                 mfma_frac=work["flops"] / (us_layer * 1e-6) / 2.5e15,
-                 algorithmic_bytes_per_layer=work["bytes"], algorithmic_flops_per_layer=work["flops"])
-
-    cpu = None
-    if not args.no_cpu:
-        log("timing the CPU oracle on a bounded sample ...")
-        cpu = cpu_baseline(w, inputs, positions, X, peers)
-        log(f"oracle: {cpu['value']:.0f} us/layer on {cpu['cores']} threads")
-
-    tokens_per_s = M / (ms_spd * 1e-3)
+    M = w.batch * w.q_len
     line = {
-        "metric": "us_per_layer_per_tp_rank_shard", "value": us_layer, "unit": "us/layer", "n_gpus": 1,
-        "steps": steps, "warmup": warmup, "ms_per_step": ms_spd, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16" if w.dtype == 1 else "f32", "data": "synthetic",
-        "config": {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_len": w.q_len, "ctx": w.ctx,
-                   "tp_degree": w.tp, "rank": 0, "spd_layers": int(sum(w.mask)), "launch": "hip-graph" if use_graph else "eager"},
-        "tokens_per_s": tokens_per_s, "device_ms_per_step": dev_ms_spd,
-        "whole_layer": whole, "stage_us": stages, "roofline": roof, "cpu_baseline": cpu,
+        "metric": "us_per_layer_per_tp_rank_shard", "value": head["us_per_layer"], "unit": "us/layer", "n_gpus": 1,
+        "steps": head["steps"], "warmup": head["warmup"], "ms_per_step": head["ms_per_step"], "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": ("bf16" if M <= 16 else "f16") if w.dtype == 1 else "f32", "data": "synthetic",
+        "config": config_of(w, use_graph),
+        "tokens_per_s": head["tokens_per_s"], "device_ms_per_step": head["device_ms_per_step"],
+        "whole_layer": head["whole_layer"], "stage_us": head["stage_us_in_model"], "stage_us_train": head["stage_us_train"],
+        "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
         "paper_context": "paper reports ~20% end-to-end latency reduction at <1% accuracy loss for LLaMA2-70B on 8 GPUs "
                          "(other hardware; not comparable to a per-layer shard time)",
     }
+    for k in ("us_per_layer_all_synced", "us_per_layer_all_spd"):
+        if k in head:
+            line[k] = head[k]
     line.update(extra)
     print(json.dumps(line), flush=True)
     shard.close()
