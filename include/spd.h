@@ -52,7 +52,10 @@ extern "C" {
 #endif
 
 #define SPD_F32 0   /* weights, KV cache and activations fp32; plain reference-style kernels */
-#define SPD_BF16 1  /* weights, KV cache and inter-kernel activations bf16; fp32 accumulation */
+#define SPD_BF16 1  /* bf16 weights and bf16 KV cache, fp32 accumulation, fp32 residual stream.  The projections run on the
+                       matrix cores with fp16 operands: the packed shard holds each bf16 weight w as fp16(2^k w), one power
+                       of two per matrix (an exact re-encoding for every weight within 2^-29 of its matrix's largest), and
+                       activations between kernels are fp16; attention contracts bf16 */
 
 #define SPD_OK 0
 #define SPD_EINVAL (-1)       /* NULL pointer, bad shape, rank, batch, position or mask value */
@@ -81,11 +84,12 @@ typedef struct spd_config {
     int32_t o_bias;      /* 1: the attention output projection has a bias (block with bias, Sec. 4.1.2); else 0 */
 } spd_config;
 
-/* bf16 MFMA needs bf16 activations.  With "split" activations every activation that feeds a
- * projection is kept as a pair hi + lo of bf16 values (lo = the rounding error of hi) and the
- * contraction runs over both, which removes the activation rounding from the result at the
- * price of twice the MFMA work.  AUTO splits calls of at most 16 tokens, where the
- * projections are bound by weight streaming and the extra MFMA work is free. */
+/* SPD_BF16 only.  An activation that feeds a projection is rounded to fp16 (11 significant bits).  A "split"
+ * activation is kept as a pair hi + lo of fp16 values (lo = the rounding error of hi) and the contraction
+ * runs over both, which removes that rounding from the result at the price of a second pass over the
+ * matrix cores.  AUTO splits the one input whose rounding shows at the block output: the QKV
+ * projection's in calls of more than 16 tokens (a prefill attends to keys it produces itself; the softmax
+ * amplifies errors of q and k).  ALWAYS splits every projection input, NEVER none. */
 #define SPD_SPLIT_AUTO 0
 #define SPD_SPLIT_ALWAYS 1
 #define SPD_SPLIT_NEVER 2
@@ -104,7 +108,8 @@ typedef struct spd_sizes {
  * (unsharded) matrices: wq [h, Hq*d], wk/wv [h, Hkv*d], wo [Hq*d, h], wg/wu [h, F],
  * wd [F, h]; for spd_pack_shard_local() they are one rank's slices.  g1/g2 [h] are the
  * gains of the two RMSNorms.  With dtype SPD_BF16 every weight must already be exactly
- * representable in bf16 (the packer copies values, it never rounds). */
+ * representable in bf16 (SPD_EINVAL otherwise): the packer re-encodes values, it does not round them
+ * (only a weight more than 2^29 times smaller than its matrix's largest moves, by < 2^-39 of that largest). */
 typedef struct spd_layer_weights {
     const float *wq, *wk, *wv, *wo, *wg, *wu, *wd, *g1, *g2;
     int64_t ld_q, ld_k, ld_v, ld_o, ld_g, ld_u, ld_d;
@@ -175,7 +180,7 @@ int spd_mask_from_sensitivity(const double *sensitivity, int32_t n_layers, int32
 
 /* ---------------------------------------------------------------- packing (host only)
  * Slices rank `rank`'s heads / FFN columns out of the dense layer and lays them out the
- * way the kernels stream them (bit-exact copies of the values, zero padding only).
+ * way the kernels stream them (the values themselves, re-encoded as described at SPD_BF16; zero padding only).
  * `packed_host` receives weight_bytes bytes; the caller then copies them to the device. */
 int spd_pack_shard(const spd_ctx *ctx, int32_t rank, const spd_layer_weights *dense, void *packed_host);
 /* Same after head grouping (Sec. 4.2.3, Fig. 5): the heads are laid over the devices in the

@@ -55,15 +55,6 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
                              void *stream, int64_t *n_rank_sums, uint32_t stage_mask,
                              spd_stage_timer *timer, float *layer_out);
 
-/* ---------------------------------------------------------------- the fp16 copy of the weights
- * A bf16 context that takes calls of more than 16 tokens keeps, in every packed shard, a second copy of
- * the four projection matrices as round_fp16(2^k w), one power of two per matrix (see spd_config.act_split).
- * For a packed shard on the host: the largest |w - 2^-k w16| over all weights, the largest |w|, how many
- * weights are not reproduced exactly and how many there are (any pointer may be NULL).  Host only.
- * SPD_EUNSUPPORTED if the context keeps no such copy (fp32, or max_tokens <= 16). */
-int spd_f16_copy_check(const spd_ctx *ctx, const void *packed_host, double *max_abs_diff, double *max_abs_weight,
-                       int64_t *n_inexact, int64_t *n_weights);
-
 /* ---------------------------------------------------------------- launch order of the GEMM tiles
  * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
  * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number

@@ -97,8 +97,6 @@ _PROTOS = {
     "spd_stage_timer_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "spd_stage_timer_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_stage_timer_destroy": (None, [C.c_void_p]),
-    "spd_f16_copy_check": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
-                                     C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
     "spd_gemm_launch_size": (C.c_int, [C.c_int32]),
     "spd_gemm_tile_of": (C.c_int, [C.c_int32] * 7 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
 }
@@ -380,14 +378,6 @@ def spd_stage_timer_read(timer: int):
 
 def spd_stage_timer_destroy(timer: int) -> None:
     lib().spd_stage_timer_destroy(timer)
-
-
-def spd_f16_copy_check(ctx: int, packed: np.ndarray):
-    """(max |w - w16|, max |w|, weights not reproduced exactly, weights) of a packed shard on the host."""
-    d, m, a, b = C.c_double(), C.c_double(), C.c_int64(), C.c_int64()
-    _check(lib().spd_f16_copy_check(ctx, packed.ctypes.data, C.byref(d), C.byref(m), C.byref(a), C.byref(b)),
-           "spd_f16_copy_check")
-    return d.value, m.value, a.value, b.value
 
 
 def spd_gemm_launch_size(n_tiles: int) -> int:

@@ -50,13 +50,11 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     {
         const bool bf = D.dtype == SPD_BF16;
         const bool always = bf && ctx->cfg.act_split == SPD_SPLIT_ALWAYS, automatic = bf && ctx->cfg.act_split == SPD_SPLIT_AUTO;
-        c->f16 = bf && c->M > SPD_AUTO_SPLIT_TOKENS;
-        // AUTO: up to 16 tokens the MLP's inputs are pairs (bound by weight streaming, the second pass is free);
-        // beyond, the fp16 activations are precise enough except the QKV projection's input, whose rounding is
-        // amplified by the softmax
-        c->sp_x = always || (automatic && c->f16);
+        // AUTO: fp16 activations are precise enough everywhere except the QKV projection's input in calls that
+        // attend to keys they produce themselves (prefill), where the softmax amplifies its rounding
+        c->sp_x = always || (automatic && c->M > SPD_AUTO_SPLIT_TOKENS);
         c->sp_a = always;
-        c->sp_m = always || (automatic && !c->f16);
+        c->sp_m = always;
     }
     c->nch1 = 0;
     std::memset(&c->pos, 0, sizeof(c->pos));

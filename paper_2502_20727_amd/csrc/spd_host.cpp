@@ -111,6 +111,7 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     D.w_g2 = o; o = spd_align256(o + h * 4);
     D.o_bias = c.o_bias;
     if (c.o_bias) { D.w_bo = o; o = spd_align256(o + h * 4); }
+    if (bf) { D.w_scale = o; o = spd_align256(o + 4 * 4); }
     D.w_qkv = o; o = spd_align256(o + h * (size_t)D.nqkv * es);
     D.w_o = o; o = spd_align256(o + qd * h * es);
     D.w_g = o; o = spd_align256(o + h * f * es);
@@ -132,16 +133,6 @@ void compute_dims(const spd_config &c, spd_dims &D) {
             D.w_gud = o;
             o = spd_align256(o + (size_t)D.gud_groups * (h / 32) * 2 * 64 * c);
         }
-    }
-    // Calls of more than 16 tokens contract fp16 operands: a second copy of the four matrices, in the same
-    // fragment order, holds round_fp16(2^k w) with one k per matrix and layer, next to the four factors 2^-k
-    if (bf && c.max_tokens > SPD_AUTO_SPLIT_TOKENS) {
-        D.has16 = 1;
-        D.w16_scale = o; o = spd_align256(o + 4 * 4);
-        D.w16_qkv = o; o = spd_align256(o + h * (size_t)D.nqkv * 2);
-        D.w16_o = o; o = spd_align256(o + qd * h * 2);
-        D.w16_g = o; o = spd_align256(o + 2 * h * f * 2);
-        D.w16_d = o; o = spd_align256(o + f * h * 2);
     }
     D.weight_bytes = o;
 
@@ -179,17 +170,37 @@ void compute_dims(const spd_config &c, spd_dims &D) {
     D.workspace_bytes = o;
 }
 
-// One packed bf16 matrix: n_tiles x k_tiles fragments.  `src(k, tile, r)` returns the fp32
-// value of contraction index k for row r of tile `tile` (0 where padded).
+// Power of two k for a matrix whose largest magnitude is mx: the largest k with mx 2^k < 2^15 (half of
+// fp16's range), clamped to what ldexp of a float can undo.
+inline int f16_shift(float mx) {
+    if (!(mx > 0.f) || !std::isfinite(mx)) return 0;
+    int e;
+    std::frexp(mx, &e);                       // mx = m 2^e, m in [0.5, 1)
+    int k = 15 - e;
+    if (k > 60) k = 60;
+    if (k < -60) k = -60;
+    return k;
+}
+
+// One packed matrix: n_tiles x k_tiles fragments of fp16 elements round_fp16(2^k w).  `src(k, tile, r)`
+// returns the fp32 value of contraction index k for row r of tile `tile` (0 where padded); it must be a
+// bf16 value (the packer copies values, it never rounds one that fp16 can hold: bf16's 8 significant bits
+// fit fp16's 11 for every weight within 2^-29 of the matrix's largest; smaller ones land on the subnormal
+// grid, at most 2^-25 / 2^k away).
 template <class Src>
-bool pack_frags(uint16_t *dst, int n_tiles, int k_tiles, Src src) {
+bool pack_frags(uint16_t *dst, int n_tiles, int k_tiles, int shift, Src src) {
+    const float up = std::ldexp(1.0f, shift);
     std::vector<int> bad(n_tiles, 0);
     parallel_for(n_tiles, [&](int nt) {
+        uint16_t scratch;
         for (int kt = 0; kt < k_tiles; ++kt) {
             uint16_t *fr = dst + spd_frag_index(nt, kt, k_tiles);
             for (int c = 0; c < 32; ++c)
-                for (int r = 0; r < 16; ++r)
-                    if (!to_bf16_exact(src(kt * 32 + c, nt, r), &fr[spd_frag_elem(r, c)])) bad[nt] = 1;
+                for (int r = 0; r < 16; ++r) {
+                    const float v = src(kt * 32 + c, nt, r);
+                    if (!to_bf16_exact(v, &scratch)) bad[nt] = 1;
+                    fr[spd_frag_elem(r, c)] = to_f16(v * up);
+                }
         }
     });
     for (int b : bad)
@@ -197,39 +208,23 @@ bool pack_frags(uint16_t *dst, int n_tiles, int k_tiles, Src src) {
     return true;
 }
 
-// The fp16 copy of a packed bf16 matrix, fragment by fragment (same order): element = round_fp16(2^k w).
-// k is the largest power of two that keeps the matrix's largest magnitude at or below 2^15 (half of fp16's
-// range), which puts bf16's 8 significant bits of every weight down to 2^-29 of that largest magnitude inside
-// fp16's 11; smaller weights land on fp16's subnormal grid (error at most 2^-25 / 2^k).  Returns 2^-k.
-float pack_f16_copy(uint16_t *dst, const uint16_t *src_bf16, size_t n_elems) {
-    float mx = 0.f;
-    for (size_t i = 0; i < n_elems; ++i) mx = std::max(mx, std::fabs(from_bf16(src_bf16[i])));
-    int k = 0;
-    if (mx > 0.f && std::isfinite(mx)) {
-        int e;
-        std::frexp(mx, &e);                       // mx = m 2^e, m in [0.5, 1)
-        k = 15 - e;                               // mx 2^k < 2^15
-        if (k > 60) k = 60;
-        if (k < -60) k = -60;
-    }
-    const float up = std::ldexp(1.0f, k);
-    const int chunks = (int)((n_elems + 65535) / 65536);
-    parallel_for(chunks, [&](int ch) {
-        const size_t a = (size_t)ch * 65536, b = std::min(n_elems, a + 65536);
-        for (size_t i = a; i < b; ++i) dst[i] = to_f16(from_bf16(src_bf16[i]) * up);
-    });
-    return std::ldexp(1.0f, -k);
-}
-
 template <class Dst>
-void unpack_frags(const uint16_t *srcp, int n_tiles, int k_tiles, Dst dst) {
+void unpack_frags(const uint16_t *srcp, int n_tiles, int k_tiles, float down, Dst dst) {
     parallel_for(n_tiles, [&](int nt) {
         for (int kt = 0; kt < k_tiles; ++kt) {
             const uint16_t *fr = srcp + spd_frag_index(nt, kt, k_tiles);
             for (int c = 0; c < 32; ++c)
-                for (int r = 0; r < 16; ++r) dst(kt * 32 + c, nt, r, from_bf16(fr[spd_frag_elem(r, c)]));
+                for (int r = 0; r < 16; ++r) dst(kt * 32 + c, nt, r, from_f16(fr[spd_frag_elem(r, c)]) * down);
         }
     });
+}
+
+// largest magnitude of a [rows, cols] matrix with row stride ld
+float max_abs(const float *p, int rows, int cols, int64_t ld) {
+    float mx = 0.f;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) mx = std::max(mx, std::fabs(p[(size_t)r * ld + c]));
+    return mx;
 }
 
 bool weights_ok(const spd_layer_weights *w) {
@@ -389,26 +384,35 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
         return SPD_OK;
     }
     bool ok = true;
+    // one power of two per matrix (the three parts of QKV share one, gate and up share one)
+    const int k_qkv = f16_shift(std::max(max_abs(w->wq, h, qd, w->ld_q), std::max(max_abs(w->wk, h, kvd, w->ld_k), max_abs(w->wv, h, kvd, w->ld_v))));
+    const int k_o = f16_shift(max_abs(w->wo, qd, h, w->ld_o));
+    const int k_gu = f16_shift(std::max(max_abs(w->wg, h, f, w->ld_g), max_abs(w->wu, h, f, w->ld_u)));
+    const int k_d = f16_shift(max_abs(w->wd, f, h, w->ld_d));
+    float *sc = (float *)(base + D.w_scale);
+    sc[0] = std::ldexp(1.0f, -k_qkv); sc[1] = std::ldexp(1.0f, -k_o); sc[2] = std::ldexp(1.0f, -k_gu); sc[3] = std::ldexp(1.0f, -k_d);
     // QKV: contraction = hidden, tiles in the rotary-interleaved order
-    ok &= pack_frags((uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, [&](int k, int nt, int r) {
+    ok &= pack_frags((uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, k_qkv, [&](int k, int nt, int r) {
         const int c = spd_qkv_tile_col0(nt, q, kv, d) + r;
         if (c < qd) return w->wq[(size_t)k * w->ld_q + c];
         if (c < qd + kvd) return w->wk[(size_t)k * w->ld_k + (c - qd)];
         return w->wv[(size_t)k * w->ld_v + (c - qd - kvd)];
     });
     // O: contraction = the rank's q*d attention features
-    ok &= pack_frags((uint16_t *)(base + D.w_o), h / 16, qd / 32,
+    ok &= pack_frags((uint16_t *)(base + D.w_o), h / 16, qd / 32, k_o,
                      [&](int k, int nt, int r) { return w->wo[(size_t)k * w->ld_o + nt * 16 + r]; });
     // gate/up: even tiles gate, odd tiles up, same 16 columns; columns >= f are zero padding
-    ok &= pack_frags((uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, [&](int k, int nt, int r) {
+    ok &= pack_frags((uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, k_gu, [&](int k, int nt, int r) {
         const int c = (nt >> 1) * 16 + r;
         if (c >= f) return 0.0f;
         return (nt & 1) ? w->wu[(size_t)k * w->ld_u + c] : w->wg[(size_t)k * w->ld_g + c];
     });
     if (D.gud_cols) {
         const int c = D.gud_cols, KT = h / 32;
+        const float up = std::ldexp(1.0f, k_gu);
         std::vector<int> bad(D.gud_groups, 0);
         parallel_for(D.gud_groups, [&](int p) {
+            uint16_t scratch;
             for (int kt = 0; kt < KT; ++kt)
                 for (int t = 0; t < 2; ++t) {
                     uint16_t *fr = (uint16_t *)(base + D.w_gud) + (((size_t)p * KT + kt) * 2 + t) * (size_t)(32 * c);
@@ -417,7 +421,8 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
                             for (int j = 0; j < 8; ++j) {
                                 const int col = p * c + r, k = kt * 32 + g * 8 + j;
                                 const float v = col >= f ? 0.0f : (t ? w->wu[(size_t)k * w->ld_u + col] : w->wg[(size_t)k * w->ld_g + col]);
-                                if (!to_bf16_exact(v, &fr[(g * c + r) * 8 + j])) bad[p] = 1;
+                                if (!to_bf16_exact(v, &scratch)) bad[p] = 1;
+                                fr[(g * c + r) * 8 + j] = to_f16(v * up);
                             }
                 }
         });
@@ -425,18 +430,10 @@ int spd_pack_shard_local(const spd_ctx *ctx, const spd_layer_weights *w, void *p
             if (b) ok = false;
     }
     // down: contraction = the rank's FFN slice (zero rows where padded)
-    ok &= pack_frags((uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r) {
+    ok &= pack_frags((uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, k_d, [&](int k, int nt, int r) {
         return k < f ? w->wd[(size_t)k * w->ld_d + nt * 16 + r] : 0.0f;
     });
-    if (!ok) return SPD_EINVAL;        // a weight that is not a bf16 value
-    if (D.has16) {
-        float *sc = (float *)(base + D.w16_scale);
-        sc[0] = pack_f16_copy((uint16_t *)(base + D.w16_qkv), (const uint16_t *)(base + D.w_qkv), (size_t)h * D.nqkv);
-        sc[1] = pack_f16_copy((uint16_t *)(base + D.w16_o), (const uint16_t *)(base + D.w_o), (size_t)qd * h);
-        sc[2] = pack_f16_copy((uint16_t *)(base + D.w16_g), (const uint16_t *)(base + D.w_g), (size_t)2 * h * D.f_pad);
-        sc[3] = pack_f16_copy((uint16_t *)(base + D.w16_d), (const uint16_t *)(base + D.w_d), (size_t)D.f_pad * h);
-    }
-    return SPD_OK;
+    return ok ? SPD_OK : SPD_EINVAL;   // a weight that is not a bf16 value
 }
 
 static bool is_permutation(const int32_t *p, int n) {
@@ -522,21 +519,22 @@ int spd_unpack_shard(const spd_ctx *ctx, const void *packed_host, const spd_laye
             std::memcpy(wd + (size_t)k * o->ld_d, (const float *)(base + D.w_d) + (size_t)k * h, (size_t)h * 4);
         return SPD_OK;
     }
-    unpack_frags((const uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, [&](int k, int nt, int r, float v) {
+    const float *sc = (const float *)(base + D.w_scale);
+    unpack_frags((const uint16_t *)(base + D.w_qkv), D.nqkv / 16, h / 32, sc[0], [&](int k, int nt, int r, float v) {
         const int c = spd_qkv_tile_col0(nt, q, kv, d) + r;
         if (c < qd) wq[(size_t)k * o->ld_q + c] = v;
         else if (c < qd + kvd) wk[(size_t)k * o->ld_k + (c - qd)] = v;
         else wv[(size_t)k * o->ld_v + (c - qd - kvd)] = v;
     });
-    unpack_frags((const uint16_t *)(base + D.w_o), h / 16, qd / 32,
+    unpack_frags((const uint16_t *)(base + D.w_o), h / 16, qd / 32, sc[1],
                  [&](int k, int nt, int r, float v) { wo[(size_t)k * o->ld_o + nt * 16 + r] = v; });
-    unpack_frags((const uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, [&](int k, int nt, int r, float v) {
+    unpack_frags((const uint16_t *)(base + D.w_g), 2 * D.f_pad / 16, h / 32, sc[2], [&](int k, int nt, int r, float v) {
         const int c = (nt >> 1) * 16 + r;
         if (c >= f) return;
         if (nt & 1) wu[(size_t)k * o->ld_u + c] = v;
         else wg[(size_t)k * o->ld_g + c] = v;
     });
-    unpack_frags((const uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, [&](int k, int nt, int r, float v) {
+    unpack_frags((const uint16_t *)(base + D.w_d), h / 16, D.f_pad / 32, sc[3], [&](int k, int nt, int r, float v) {
         if (k < f) wd[(size_t)k * o->ld_d + nt * 16 + r] = v;
     });
     return SPD_OK;
@@ -620,32 +618,3 @@ extern "C" int spd_gemm_tile_of(int32_t TN, int32_t TM, int32_t rn, int32_t rm, 
     return 0;
 }
 
-// spd_testing.h: how far the fp16 copy of a packed shard is from its bf16 weights
-extern "C" int spd_f16_copy_check(const spd_ctx *ctx, const void *packed_host, double *max_abs_diff, double *max_abs_weight,
-                                  int64_t *n_inexact, int64_t *n_weights) {
-    if (!ctx || !packed_host) return SPD_EINVAL;
-    const spd_dims &D = ctx->D;
-    if (!D.has16) return SPD_EUNSUPPORTED;
-    const char *base = (const char *)packed_host;
-    const float *sc = (const float *)(base + D.w16_scale);
-    const size_t off_b[4] = {D.w_qkv, D.w_o, D.w_g, D.w_d}, off_h[4] = {D.w16_qkv, D.w16_o, D.w16_g, D.w16_d};
-    const size_t n[4] = {(size_t)D.h * D.nqkv, (size_t)D.q * D.d * D.h, (size_t)2 * D.h * D.f_pad, (size_t)D.f_pad * D.h};
-    double worst = 0.0, big = 0.0;
-    int64_t inexact = 0, total = 0;
-    for (int m = 0; m < 4; ++m) {
-        const uint16_t *b = (const uint16_t *)(base + off_b[m]), *hh = (const uint16_t *)(base + off_h[m]);
-        for (size_t i = 0; i < n[m]; ++i) {
-            const double w = (double)from_bf16(b[i]), w16 = (double)from_f16(hh[i]) * (double)sc[m];
-            const double diff = std::fabs(w - w16);
-            if (diff > 0.0) ++inexact;
-            if (diff > worst) worst = diff;
-            if (std::fabs(w) > big) big = std::fabs(w);
-        }
-        total += (int64_t)n[m];
-    }
-    if (max_abs_diff) *max_abs_diff = worst;
-    if (max_abs_weight) *max_abs_weight = big;
-    if (n_inexact) *n_inexact = inexact;
-    if (n_weights) *n_weights = total;
-    return SPD_OK;
-}

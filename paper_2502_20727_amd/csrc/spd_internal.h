@@ -16,7 +16,8 @@
 // ------------------------------------------------------------------------------------------
 // Packed layouts of the bf16 path.
 //
-// Every matrix operand of an MFMA 16x16x32 (bf16) is stored as a sequence of 1 KiB
+// Every matrix operand of an MFMA 16x16x32 (16-bit elements: fp16 for the projections, bf16 for
+// attention) is stored as a sequence of 1 KiB
 // "fragments": 16 rows x 32 contraction elements, in the register order of the
 // instruction.  Lane l of a wavefront owns row (l % 16) and the 8 consecutive contraction
 // elements starting at 8 * (l / 16); its 8 bf16 values are contiguous (16 bytes), and the
@@ -30,7 +31,7 @@
 
 constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
-constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of at most this many tokens carry the MLP inputs as hi + lo pairs
+constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of more than this many tokens carry the QKV projection's input as a hi + lo pair
 constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
 constexpr int SPD_MID_KPART = 2304 * 8;   // ... and a call of 17 .. 128 tokens (pairs x splits x m-tiles)
@@ -142,10 +143,9 @@ struct spd_dims {
     float eps, rope_base;
     // packed shard (bytes from its start)
     size_t w_g1, w_g2, w_qkv, w_o, w_g, w_u, w_d, weight_bytes;   // w_u: f32 path only (bf16: gate/up interleaved at w_g)
-    // bf16 path with calls of more than 16 tokens: the fp16 copy of the four matrices (same fragment order; element
-    // = round_fp16(2^k w), one k per matrix) and the four factors 2^-k (fp32) that undo it
-    int has16;
-    size_t w16_scale, w16_qkv, w16_o, w16_g, w16_d;
+    // bf16 path: the four matrices are stored as round_fp16(2^k w), one k per matrix; w_scale holds the four
+    // factors 2^-k (fp32; 0 QKV, 1 O, 2 gate/up incl. its decode-only copy, 3 down) that undo it
+    size_t w_scale;
     // KV cache (bytes)
     size_t kv_v, kv_bytes;
     // workspace (bytes)
@@ -188,8 +188,7 @@ struct spd_call {
     int batch, q_len, M;
     spd_positions pos;
     int max_pos_end;          // max over sequences of positions[b] + q_len
-    // bf16 path: operand format of the projections and which of their inputs are carried as hi + lo pairs
-    bool f16;                 // a call of more than 16 tokens: fp16 activations against the fp16 copy of the weights
+    // bf16 path: which projection inputs are carried as hi + lo pairs of fp16 values
     bool sp_x;                // first norm's output (input of the QKV projection)
     bool sp_a;                // attention output (input of the O projection)
     bool sp_m;                // second norm's output and SwiGLU output (inputs of the MLP's projections)

@@ -12,13 +12,14 @@
 // element, the rounding error of the first plane (x = hi + lo up to 2^-17 relative).
 // Contractions then run over both planes.
 //
-// Two operand formats.  Calls of at most 16 tokens (the weight-streaming kernel k_gemv) and the
-// attention kernels contract bf16 operands.  Calls of more than 16 tokens contract fp16 operands
-// (v_mfma_f32_16x16x32_f16, same register layout, same rate): their activations are rounded to
-// fp16's 11 significant bits instead of bf16's 8, and their weights come from a second copy of the
-// shard that holds round_fp16(2^k w) with one power of two per matrix, undone in the epilogue
-// (`wsc`).  The fragments of both formats are 16-bit elements in the same order, so everything
-// that only moves data is shared and typed as bf16.
+// Operand format.  The projections contract fp16 operands (v_mfma_f32_16x16x32_f16): activations are
+// rounded to fp16's 11 significant bits, and the packed shard holds every weight w as
+// round_fp16(2^k w), one power of two per matrix, undone in the epilogue (`wsc`).  The bf16 weights the
+// library is given fit that encoding exactly (8 significant bits; the power of two puts the matrix's
+// largest magnitude just below 2^15, so every weight within 2^-29 of it is a normal fp16 number).
+// Attention contracts bf16: the KV cache holds bf16 values, queries and probabilities are bf16 pairs.
+// fp16 and bf16 fragments are 16-bit elements in the same order, so everything that only moves data
+// is typed as bf16.
 #include <mutex>
 
 #include "spd_internal.h"
@@ -36,30 +37,7 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 #define MFMA16(a, b, c) \
     __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, (a)), __builtin_bit_cast(f16x8, (b)), (c), 0, 0, 0)
 
-// Activation element of either format as raw 16 bits typed __bf16.  H: fp16, else bf16.
-template <bool H>
-struct Act {
-    static __device__ __forceinline__ __bf16 one(float v) {
-        if constexpr (H) return __builtin_bit_cast(__bf16, (_Float16)v);
-        else return (__bf16)v;
-    }
-    static __device__ __forceinline__ float back(__bf16 r) {
-        if constexpr (H) return (float)__builtin_bit_cast(_Float16, r);
-        else return (float)r;
-    }
-};
-template <bool H>
-__device__ __forceinline__ bf16x4 cvt4t(float a, float b, float c, float d) {
-    bf16x4 r;
-    r[0] = Act<H>::one(a); r[1] = Act<H>::one(b); r[2] = Act<H>::one(c); r[3] = Act<H>::one(d);
-    return r;
-}
-// rounding error of cvt4t, itself rounded to the same format
-template <bool H>
-__device__ __forceinline__ bf16x4 cvt4t_lo(float a, float b, float c, float d, bf16x4 hi) {
-    return cvt4t<H>(a - Act<H>::back(hi[0]), b - Act<H>::back(hi[1]), c - Act<H>::back(hi[2]), d - Act<H>::back(hi[3]));
-}
-
+// bf16 (attention operands: queries, keys, values, probabilities)
 __device__ __forceinline__ bf16x4 cvt4(float a, float b, float c, float d) {
     bf16x4 r;
     r[0] = (__bf16)a; r[1] = (__bf16)b; r[2] = (__bf16)c; r[3] = (__bf16)d;
@@ -68,6 +46,18 @@ __device__ __forceinline__ bf16x4 cvt4(float a, float b, float c, float d) {
 // rounding error of cvt4, itself rounded to bf16
 __device__ __forceinline__ bf16x4 cvt4_lo(float a, float b, float c, float d, bf16x4 hi) {
     return cvt4(a - (float)hi[0], b - (float)hi[1], c - (float)hi[2], d - (float)hi[3]);
+}
+// An fp16 activation as raw 16 bits typed __bf16 (the type the data-moving code uses).
+__device__ __forceinline__ __bf16 act_one(float v) { return __builtin_bit_cast(__bf16, (_Float16)v); }
+__device__ __forceinline__ float act_back(__bf16 r) { return (float)__builtin_bit_cast(_Float16, r); }
+__device__ __forceinline__ bf16x4 cvt4h(float a, float b, float c, float d) {
+    bf16x4 r;
+    r[0] = act_one(a); r[1] = act_one(b); r[2] = act_one(c); r[3] = act_one(d);
+    return r;
+}
+// rounding error of cvt4h, itself rounded to fp16
+__device__ __forceinline__ bf16x4 cvt4h_lo(float a, float b, float c, float d, bf16x4 hi) {
+    return cvt4h(a - act_back(hi[0]), b - act_back(hi[1]), c - act_back(hi[2]), d - act_back(hi[3]));
 }
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, 64); }
 // Sum / maximum over the four lanes l, l^16, l^32, l^48 (the lanes that share a token or an attention column),
@@ -117,7 +107,6 @@ __device__ __forceinline__ float row_rsqrt(const float *__restrict__ ss, int nch
 // lo plane), and the partial sums of squares of `out` per (k-chunk, token).  One wave per
 // (m-tile, chunk of `tpw` k-tiles); lane l handles token l%16 and 8 consecutive features.
 // ------------------------------------------------------------------------------------------
-template <bool H>      // H: the normalised activations are written as fp16 (calls of more than 16 tokens)
 __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, const float *__restrict__ slots,
                                               int n_slots, size_t slot_stride, float *__restrict__ out,
                                               const float *__restrict__ gain, __bf16 *__restrict__ xhat,
@@ -189,8 +178,8 @@ __global__ void __launch_bounds__(256) k_prep(const float *__restrict__ base, co
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float p = v[i] * gg[i];
-                    x[i] = Act<H>::one(p);
-                    xl[i] = Act<H>::one(p - Act<H>::back(x[i]));
+                    x[i] = act_one(p);
+                    xl[i] = act_one(p - act_back(x[i]));
                 }
             }
             const size_t fo = spd_frag_index(mt, kt, KT) + lane * 8;
@@ -215,7 +204,7 @@ __device__ __forceinline__ float4 ldnt4(const float *p) {
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
-template <int NP, bool H>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
+template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
                                                    const float *__restrict__ gain, __bf16 *__restrict__ xhat,
@@ -295,9 +284,9 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
                 if (ss && lane == 0) ss[(size_t)(chunk0 + q) * m_pad + mt * 16 + r] = sq;
                 if (xhat) {
                     const float q0 = u.x * gn[q].x, q1 = u.y * gn[q].y, q2 = u.z * gn[q].z, q3 = u.w * gn[q].w;
-                    const bf16x4 hi = cvt4t<H>(q0, q1, q2, q3);
+                    const bf16x4 hi = cvt4h(q0, q1, q2, q3);
                     *(bf16x4 *)&tile[0][r][256 * q + lane * 4] = hi;
-                    if (xlo) *(bf16x4 *)&tile[1][r][256 * q + lane * 4] = cvt4t_lo<H>(q0, q1, q2, q3, hi);
+                    if (xlo) *(bf16x4 *)&tile[1][r][256 * q + lane * 4] = cvt4h_lo(q0, q1, q2, q3, hi);
                 }
             }
         }
@@ -363,13 +352,12 @@ const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_
 // (so that they can be started before the weights are streamed), operator() finishes the tile.
 // kNeedsRs: the tile must be scaled by 1/sqrt(mean(x^2)+eps) of the token, which the caller
 // computes from the partial sums of squares ss[nch][m_pad].
-template <bool H>      // H: fp16 contraction (the weights' power of two is undone here)
 struct EpiQKV {
     static constexpr bool kNeedsRs = true;
     int M, q_len, q, kv, d, h, max_ctx, nch, m_pad;
     float eps;
     const float *ss, *cosT, *sinT;
-    const float *wsc = nullptr;       // NULL, or the factor that undoes the power of two in the fp16 copy of the weights
+    const float *wsc;                 // the factor 2^-k that undoes the power of two in the packed weights
     __bf16 *qbuf, *qlo, *kc, *vc;     // queries are kept as hi + lo pairs
     spd_positions P;
     struct Pre {
@@ -399,7 +387,7 @@ struct EpiQKV {
         const int bseq = m / q_len, pos = P.pos[bseq] + (m % q_len);
         const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) - head * d + 4 * g;       // column inside the head
         const int cb = spd_qkv_tile_col0(2 * pair + 1, q, kv, d) - head * d + 4 * g;
-        if constexpr (H) rs *= *wsc;
+        rs *= *wsc;
         a *= rs;
         b *= rs;
         if (head < q + kv) {
@@ -436,17 +424,16 @@ struct EpiQKV {
 // so every slice applies them to its own partial sums and parks the result, fp32, in
 // part[slice][token][column] (columns in natural order: head * d + j).  The attention kernel adds
 // the slices in ascending order, rounds, and appends the new key and value to the cache.
-template <bool H>
 struct EpiQKVPart {
     static constexpr bool kNeedsRs = true;
     int M, q_len, q, kv, d, h, nqkv, nch, m_pad;
     int part_rows;             // token rows per slice of `part`
     float eps;
     const float *ss, *cosT, *sinT;
-    const float *wsc = nullptr;
+    const float *wsc;
     float *part;
     spd_positions P;
-    typedef typename EpiQKV<H>::Pre Pre;
+    typedef EpiQKV::Pre Pre;
 
     __device__ __forceinline__ Pre pre(int pair, int mt, int lane) const {
         Pre p;
@@ -470,7 +457,7 @@ struct EpiQKVPart {
         const int head = (2 * pair) / tph;
         const int ca = spd_qkv_tile_col0(2 * pair, q, kv, d) + 4 * g;
         const int cb = spd_qkv_tile_col0(2 * pair + 1, q, kv, d) + 4 * g;
-        if constexpr (H) rs *= *wsc;
+        rs *= *wsc;
         a *= rs;
         b *= rs;
         float4 lo = make_float4(a[0], a[1], a[2], a[3]), hi = make_float4(b[0], b[1], b[2], b[3]);
@@ -485,13 +472,13 @@ struct EpiQKVPart {
     }
 };
 
-template <bool MID, bool H>      // MID: the epilogue can also perform the kept attention sync point (spd = 2); H: fp16 activations out
+template <bool MID>      // MID: the epilogue can also perform the kept attention sync point (spd = 2)
 struct EpiOT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
     const float *bo = nullptr; // bias of the output projection or NULL: part of the SPD block's MLP input (Sec. 4.1.2)
-    const float *wsc = nullptr;
+    const float *wsc;
     float *ybuf, *slot, *ss2;
     __bf16 *xhat2, *xlo2;      // xlo2 may be NULL
     // spd = 2: TP block whose kept attention sync point is performed here (one rank, the peers' partial
@@ -531,7 +518,7 @@ struct EpiOT {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const int na = pair * 32 + 4 * g, nb = na + 16;
         const bool valid = m < M;
-        if constexpr (H) {
+        {
             const float sc = *wsc;
             a *= sc;
             b *= sc;
@@ -567,15 +554,15 @@ struct EpiOT {
             pa[0] = ra[0] * p.ga.x; pa[1] = ra[1] * p.ga.y; pa[2] = ra[2] * p.ga.z; pa[3] = ra[3] * p.ga.w;
             pb[0] = rb[0] * p.gb.x; pb[1] = rb[1] * p.gb.y; pb[2] = rb[2] * p.gb.z; pb[3] = rb[3] * p.gb.w;
         }
-        const bf16x4 xa = cvt4t<H>(pa[0], pa[1], pa[2], pa[3]), xb = cvt4t<H>(pb[0], pb[1], pb[2], pb[3]);
+        const bf16x4 xa = cvt4h(pa[0], pa[1], pa[2], pa[3]), xb = cvt4h(pb[0], pb[1], pb[2], pb[3]);
         // the pair's 32 features are k-tile `pair` of the next contraction
         const size_t fo = spd_frag_index(mt, pair, h >> 5);
         const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
         *(bf16x4 *)(xhat2 + fo + ea) = xa;
         *(bf16x4 *)(xhat2 + fo + eb) = xb;
         if (xlo2) {
-            *(bf16x4 *)(xlo2 + fo + ea) = cvt4t_lo<H>(pa[0], pa[1], pa[2], pa[3], xa);
-            *(bf16x4 *)(xlo2 + fo + eb) = cvt4t_lo<H>(pb[0], pb[1], pb[2], pb[3], xb);
+            *(bf16x4 *)(xlo2 + fo + ea) = cvt4h_lo(pa[0], pa[1], pa[2], pa[3], xa);
+            *(bf16x4 *)(xlo2 + fo + eb) = cvt4h_lo(pb[0], pb[1], pb[2], pb[3], xb);
         }
         float s = 0.f;
 #pragma unroll
@@ -586,14 +573,13 @@ struct EpiOT {
     }
 };
 
-template <bool H>
 struct EpiGU {
     static constexpr bool kNeedsRs = true;
     int M, h, f_pad, nch, m_pad;
     int cols = 16;             // FFN columns per group: 16, or fewer for the decode-only narrow groups
     float eps;
     const float *ss;
-    const float *wsc = nullptr;
+    const float *wsc;
     __bf16 *uhat, *ulo;        // ulo may be NULL
     struct Pre {};
 
@@ -602,7 +588,7 @@ struct EpiGU {
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &) const {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         float o[4] = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (H) rs *= *wsc;
+        rs *= *wsc;
         if (m < M) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -610,10 +596,10 @@ struct EpiGU {
                 o[i] = gt / (1.0f + __expf(-gt)) * up;
             }
         }
-        const bf16x4 u = cvt4t<H>(o[0], o[1], o[2], o[3]);
+        const bf16x4 u = cvt4h(o[0], o[1], o[2], o[3]);
         if (cols != 16) {
             // narrow group: rows 4g .. 4g+3 are FFN columns cols*pair + 4g + i, stored one by one
-            const bf16x4 lo = cvt4t_lo<H>(o[0], o[1], o[2], o[3], u);
+            const bf16x4 lo = cvt4h_lo(o[0], o[1], o[2], o[3], u);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int col = pair * cols + 4 * g + i;
@@ -628,11 +614,11 @@ struct EpiGU {
         // gate/up pair p covers FFN columns [16p, 16p+16): half of k-tile p/2 of the down projection
         const size_t fo = spd_frag_index(mt, pair >> 1, f_pad >> 5) + spd_frag_elem(r, 16 * (pair & 1) + 4 * g);
         *(bf16x4 *)(uhat + fo) = u;
-        if (ulo) *(bf16x4 *)(ulo + fo) = cvt4t_lo<H>(o[0], o[1], o[2], o[3], u);
+        if (ulo) *(bf16x4 *)(ulo + fo) = cvt4h_lo(o[0], o[1], o[2], o[3], u);
     }
 };
 
-template <bool FUSED, bool H>
+template <bool FUSED>
 struct EpiDownT {
     static constexpr bool kNeedsRs = false;
     int M, h, spd;
@@ -642,7 +628,7 @@ struct EpiDownT {
     // inputs).  base == NULL: not fused.
     const float *base, *slots, *g1;
     const float *bias;         // [h] added once after the sum (SPD block with bias) or NULL
-    const float *wsc = nullptr;
+    const float *wsc;
     size_t slot_stride;
     int tp, rank, m_pad;
     float *x_out, *ss1;
@@ -673,7 +659,7 @@ struct EpiDownT {
         const int r = lane & 15, m = mt * 16 + r, g = lane >> 4;
         const bool valid = m < M;
         const size_t oa = (size_t)m * h + pair * 32 + 4 * g, ob = oa + 16;
-        if constexpr (H) {
+        {
             const float sc = *wsc;
             a *= sc;
             b *= sc;
@@ -699,14 +685,14 @@ struct EpiDownT {
             qa[0] = xa.x * ga.x; qa[1] = xa.y * ga.y; qa[2] = xa.z * ga.z; qa[3] = xa.w * ga.w;
             qb[0] = xb.x * gb.x; qb[1] = xb.y * gb.y; qb[2] = xb.z * gb.z; qb[3] = xb.w * gb.w;
         }
-        const bf16x4 ha = cvt4t<H>(qa[0], qa[1], qa[2], qa[3]), hb = cvt4t<H>(qb[0], qb[1], qb[2], qb[3]);
+        const bf16x4 ha = cvt4h(qa[0], qa[1], qa[2], qa[3]), hb = cvt4h(qb[0], qb[1], qb[2], qb[3]);
         const size_t fo = spd_frag_index(mt, pair, h >> 5);
         const int ea = spd_frag_elem(r, 4 * g), eb = spd_frag_elem(r, 16 + 4 * g);
         *(bf16x4 *)(xhat + fo + ea) = ha;
         *(bf16x4 *)(xhat + fo + eb) = hb;
         if (xlo) {
-            *(bf16x4 *)(xlo + fo + ea) = cvt4t_lo<H>(qa[0], qa[1], qa[2], qa[3], ha);
-            *(bf16x4 *)(xlo + fo + eb) = cvt4t_lo<H>(qb[0], qb[1], qb[2], qb[3], hb);
+            *(bf16x4 *)(xlo + fo + ea) = cvt4h_lo(qa[0], qa[1], qa[2], qa[3], ha);
+            *(bf16x4 *)(xlo + fo + eb) = cvt4h_lo(qb[0], qb[1], qb[2], qb[3], hb);
         }
         float sq = xa.x * xa.x + xa.y * xa.y + xa.z * xa.z + xa.w * xa.w + xb.x * xb.x + xb.y * xb.y + xb.z * xb.z + xb.w * xb.w;
         sq += shfl_xor_f(sq, 16);
@@ -773,11 +759,11 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
     auto consume = [&](const GemvBatch<U, SPLIT> &B) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a = MFMA(B.fa[u], B.fh[u], a);
-            b = MFMA(B.fb[u], B.fh[u], b);
+            a = MFMA16(B.fa[u], B.fh[u], a);
+            b = MFMA16(B.fb[u], B.fh[u], b);
             if (SPLIT) {
-                a = MFMA(B.fa[u], B.fl[u], a);
-                b = MFMA(B.fb[u], B.fl[u], b);
+                a = MFMA16(B.fa[u], B.fl[u], a);
+                b = MFMA16(B.fb[u], B.fl[u], b);
             }
         }
     };
@@ -822,12 +808,12 @@ __global__ void __launch_bounds__(W * 64) k_gemv(const __bf16 *__restrict__ Wp, 
         const bf16x8 fa = __builtin_nontemporal_load(wa + (size_t)kt * kstr);
         const bf16x8 fb = __builtin_nontemporal_load(wb + (size_t)kt * kstr);
         const bf16x8 fh = xh[(size_t)kt * 64];
-        a = MFMA(fa, fh, a);
-        b = MFMA(fb, fh, b);
+        a = MFMA16(fa, fh, a);
+        b = MFMA16(fb, fh, b);
         if (SPLIT) {
             const bf16x8 fl = xl[(size_t)kt * 64];
-            a = MFMA(fa, fl, a);
-            b = MFMA(fb, fl, b);
+            a = MFMA16(fa, fl, a);
+            b = MFMA16(fb, fl, b);
         }
     }
     __shared__ f32x4 red[W][2][64];
@@ -1768,7 +1754,6 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __bf16 *__restrict__ 
 // grid (kv heads, sequences, d/16); thread -> (feature dd, column c).  Every thread reads the
 // running max and sum of its column itself (16 splits at a time, all loads issued together), so
 // the kernel is one memory round trip per 16 splits; the splits are merged in ascending order.
-template <bool H>      // H: the output feeds an fp16 contraction
 __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ part, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, int q, int kv, int d, int n_splits) {
     const int kvh = blockIdx.x, b = blockIdx.y;
@@ -1805,9 +1790,9 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
     const float val = num / den;
     const int kidx = (kvh * group + c) * d + dd;
     const size_t o = spd_frag_index(b >> 4, kidx >> 5, qd >> 5) + spd_frag_elem(b & 15, kidx & 31);
-    const __bf16 hi = Act<H>::one(val);
+    const __bf16 hi = act_one(val);
     ahat[o] = hi;
-    if (alo) alo[o] = Act<H>::one(val - Act<H>::back(hi));
+    if (alo) alo[o] = act_one(val - act_back(hi));
 }
 
 // Prefill (q_len > 1): grid (groups of CT column tiles, kv heads, sequences), 4 waves.  All four
@@ -1815,7 +1800,7 @@ __global__ void __launch_bounds__(256) k_attn_combine(const float *__restrict__ 
 // among themselves block by block (the latest tokens attend thousands of keys: one wave walking
 // them alone would be the critical path of the launch); their partial states meet in LDS and
 // every wave finishes a quarter of the (tile, 16-feature slice) outputs.
-template <int DT, int CT, bool H>
+template <int DT, int CT>
 __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__ qbuf, const __bf16 *__restrict__ qlo, const __bf16 *__restrict__ kc,
                                                       const __bf16 *__restrict__ vc, __bf16 *__restrict__ ahat,
                                                       __bf16 *__restrict__ alo, spd_positions P, int q_len, int q, int kv,
@@ -1895,24 +1880,23 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const __bf16 *__restrict__
         const int mt = mrow[c] >> 4, r = mrow[c] & 15;
         const int kidx = hd[c] * d + dt * 16 + 4 * g;
         const float o0 = num[0] * inv, o1 = num[1] * inv, o2 = num[2] * inv, o3 = num[3] * inv;
-        const bf16x4 v = cvt4t<H>(o0, o1, o2, o3);
+        const bf16x4 v = cvt4h(o0, o1, o2, o3);
         const size_t o = spd_frag_index(mt, kidx >> 5, qd >> 5) + spd_frag_elem(r, kidx & 31);
         *(bf16x4 *)(ahat + o) = v;
-        if (alo) *(bf16x4 *)(alo + o) = cvt4t_lo<H>(o0, o1, o2, o3, v);
+        if (alo) *(bf16x4 *)(alo + o) = cvt4h_lo(o0, o1, o2, o3, v);
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // taps (tests only): packed bf16 (hi [+ lo]) -> natural fp32
 // ------------------------------------------------------------------------------------------
-template <bool H>
 __global__ void k_unpack_act(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst, int M,
                              int K_packed, int K_out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)M * K_out) return;
     const int m = (int)(i / K_out), k = (int)(i % K_out);
     const size_t o = spd_frag_index(m >> 4, k >> 5, K_packed >> 5) + spd_frag_elem(m & 15, k & 31);
-    dst[i] = Act<H>::back(src[o]) + (lo ? Act<H>::back(lo[o]) : 0.f);
+    dst[i] = act_back(src[o]) + (lo ? act_back(lo[o]) : 0.f);
 }
 __global__ void k_bf16_to_f32(const __bf16 *__restrict__ src, const __bf16 *__restrict__ lo, float *__restrict__ dst,
                               int64_t n) {
@@ -2074,22 +2058,17 @@ inline int skinny_limit(int n_pairs, int KT, int n_mtiles) {
     return t_skinny < t_gemm ? n_mtiles : SKINNY_MAX_MTILES;
 }
 
-// Projection of a call of any size.  At most 16 tokens: the weight-streaming kernel on the bf16 weights
-// Wp; beyond that the fp16 kernels on the fp16 copy W16 (skinny up to `skinny_max` m-tiles, the LDS-tiled
-// GEMM beyond).
-template <bool H, class Epi>     // H: a call of more than 16 tokens (fp16 operands), Wp then is the fp16 copy
+// Projection of a call of any size: the weight-streaming kernel up to 16 tokens, the skinny kernel up to
+// `skinny_max` m-tiles, the LDS-tiled GEMM beyond.
+template <class Epi>
 hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __bf16 *Xhi, size_t plane, int n_pairs, int KT,
                        const Epi &epi, int skinny_max = SKINNY_MAX_MTILES) {
     const int n_mtiles = (c.M + 15) / 16;
     const __bf16 *Xlo = Xhi + plane;
-    if constexpr (!H) {
-        if (n_mtiles != 1) return hipErrorInvalidValue;
+    if (n_mtiles == 1)
         return split ? launch_gemv<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemv<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
-    } else {
-        if (n_mtiles <= skinny_max) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
-        return split ? launch_gemm_lds<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi)
-                     : launch_gemm_lds<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
-    }
+    if (n_mtiles <= skinny_max) return launch_skinny<0>(c, split, Wp, Xhi, plane, n_pairs, KT, 1, 16, epi);
+    return split ? launch_gemm_lds<true>(c, Wp, Xhi, Xlo, n_pairs, KT, epi) : launch_gemm_lds<false>(c, Wp, Xhi, Xlo, n_pairs, KT, epi);
 }
 
 // chunking of the sum-of-squares partials written by prep()
@@ -2112,48 +2091,35 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     if (!c.on(SPD_STAGE_PREP)) return hipSuccess;
     spd_stage_scope prof(c, SPD_STAGE_PREP);
     // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
-    if (tpw == 8 && D.h % 256 == 0) {
-        const dim3 grid(D.h / 256, cdiv(c.M, 16));
-        if (c.f16)
-            hipLaunchKernelGGL((k_prep_rows<1, true>), grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out,
-                               gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
-        else
-            hipLaunchKernelGGL((k_prep_rows<1, false>), grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out,
-                               gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
-    } else {
-        const dim3 grid(cdiv(nch, 4), cdiv(c.M, 16));
-        if (c.f16)
-            hipLaunchKernelGGL(k_prep<true>, grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out, gain, xhat,
-                               xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
-        else
-            hipLaunchKernelGGL(k_prep<false>, grid, dim3(256), 0, c.s, base, slots, n_slots, (size_t)c.M * D.h, out, gain, xhat,
-                               xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
-    }
+    if (tpw == 8 && D.h % 256 == 0)
+        hipLaunchKernelGGL(k_prep_rows<1>, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
+                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
+    else
+        hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
+                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
     return hipGetLastError();
 }
 
 int prep_chunks(const spd_call &c) { return prep_nch(c.D->h, c.M); }
 
 namespace {
-// weights of projection `i` (0 QKV, 1 O, 2 gate/up, 3 down) in the operand format of the call, and the
-// factor that undoes the fp16 copy's power of two (NULL for the bf16 weights)
+// weights of projection `i` (0 QKV, 1 O, 2 gate/up, 3 down) and the factor 2^-k that undoes their power of two
 struct ProjW {
     const __bf16 *w;
     const float *wsc;
 };
 inline ProjW proj_weights(const spd_call &c, const char *w, int i) {
     const spd_dims &D = *c.D;
-    const size_t off_b[4] = {D.w_qkv, D.w_o, D.w_g, D.w_d}, off_h[4] = {D.w16_qkv, D.w16_o, D.w16_g, D.w16_d};
+    const size_t off[4] = {D.w_qkv, D.w_o, D.w_g, D.w_d};
     ProjW p;
-    p.w = (const __bf16 *)(w + (c.f16 ? off_h[i] : off_b[i]));
-    p.wsc = c.f16 ? (const float *)(w + D.w16_scale) + i : nullptr;
+    p.w = (const __bf16 *)(w + off[i]);
+    p.wsc = (const float *)(w + D.w_scale) + i;
     return p;
 }
 }  // namespace
 
-template <bool H>
-static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
-                                   const spd_mid_sync *mid, bool *mid_done) {
+hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
+                          const spd_mid_sync *mid, bool *mid_done) {
     const spd_dims &D = *c.D;
     const int M = c.M, qd = D.q * D.d;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat);
@@ -2189,7 +2155,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
     }
     float *qkvp = (float *)(c.ws + D.ws_kpart);
     if (fused_q || gather_q) {
-        EpiQKVPart<H> e1;
+        EpiQKVPart e1;
         e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
         e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.part_rows = 16 * n_mtiles; e1.eps = D.eps;
         e1.ss = (const float *)(c.ws + D.ws_ss1);
@@ -2198,7 +2164,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
         e1.part = qkvp; e1.P = c.pos;
         if (c.on(SPD_STAGE_QKV)) {
             spd_stage_scope prof(c, SPD_STAGE_QKV);
-            if constexpr (!H) {
+            if (n_mtiles == 1) {
                 SPD_TRY(launch_gemv_sliced(c, c.sp_x, wqkv.w, xhat, D.pl_x, qkv_pairs, D.h / 32, qkv_slices, e1));
             } else {
                 SPD_TRY(launch_skinny<2>(c, c.sp_x, wqkv.w, xhat, D.pl_x, qkv_pairs, D.h / 32, qkv_slices, 16, e1));
@@ -2210,7 +2176,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
             }
         }
     } else {
-        EpiQKV<H> e1;
+        EpiQKV e1;
         e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
         e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
         e1.ss = (const float *)(c.ws + D.ws_ss1);
@@ -2219,7 +2185,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
         e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
         if (c.on(SPD_STAGE_QKV)) {
             spd_stage_scope prof(c, SPD_STAGE_QKV);
-            SPD_TRY(launch_proj<H>(c, c.sp_x, wqkv.w, xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
+            SPD_TRY(launch_proj(c, c.sp_x, wqkv.w, xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
                                    skinny_limit(D.nqkv / 32, D.h / 32, n_mtiles)));
         }
     }
@@ -2264,7 +2230,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
         }
 #undef SPD_DECODE
         SPD_TRY(hipGetLastError());
-        hipLaunchKernelGGL(k_attn_combine<H>, dim3(D.kv, c.batch, D.d / 16), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
+        hipLaunchKernelGGL(k_attn_combine, dim3(D.kv, c.batch, D.d / 16), dim3(256), 0, c.s, part, ahat, alo, D.q, D.kv,
                            D.d, splits);
         SPD_TRY(hipGetLastError());
     } else {
@@ -2277,10 +2243,10 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
         static std::once_flag once;                                                                                        \
         static hipError_t attr_err = hipSuccess;                                                                           \
         std::call_once(once, [] {                                                                                          \
-            attr_err = hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT, H>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
+            attr_err = hipFuncSetAttribute((const void *)k_attn_prefill<DTV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
         });                                                                                                                \
         SPD_TRY(attr_err);                                                                                                 \
-        hipLaunchKernelGGL((k_attn_prefill<DTV, CT, H>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
+        hipLaunchKernelGGL((k_attn_prefill<DTV, CT>), grid, dim3(256), lds, c.s, qbuf, qlo, kc, vc, ahat, alo, c.pos, c.q_len, \
                            D.q, D.kv, D.max_ctx);                                                                          \
     }
         switch (DT) {
@@ -2310,19 +2276,19 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
         spd_stage_scope prof(c, SPD_STAGE_O);
         if (fuse_mid) {
             // the weight-streaming kernels only
-            EpiOT<true, H> e2;
+            EpiOT<true> e2;
             fill_o(e2);
             e2.spd = 2;
             e2.slots = mid->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = mid->tp; e2.rank = mid->rank; e2.rbuf = mid->rbuf;
-            if constexpr (!H)
+            if (M <= 16)
                 SPD_TRY(c.sp_a ? launch_gemv<true>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2)
                                : launch_gemv<false>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2));
             else
                 SPD_TRY(launch_skinny<0>(c, c.sp_a, wo.w, ahat, D.pl_a, D.h / 32, qd / 32, 1, 16, e2));
         } else {
-            EpiOT<false, H> e2;
+            EpiOT<false> e2;
             fill_o(e2);
-            SPD_TRY(launch_proj<H>(c, c.sp_a, wo.w, ahat, D.pl_a, D.h / 32, qd / 32, e2));
+            SPD_TRY(launch_proj(c, c.sp_a, wo.w, ahat, D.pl_a, D.h / 32, qd / 32, e2));
         }
     }
 
@@ -2333,7 +2299,7 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
             SPD_TRY(hipGetLastError());
         }
         if (c.taps->attn) {
-            hipLaunchKernelGGL(k_unpack_act<H>, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, alo, c.taps->attn, M,
+            hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * qd, 256)), dim3(256), 0, c.s, ahat, alo, c.taps->attn, M,
                                qd, qd);
             SPD_TRY(hipGetLastError());
         }
@@ -2342,15 +2308,8 @@ static hipError_t attention_half_t(const spd_call &c, const char *w, char *kvc, 
     return hipSuccess;
 }
 
-hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
-                          const spd_mid_sync *mid, bool *mid_done) {
-    return c.f16 ? attention_half_t<true>(c, w, kvc, x, spd, slot, mid, mid_done)
-                 : attention_half_t<false>(c, w, kvc, x, spd, slot, mid, mid_done);
-}
-
-template <bool H>
-static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
-                             bool ss_per_pair) {
+hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
+                    bool ss_per_pair) {
     const spd_dims &D = *c.D;
     const int M = c.M;
     const __bf16 *xhat = (const __bf16 *)(c.ws + D.ws_xhat2);
@@ -2358,7 +2317,7 @@ static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *s
     __bf16 *ulo = c.sp_m ? uhat + D.pl_u : nullptr;
     const ProjW wgu = proj_weights(c, w, 2), wdn = proj_weights(c, w, 3);
 
-    EpiGU<H> e1;
+    EpiGU e1;
     e1.M = M; e1.h = D.h; e1.f_pad = D.f_pad; e1.m_pad = D.m_pad; e1.eps = D.eps;
     // SPD block: the O-projection epilogue wrote one partial per pair of n-tiles (h/32 of them);
     // TP block: prep() wrote them after the kept sync point
@@ -2368,7 +2327,7 @@ static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *s
     e1.uhat = uhat; e1.ulo = ulo;
     if (c.on(SPD_STAGE_GATEUP)) {
         spd_stage_scope prof(c, SPD_STAGE_GATEUP);
-        if constexpr (!H) {
+        if (M <= 16) {
             if (D.gud_cols) {
                 // decode: the copy with narrow column groups, one workgroup per group
                 e1.cols = D.gud_cols;
@@ -2376,12 +2335,12 @@ static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *s
                 SPD_TRY(c.sp_m ? launch_gemv<true>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols)
                                : launch_gemv<false>(c, wd, xhat, xlo, D.gud_groups, D.h / 32, e1, D.gud_cols));
             } else {
-                SPD_TRY(launch_proj<H>(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+                SPD_TRY(launch_proj(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
             }
         } else {
             bool mid = false;
             if (!c.sp_m) SPD_TRY(launch_mid(c, wgu.w, xhat, D.f_pad / 16, D.h / 32, e1, &mid));
-            if (!mid) SPD_TRY(launch_proj<H>(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
+            if (!mid) SPD_TRY(launch_proj(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
         }
     }
 
@@ -2409,32 +2368,26 @@ static hipError_t mlp_half_t(const spd_call &c, const char *w, int spd, float *s
     if (c.on(SPD_STAGE_DOWN)) {
         spd_stage_scope prof(c, SPD_STAGE_DOWN);
         if (do_fuse) {
-            EpiDownT<true, H> e2;
+            EpiDownT<true> e2;
             fill(e2);
-            if constexpr (!H)
+            if (M <= 16)
                 SPD_TRY(c.sp_m ? launch_gemv<true>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
                                : launch_gemv<false>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
             else
                 SPD_TRY(launch_skinny<0>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
         } else {
-            EpiDownT<false, H> e2;
+            EpiDownT<false> e2;
             fill(e2);
-            SPD_TRY(launch_proj<H>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
+            SPD_TRY(launch_proj(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, e2));
         }
     }
 
     if (c.taps && c.taps->u) {
-        hipLaunchKernelGGL(k_unpack_act<H>, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, ulo, c.taps->u, M,
+        hipLaunchKernelGGL(k_unpack_act, dim3(cdiv((int64_t)M * D.f, 256)), dim3(256), 0, c.s, uhat, ulo, c.taps->u, M,
                            D.f_pad, D.f);
         SPD_TRY(hipGetLastError());
     }
     return hipSuccess;
-}
-
-hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, const spd_end_sync *fuse, bool *fused,
-                    bool ss_per_pair) {
-    return c.f16 ? mlp_half_t<true>(c, w, spd, slot, fuse, fused, ss_per_pair)
-                 : mlp_half_t<false>(c, w, spd, slot, fuse, fused, ss_per_pair);
 }
 
 }  // namespace spd_bf16

@@ -249,7 +249,8 @@ def test_grouped_pack_is_the_oracle_grouping_bit_for_bit(w):
 
 
 def test_pack_every_value_lands_exactly_once():
-    # a packed bf16 shard is a permutation of the shard's values plus zero padding
+    # a packed shard of the bf16 path is a permutation of the shard's values (each times its matrix's power of
+    # two, as fp16) plus zero padding
     w = SMALL_BF16
     ctx = B.spd_create(B.make_config(w))
     shard = inputs.layer_shard(w, 0, 1)
@@ -259,9 +260,11 @@ def test_pack_every_value_lands_exactly_once():
         a[...] = (np.arange(n, n + a.size, dtype=np.int64) % 251 + 1).reshape(a.shape).astype(np.float32)
         n += a.size
     packed = B.spd_pack_shard_local(ctx, shard)
-    vals = packed[2 * 256 * 2:].view(np.uint16)                       # skip the two fp32 gain vectors
-    as_f32 = (vals.astype(np.uint32) << 16).view(np.float32)
-    got = np.bincount(as_f32.astype(np.int64), minlength=252)
+    # skip the two fp32 gain vectors and the block of four scale factors; every matrix has the largest value 251,
+    # so each is stored as fp16(2^7 w)
+    vals = packed[2 * 256 * 2 + 256:].view(np.float16).astype(np.float64) / 128.0
+    assert np.array_equal(vals, np.round(vals))
+    got = np.bincount(vals.astype(np.int64), minlength=252)
     want = np.zeros(252, dtype=np.int64)
     for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
         want += np.bincount(shard[k].astype(np.int64).ravel(), minlength=252)
@@ -283,9 +286,10 @@ def test_pack_keeps_a_second_gate_up_copy_when_tiles_do_not_fill_the_chip():
         n += a.size
     packed = B.spd_pack_shard_local(ctx, shard)
     assert packed.size == B.spd_get_sizes(ctx).weight_bytes
-    vals = packed[2 * 256:].view(np.uint16)                           # skip the two fp32 gain vectors (64 floats, padded)
-    as_f32 = (vals.astype(np.uint32) << 16).view(np.float32)
-    got = np.bincount(as_f32.astype(np.int64), minlength=252)
+    # skip the two fp32 gain vectors (64 floats, padded) and the block of scale factors; stored as fp16(2^7 w)
+    vals = packed[2 * 256 + 256:].view(np.float16).astype(np.float64) / 128.0
+    assert np.array_equal(vals, np.round(vals))
+    got = np.bincount(vals.astype(np.int64), minlength=252)
     want = np.zeros(252, dtype=np.int64)
     for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
         want += np.bincount(shard[k].astype(np.int64).ravel(), minlength=252) * (2 if k in ("wg", "wu") else 1)
@@ -324,33 +328,37 @@ def test_pack_with_output_bias(w):
     B.spd_destroy(ctx)
 
 
-def test_fp16_copy_of_the_weights_reproduces_them():
-    """A bf16 context that takes calls of more than 16 tokens keeps an fp16 copy round_fp16(2^k w) of the four
-    matrices.  With one power of two per matrix every weight within 2^-29 of the largest is reproduced bit for
-    bit; whatever is smaller lands on fp16's subnormal grid, at most 2^-25 / 2^k = 2^-40 max|w| away."""
+def test_fp16_encoding_of_the_weights_reproduces_them():
+    """The packed shard holds every weight as round_fp16(2^k w), one power of two per matrix.  bf16 values fit:
+    every weight within 2^-29 of its matrix's largest comes back bit for bit; whatever is smaller lands on
+    fp16's subnormal grid, at most 2^-25 / 2^k < 2^-39 max|w| away."""
     w = SMALL_BF16
-    ctx = B.spd_create(B.make_config(w, max_tokens=64))
+    ctx = B.spd_create(B.make_config(w))
     shard = inputs.layer_shard(w, 0, 1)
-    diff, big, inexact, n = B.spd_f16_copy_check(ctx, B.spd_pack_shard_local(ctx, shard))
-    assert n >= sum(shard[k].size for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"))
-    assert inexact == 0 and diff == 0.0 and big > 0.0
-    # a dynamic range no fp16 scale can hold: the large entries stay exact, the tiny ones move by < 2^-40 max|w|
+    shapes = {k: v.shape for k, v in shard.items()}
+    # a wide dynamic range inside one matrix, far beyond trained or synthetic weights
     for k in ("wq", "wd"):
         a = shard[k]
         a.flat[0] = np.float32(64.0)
-        a.flat[1] = np.float32(2.0 ** -40)            # a bf16 value 46 binades below the largest
+        a.flat[1] = np.float32(2.0 ** -20)            # 26 binades below the largest: still exact
+        a.flat[2] = np.float32(1.5 * 2.0 ** -22)
+    back = B.spd_unpack_shard(ctx, B.spd_pack_shard_local(ctx, shard), shapes)
+    for k in shapes:
+        assert np.array_equal(back[k], shard[k]), k
+    # beyond fp16's reach: the large entries stay exact, the tiny ones move by less than 2^-39 of the largest
+    for k in ("wq", "wd"):
+        a = shard[k]
+        a.flat[1] = np.float32(2.0 ** -40)            # 46 binades below the largest
         a.flat[2] = np.float32(1.5 * 2.0 ** -60)
-    diff, big, inexact, n = B.spd_f16_copy_check(ctx, B.spd_pack_shard_local(ctx, shard))
-    assert big == 64.0 and 1 <= inexact <= 4
-    assert 0.0 < diff <= 2.0 ** -40 * big
+    back = B.spd_unpack_shard(ctx, B.spd_pack_shard_local(ctx, shard), shapes)
+    for k in shapes:
+        diff = np.abs(back[k].astype(np.float64) - shard[k].astype(np.float64))
+        if k in ("wq", "wd"):
+            assert 0.0 < diff.max() <= 2.0 ** -39 * 64.0 and np.count_nonzero(diff) <= 2
+            assert back[k].flat[0] == 64.0
+        else:
+            assert diff.max() == 0.0
     B.spd_destroy(ctx)
-    # a context for calls of at most 16 tokens keeps no such copy (and its shard is that much smaller)
-    small = B.spd_create(B.make_config(w, max_tokens=16))
-    with pytest.raises(B.SpdError) as e:
-        B.spd_f16_copy_check(small, np.zeros(B.spd_get_sizes(small).weight_bytes, np.uint8))
-    assert e.value.code == B.SPD_EUNSUPPORTED
-    assert B.spd_get_sizes(small).weight_bytes < B.spd_get_sizes(B.spd_create(B.make_config(w, max_tokens=64))).weight_bytes
-    B.spd_destroy(small)
 
 
 def test_pack_rejects_values_that_are_not_bf16():
