@@ -42,6 +42,7 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->batch = batch;
     c->q_len = q_len;
     c->M = batch * q_len;
+    c->slot_stride = (size_t)c->M * D.h;
     c->ws = (char *)workspace;
     c->taps = nullptr;
     c->stages = SPD_ALL_STAGES;
@@ -77,7 +78,7 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
                const float *x, float *slots, const float **base_out, const float **bias_out, int64_t *syncs,
                float *x_out, const float *next_g1, bool *end_done) {
     const spd_dims &D = ctx->D;
-    const size_t slot_n = (size_t)c.M * D.h;
+    const size_t slot_n = c.slot_stride;      // distance between two ranks' slots (the whole call's tokens)
     float *ybuf = (float *)(c.ws + D.ws_y), *rbuf = (float *)(c.ws + D.ws_r);
     const int r0 = rank == SPD_ALL_RANKS ? 0 : rank, r1 = rank == SPD_ALL_RANKS ? D.tp : rank + 1;
     const bool all = rank == SPD_ALL_RANKS;
@@ -121,7 +122,7 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
     if (spd) {
         for (int r = r0; r < r1; ++r) {
             SPD_HIP(spd_f32::attention_half(c, wr(r), kr(r), x, ybuf));
-            SPD_HIP(spd_common::rank_sum(x, ybuf, 1, (int64_t)slot_n, rbuf, c.s, bo, D.h));   // local fold X + Y_r (+ b)
+            SPD_HIP(spd_common::rank_sum(x, ybuf, 1, (int64_t)c.M * D.h, rbuf, c.s, bo, D.h));   // local fold X + Y_r (+ b)
             SPD_HIP(spd_f32::mlp_half(c, wr(r), rbuf, ybuf, slots + r * slot_n));        // slot = Y_r + Z_r
         }
         *base_out = x;
@@ -133,6 +134,29 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
         *base_out = rbuf;
     }
     return SPD_OK;
+}
+
+// The helper stream of the two-chain model forward and the events that fork to it and join from it: one
+// set per process, created on first use (default priority, non-blocking), never destroyed.
+struct TwoStreams {
+    std::mutex mu;
+    hipStream_t helper = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+};
+TwoStreams *two_streams() {
+    static TwoStreams ts;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        ts.ok = hipStreamCreateWithFlags(&ts.helper, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ts.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ts.join, hipEventDisableTiming) == hipSuccess;
+    });
+    if (!ts.ok) {
+        std::snprintf(g_hip_msg, sizeof(g_hip_msg), "could not create the helper stream of the two-chain model forward");
+        return nullptr;
+    }
+    return &ts;
 }
 
 // spd_block_forward() and its variant without allocations differ only in where the workspace comes from
@@ -175,8 +199,11 @@ int spd_workspace_init(const spd_ctx *ctx, void *workspace, void *stream) {
     const spd_dims &D = ctx->D;
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
-    SPD_HIP(hipMemcpyAsync(ws + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
-    SPD_HIP(hipMemcpyAsync(ws + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
+    for (int k = 0; k < (D.ws_dual ? 2 : 1); ++k) {      // a workspace for two chains holds the table twice
+        char *half = ws + (size_t)k * D.ws_single;
+        SPD_HIP(hipMemcpyAsync(half + D.ws_cos, ctx->rope_cos.data(), ctx->rope_cos.size() * 4, hipMemcpyHostToDevice, s));
+        SPD_HIP(hipMemcpyAsync(half + D.ws_sin, ctx->rope_sin.data(), ctx->rope_sin.size() * 4, hipMemcpyHostToDevice, s));
+    }
     SPD_HIP(hipStreamSynchronize(s));
     return SPD_OK;
 }
@@ -220,33 +247,95 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
     clear_stale_hip_error();
     const bool bf = D.dtype == SPD_BF16;
     int64_t syncs = 0;
-    const float *x = x_in;
-    if (bf) {
-        SPD_HIP(spd_bf16::prep(c, x_in, nullptr, 0, nullptr, (const float *)((const char *)layer_weights[0] + D.w_g1),
-                               true, 0));
-        c.nch1 = spd_bf16::prep_chunks(c);
+
+    // One chain of launches per half of the sequences, or a single chain for the whole call.  A prefill is
+    // independent from sequence to sequence all the way through the model, and a chain alternates between
+    // kernels bound by the matrix cores (the projections) and kernels bound by memory (the rank-sums, the
+    // norm preparation, attention's vector work): two chains on two streams let one chain's memory-bound
+    // kernels share the compute units with the other's GEMMs.  Each chain has its own workspace half.
+    struct Chain {
+        spd_call c;
+        const float *x_in, *x;
+        float *slots, *x_out, *layer_out;
+        size_t kv_off;            // byte offset of the chain's first sequence inside a layer's K (and V) region
+        size_t row0;              // first token row of the chain in the call
+    };
+    Chain ch[2];
+    int n_chains = 1;
+    ch[0].c = c; ch[0].x_in = x_in; ch[0].x = x_in; ch[0].slots = slots; ch[0].x_out = x_out; ch[0].kv_off = 0; ch[0].row0 = 0;
+    const bool two = bf && D.ws_dual && rank != SPD_ALL_RANKS && q_len > 1 && batch >= 2 &&
+                     (int64_t)(batch / 2) * q_len >= SPD_DUAL_MIN_TOKENS;
+    TwoStreams *ts = nullptr;
+    std::unique_lock<std::mutex> dual_lock;
+    if (two) {
+        ts = two_streams();
+        if (!ts) return SPD_EHIP;
+        dual_lock = std::unique_lock<std::mutex>(ts->mu);     // the helper stream and its events serve one call at a time
+        n_chains = 2;
+        const int b0 = (batch + 1) / 2, b1 = batch - b0;
+        const size_t es = 2, seq_bytes = (size_t)D.kv * D.max_ctx * D.d * es;
+        for (int k = 0; k < 2; ++k) {
+            Chain &h = ch[k];
+            const int bb = k ? b1 : b0, first = k ? b0 : 0;
+            h.c = c;
+            h.c.batch = bb;
+            h.c.M = bb * q_len;
+            std::memset(&h.c.pos, 0, sizeof(h.c.pos));
+            for (int i = 0; i < bb; ++i) h.c.pos.pos[i] = c.pos.pos[first + i];
+            h.row0 = (size_t)first * q_len;
+            h.x_in = h.x = x_in + h.row0 * D.h;
+            h.slots = slots + h.row0 * D.h;
+            h.x_out = x_out + h.row0 * D.h;
+            h.kv_off = (size_t)first * seq_bytes;
+            if (k) {
+                h.c.ws = c.ws + D.ws_single;
+                h.c.s = ts->helper;
+            }
+        }
+        // fork: the second chain starts when everything enqueued on the caller's stream so far is done
+        SPD_HIP(hipEventRecord(ts->fork, c.s));
+        SPD_HIP(hipStreamWaitEvent(ts->helper, ts->fork, 0));
+    }
+    for (int k = 0; k < n_chains; ++k) {
+        Chain &h = ch[k];
+        h.layer_out = layer_out;
+        if (bf) {
+            SPD_HIP(spd_bf16::prep(h.c, h.x_in, nullptr, 0, nullptr, (const float *)((const char *)layer_weights[0] + D.w_g1),
+                                   true, 0));
+            h.c.nch1 = spd_bf16::prep_chunks(h.c);
+        }
     }
     for (int l = 0; l < L; ++l) {
-        const float *base = nullptr, *bias = nullptr;
         const bool more = l + 1 < L;
         const float *g1 = (bf && more) ? (const float *)((const char *)layer_weights[l + 1] + D.w_g1) : nullptr;
-        bool end_done = false;
-        const int rc2 = block_core(ctx, c, spd_mask[l], rank, (const char *)layer_weights[l], (char *)layer_kv[l], x,
-                                   slots, &base, &bias, &syncs, x_out, g1, &end_done);
-        if (rc2 != SPD_OK) return rc2;
-        // end-of-block sync point; in the bf16 path it also prepares the next block's first norm
-        if (end_done) {
-            c.nch1 = D.h / 32;                   // the fused epilogue left one partial per pair of n-tiles
-        } else if (bf) {
-            SPD_HIP(spd_bf16::prep(c, base, slots, D.tp, x_out, g1, more, 0, bias));
-            c.nch1 = spd_bf16::prep_chunks(c);
-        } else if (c.on(SPD_STAGE_PREP)) {
-            SPD_HIP(spd_common::rank_sum(base, slots, D.tp, (int64_t)c.M * D.h, x_out, c.s, bias, D.h));
+        for (int k = 0; k < n_chains; ++k) {
+            Chain &h = ch[k];
+            const float *base = nullptr, *bias = nullptr;
+            bool end_done = false;
+            int64_t kept = 0;
+            const int rc2 = block_core(ctx, h.c, spd_mask[l], rank, (const char *)layer_weights[l],
+                                       (char *)layer_kv[l] + h.kv_off, h.x, h.slots, &base, &bias, &kept, h.x_out, g1, &end_done);
+            if (rc2 != SPD_OK) return rc2;
+            if (k == 0) syncs += kept;
+            // end-of-block sync point; in the bf16 path it also prepares the next block's first norm
+            if (end_done) {
+                h.c.nch1 = D.h / 32;                   // the fused epilogue left one partial per pair of n-tiles
+            } else if (bf) {
+                SPD_HIP(spd_bf16::prep(h.c, base, h.slots, D.tp, h.x_out, g1, more, 0, bias));
+                h.c.nch1 = spd_bf16::prep_chunks(h.c);
+            } else if (h.c.on(SPD_STAGE_PREP)) {
+                SPD_HIP(spd_common::rank_sum(base, h.slots, D.tp, (int64_t)h.c.M * D.h, h.x_out, h.c.s, bias, D.h));
+            }
+            h.x = h.x_out;
+            if (layer_out)       // test tap: every block's output
+                SPD_HIP(hipMemcpyAsync(layer_out + ((size_t)l * c.M + h.row0) * D.h, h.x_out, (size_t)h.c.M * D.h * 4,
+                                       hipMemcpyDeviceToDevice, h.c.s));
         }
         syncs += 1;
-        x = x_out;
-        if (layer_out)       // test tap: every block's output
-            SPD_HIP(hipMemcpyAsync(layer_out + (size_t)l * c.M * D.h, x_out, (size_t)c.M * D.h * 4, hipMemcpyDeviceToDevice, c.s));
+    }
+    if (two) {       // join: the caller's stream continues when the second chain is done
+        SPD_HIP(hipEventRecord(ts->join, ts->helper));
+        SPD_HIP(hipStreamWaitEvent(c.s, ts->join, 0));
     }
     if (n_rank_sums) *n_rank_sums = syncs;
     return SPD_OK;

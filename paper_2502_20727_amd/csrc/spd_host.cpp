@@ -167,7 +167,9 @@ void compute_dims(const spd_config &c, spd_dims &D) {
         D.ws_gu = o; o = spd_align256(o + M * 2 * f * 4);
         D.ws_uhat = o; o = spd_align256(o + M * f * 4);
     }
-    D.workspace_bytes = o;
+    D.ws_single = o;
+    D.ws_dual = bf && c.max_batch >= 2 && c.max_tokens / 2 >= SPD_DUAL_MIN_TOKENS;
+    D.workspace_bytes = D.ws_dual ? 2 * o : o;
 }
 
 // Power of two k for a matrix whose largest magnitude is mx: the largest k with mx 2^k < 2^15 (half of

@@ -33,6 +33,7 @@ constexpr int SPD_FRAG_ELEMS = 512;   // 16 x 32
 constexpr int SPD_MAX_SPLITS = 64;    // decode attention: context splits per (sequence, KV head)
 constexpr int SPD_AUTO_SPLIT_TOKENS = 16;    // SPD_SPLIT_AUTO: calls of more than this many tokens carry the QKV projection's input as a hi + lo pair
 constexpr int SPD_MAX_QKV_SLICES = 8;  // K slices of a decode QKV projection that the attention kernel adds up itself
+constexpr int SPD_DUAL_MIN_TOKENS = 1024;   // a prefill runs as two chains when each half has at least this many tokens
 constexpr int SPD_MAX_KPART = 4096;   // split-K partial tiles (pairs x splits) a GEMV may park in the workspace
 constexpr int SPD_MID_KPART = 2304 * 8;   // ... and a call of 17 .. 128 tokens (pairs x splits x m-tiles)
 
@@ -151,6 +152,10 @@ struct spd_dims {
     // workspace (bytes)
     size_t ws_cos, ws_sin, ws_xhat, ws_xhat2, ws_q, ws_ahat, ws_y, ws_r, ws_ss1, ws_ss2, ws_uhat,
         ws_apart, ws_kpart, ws_qkv, ws_gu, workspace_bytes;
+    // a context for long prefills of several sequences lays out two such workspaces back to back (ws_single bytes
+    // each), one per chain of the two-chain model forward
+    int ws_dual;
+    size_t ws_single;
     // bf16 path: every packed activation buffer has a second plane (the "lo" halves) this many
     // elements after the first
     size_t pl_x, pl_a, pl_u;
@@ -186,6 +191,7 @@ struct spd_call {
     const spd_dims *D;
     hipStream_t s;
     int batch, q_len, M;
+    size_t slot_stride;       // elements between two ranks' slots (a chain of a two-chain call keeps the whole call's)
     spd_positions pos;
     int max_pos_end;          // max over sequences of positions[b] + q_len
     // bf16 path: which projection inputs are carried as hi + lo pairs of fp16 values

@@ -204,16 +204,21 @@ __device__ __forceinline__ float4 ldnt4(const float *p) {
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
+// The launch is a fixed, small number of workgroups that walk the (chunk, m-tile) items with a stride: a
+// workgroup with 16 KiB of LDS and one wave per SIMD fits beside a workgroup of the LDS-tiled GEMM on the same
+// compute unit, so that in a two-chain prefill this memory-bound kernel and the other chain's GEMM share the chip.
 template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
                                                    const float *__restrict__ gain, __bf16 *__restrict__ xhat,
                                                    __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h,
-                                                   int m_pad, const float *__restrict__ bias) {
-    constexpr int PITCH = NP * 256 + 8;      // bf16 elements; the pad spreads the fragment reads over the banks
+                                                   int m_pad, const float *__restrict__ bias, int n_chunks, int n_items) {
+    constexpr int PITCH = NP * 256;          // bf16 elements (no pad: 16 KiB for both planes)
     __shared__ __attribute__((aligned(16))) __bf16 tile[2][16][PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int chunk0 = blockIdx.x * NP, mt = blockIdx.y, KT = h >> 5;
+    const int KT = h >> 5;
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int chunk0 = (item % n_chunks) * NP, mt = item / n_chunks;
     const int col = chunk0 * 256 + lane * 4;           // piece q: + 256 q
     float4 gn[NP], bs[NP];
 #pragma unroll
@@ -291,7 +296,7 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
             }
         }
     }
-    if (!xhat) return;
+    if (!xhat) continue;
     __syncthreads();
     // wave w writes fragments 2 NP w .. 2 NP w + 2 NP - 1 of the workgroup's 8 NP k-tiles
 #pragma unroll
@@ -301,6 +306,8 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
         *(bf16x8 *)(xhat + fo) = *(const bf16x8 *)&tile[0][r][kt * 32 + g * 8];
         if (xlo) *(bf16x8 *)(xlo + fo) = *(const bf16x8 *)&tile[1][r][kt * 32 + g * 8];
     }
+    __syncthreads();      // the tile is free for the next item
+  }
 }
 
 // The sum over the ranks at a sync point, for one rank whose own partial is still in registers:
@@ -2073,6 +2080,7 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
 
 // chunking of the sum-of-squares partials written by prep()
 // k-tiles per wave of k_prep: enough waves to occupy the chip at every call size
+constexpr int PREP_ROWS_WGS = 512;       // workgroups of the row-wise preparation kernel (two per compute unit)
 inline int prep_tpw(int M) { return M <= 64 ? 1 : (M <= 512 ? 2 : 8); }
 inline int prep_nch(int h, int M) { return (int)cdiv(h / 32, prep_tpw(M)); }
 
@@ -2092,11 +2100,14 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     spd_stage_scope prof(c, SPD_STAGE_PREP);
     // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
     if (tpw == 8 && D.h % 256 == 0)
-        hipLaunchKernelGGL(k_prep_rows<1>, dim3(D.h / 256, cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias);
+    {
+        const int n_chunks = D.h / 256, n_items = n_chunks * (int)cdiv(c.M, 16);
+        hipLaunchKernelGGL(k_prep_rows<1>, dim3(n_items < PREP_ROWS_WGS ? n_items : PREP_ROWS_WGS), dim3(256), 0, c.s, base, slots,
+                           n_slots, c.slot_stride, out, gain, xhat, xlo, ss, c.M, D.h, D.m_pad, bias, n_chunks, n_items);
+    }
     else
         hipLaunchKernelGGL(k_prep, dim3(cdiv(nch, 4), cdiv(c.M, 16)), dim3(256), 0, c.s, base, slots, n_slots,
-                           (size_t)c.M * D.h, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
+                           c.slot_stride, out, gain, xhat, xlo, ss, c.M, D.h, tpw, D.m_pad, bias);
     return hipGetLastError();
 }
 
@@ -2279,7 +2290,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
             EpiOT<true> e2;
             fill_o(e2);
             e2.spd = 2;
-            e2.slots = mid->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = mid->tp; e2.rank = mid->rank; e2.rbuf = mid->rbuf;
+            e2.slots = mid->slots; e2.slot_stride = c.slot_stride; e2.tp = mid->tp; e2.rank = mid->rank; e2.rbuf = mid->rbuf;
             if (M <= 16)
                 SPD_TRY(c.sp_a ? launch_gemv<true>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2)
                                : launch_gemv<false>(c, wo.w, ahat, ahat + D.pl_a, D.h / 32, qd / 32, e2));
@@ -2357,7 +2368,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
         e2.x_out = nullptr; e2.ss1 = nullptr; e2.xhat = nullptr; e2.xlo = nullptr;
         e2.wsc = wdn.wsc;
         if (do_fuse) {
-            e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = (size_t)M * D.h; e2.tp = fuse->tp;
+            e2.base = fuse->base; e2.slots = fuse->slots; e2.slot_stride = c.slot_stride; e2.tp = fuse->tp;
             e2.rank = fuse->rank; e2.x_out = fuse->x_out; e2.g1 = fuse->next_g1; e2.bias = fuse->bias; e2.ss1 = (float *)(c.ws + D.ws_ss1);
             if (fuse->next_g1) {
                 e2.xhat = (__bf16 *)(c.ws + D.ws_xhat);

@@ -577,3 +577,65 @@ def test_full_depth_model_forward(gpu, name, n_syncs):
     # errors of the blocks add up along the chain (each at most 2e-2, amplified or damped by what follows):
     # the end-to-end figure is reported relative to the output's rms and bounded by the sum of the per-block bounds
     assert e2e <= 2e-2 * w.n_layers * max(1.0, rms)
+
+
+# ------------------------------------------------------------------------------------------------
+# a long prefill of several sequences: spd_model_forward runs it as two chains on two streams
+# ------------------------------------------------------------------------------------------------
+TWO_CHAIN = Workload(name="two-chain-bf16", hidden=256, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=832, n_layers=3,
+                     tp=4, dtype=BF16, seed=19, batch=3, q_len=1100, ctx=1120, mask=(1, 0, 1))
+
+
+def test_bf16_two_chain_prefill(gpu):
+    """Three sequences of 1100 tokens (the second one continuing after 5 cached positions): the model
+    forward cuts the call into a chain of two sequences and a chain of one and runs them on two streams.
+    Every block's output is checked against the oracle's block fed the same input, and the result against
+    what the blocks give one after the other on one stream (spd_block_forward)."""
+    import torch
+    w, rank = TWO_CHAIN, 1
+    batch, q_len, positions = w.batch, w.q_len, [0, 5, 0]
+    M = batch * q_len
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    case = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=w.ctx, max_tokens=M)
+    x, slots = case.to_dev(X), case.to_dev(peers)
+    out = torch.empty_like(x)
+    taps = torch.zeros((w.n_layers, M, w.hidden), dtype=torch.float32, device=gpu)
+    say(f"two-chain prefill: {batch} x {q_len} tokens")
+    syncs = B.spd_model_forward_staged(case.dev.ctx, w.mask, rank, case.dev.weights, case.dev.kv, positions, batch, q_len,
+                                       x, slots, out, case.dev.workspace, layer_out=taps)
+    torch.cuda.synchronize()
+    assert syncs == B.spd_sync_count(case.dev.ctx, w.mask) == 4
+    got = taps.cpu().numpy()
+    assert np.array_equal(got[-1], out.cpu().numpy())
+    # the same blocks one after the other, one chain
+    ref = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=w.ctx, max_tokens=M)
+    xr, sr = ref.to_dev(X), ref.to_dev(peers)
+    for l in range(w.n_layers):
+        o = torch.empty_like(xr)
+        B.spd_block_forward(ref.dev.ctx, l, w.mask[l], rank, ref.dev.weights[l], ref.dev.kv[l], positions, batch, q_len, xr,
+                            sr, o, ref.dev.workspace)
+        xr = o
+    torch.cuda.synchronize()
+    # (not bit for bit: which kernel runs a projection depends on the number of tokens of the call or chain, and
+    # the kernels add up K in different orders)
+    d = float(np.max(np.abs(xr.cpu().numpy() - got[-1])))
+    say(f"  two chains vs one chain of blocks: max difference {d:.2e}")
+    assert d <= 2e-3
+    assert float(np.max(np.abs(sr.cpu().numpy() - slots.cpu().numpy()))) <= 2e-3
+    for l in (0, w.n_layers - 1):
+        k0, v0 = case.dev.read_kv(l, 0, batch, max(positions) + q_len)
+        k1, v1 = ref.dev.read_kv(l, 0, batch, max(positions) + q_len)
+        # bf16 values on both sides; a last-bit disagreement is one unit in the last place
+        assert np.max(np.abs(k0 - k1)) <= 2.0 ** -7 * np.max(np.abs(k1)) and np.max(np.abs(v0 - v1)) <= 2.0 ** -7 * np.max(np.abs(v1))
+    ref.close()
+    # block by block against the oracle
+    o_slots = peers.astype(np.float64)
+    worst = 0.0
+    for l in range(w.n_layers):
+        x_in = X if l == 0 else got[l - 1]
+        want = O.block_single_rank(case.sh, x_in, case.shards[l][0], case.caches[l][0], positions, batch, q_len, w.mask[l],
+                                   rank, o_slots)
+        worst = max(worst, assert_close(got[l], want, w, f"two-chain block {l}"))
+    say(f"  worst block max err {worst:.2e}")
+    case.close()
