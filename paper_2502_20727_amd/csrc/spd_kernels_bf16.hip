@@ -1251,6 +1251,9 @@ struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
     static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
 };
+struct GemmWide {     // 8 waves, 160 x 256, every wave all 10 n-tiles of 2 m-tiles: for split activations and few n-tiles
+    static constexpr int WN = 1, WM = 8, TI = 10, TJ = 2, KPS = 2, MINB = 1;      // (80 n-tiles x 512 m-tiles = exactly 256 tiles)
+};
 // XS: the activations are hi + lo pairs (second plane at Xlo).  A step then covers ONE k-tile: its weight
 // fragments and, per m-tile, the hi and the lo fragment of that k-tile, so the copies and the fragment
 // reads of the weights are shared by both passes and any number of k-tiles will do.
@@ -1264,8 +1267,9 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     constexpr int KW = XS ? 1 : KPS;                                     // weight fragments per tile row and step
     constexpr int KX = XS ? 2 : KPS;                                     // activation fragments per tile row and step
     constexpr int GL_STAGE = (GL_BN * KW + GL_BM * KX) * 1024;
-    constexpr int GL_FPW = (GL_BN + GL_BM) / (GL_WN * GL_WM);            // tile rows copied per wave and stage
-    static_assert((GL_BN + GL_BM) % (GL_WN * GL_WM) == 0 && GL_TI % 2 == 0, "tile shape");
+    constexpr int GL_FPW = (GL_BN + GL_BM + GL_WN * GL_WM - 1) / (GL_WN * GL_WM);   // tile rows copied per wave and stage
+    constexpr bool RAGGED = (GL_BN + GL_BM) % (GL_WN * GL_WM) != 0;      // the last waves copy fewer rows
+    static_assert(GL_TI % 2 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wn = wave % GL_WN, wm = wave / GL_WN;
@@ -1297,7 +1301,8 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     bool isx[GL_FPW];
 #pragma unroll
     for (int i = 0; i < GL_FPW; ++i) {
-        const int row = wave * GL_FPW + i;
+        int row = wave * GL_FPW + i;
+        if (RAGGED && row >= GL_BN + GL_BM) row = GL_BN + GL_BM - 1;     // never issued (see issue())
         isx[i] = row >= GL_BN;
         if (!isx[i]) {
             int t = nt0 + row;
@@ -1315,6 +1320,7 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     auto issue = [&](int stage, int ks) {
 #pragma unroll
         for (int i = 0; i < GL_FPW; ++i) {
+            if (RAGGED && wave * GL_FPW + i >= GL_BN + GL_BM) continue;
             const __bf16 *g = src[i] + (size_t)ks * ((XS ? 1 : KPS) * 512);
             char *l = lds + stage * GL_STAGE + loff[i];
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
@@ -1443,6 +1449,13 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
     // fill one round better
     const int n_mtiles = (c.M + 15) / 16;
     const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
+    if constexpr (XS) {
+        // split activations, few n-tiles: 160 x 256 tiles when they come to one full round of the chip with less work
+        // per tile than the other shapes (the QKV projection of the 70B shard: 8 x 32 = 256 tiles)
+        const int wide = ((2 * n_pairs + 9) / 10) * ((n_mtiles + 15) / 16);
+        if (big < 224 && wide <= 256 && wide > tall && 160 * ((wide + 255) / 256) < 192 * ((tall + 255) / 256))
+            return launch_gemm_lds_cfg<GemmWide, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+    }
     if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
     // a last round that would occupy at most half of the compute units runs as twice as many half tiles
     // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)
