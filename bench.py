@@ -41,47 +41,69 @@ def log(*a):
 # ------------------------------------------------------------------------------------------------
 # HBM traffic per launch, read from the committed rocprofv3 counter summary (never typed in here)
 # ------------------------------------------------------------------------------------------------
+def profile_lines(tag: str):
+    """Key=value lines of the committed rocprofv3 summaries under profiles/ that start with `tag`."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return
+    for fn in sorted(os.listdir(pdir)):
+        if not fn.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, fn)):
+            if line.startswith(tag + " "):
+                kv = dict(re.findall(r"(\w+)=(\"[^\"]*\"|\S+)", line))
+                yield fn, {k: v.strip('"') for k, v in kv.items()}
+
+
 def measured_traffic(workload: str, stage: str, kernel: str):
-    """Bytes per launch of `stage` of `workload` from profiles/hbm_traffic__*.txt, or (None, why).
+    """Bytes per launch of `stage` of `workload` from the committed counter summary, or (None, why).
 
     The summary carries one line per measured stage:
       TRAFFIC workload=<name> stage=<stage> kernel=<label> fetch=<FETCH_SIZE> write=<WRITE_SIZE> fetch_kib=<f> write_kib=<f>
     (counter averages per dispatch and what one counter unit is worth, from the copy calibration in the
     same file).  The figure is only used if the kernel it was measured on is the kernel launched now."""
-    pdir = os.path.join(ROOT, "profiles")
-    if not os.path.isdir(pdir):
-        return None, "no profiles/ folder"
-    for fn in sorted(os.listdir(pdir)):
-        if not fn.startswith("hbm_traffic") or not fn.endswith(".txt"):
+    for fn, kv in profile_lines("TRAFFIC"):
+        if kv.get("workload") != workload or kv.get("stage") != stage:
             continue
-        for line in open(os.path.join(pdir, fn)):
-            if not line.startswith("TRAFFIC "):
-                continue
-            kv = dict(re.findall(r"(\w+)=(\"[^\"]*\"|\S+)", line))
-            kv = {k: v.strip('"') for k, v in kv.items()}
-            if kv.get("workload") != workload or kv.get("stage") != stage:
-                continue
-            if kv.get("kernel") != kernel:
-                return None, f"profiles/{fn} holds {kv.get('kernel')!r} for this stage, the kernel launched is {kernel!r}"
-            b = float(kv["fetch"]) * float(kv["fetch_kib"]) * 1024 + float(kv["write"]) * float(kv["write_kib"]) * 1024
-            return int(b), f"profiles/{fn}"
+        if kv.get("kernel") != kernel:
+            return None, f"profiles/{fn} holds {kv.get('kernel')!r} for this stage, the kernel launched is {kernel!r}"
+        b = float(kv["fetch"]) * float(kv["fetch_kib"]) * 1024 + float(kv["write"]) * float(kv["write_kib"]) * 1024
+        return int(b), f"profiles/{fn}"
     return None, "no TRAFFIC line for this workload and stage"
+
+
+def profiled_duration(workload: str, stage: str, kernel: str):
+    """rocprofv3's duration (us per layer) of the stage's kernel(s), from the committed kernel-trace summary:
+    (us, scope, source) or (None, None, why).  The summary's line is
+      DURATION workload=.. stage=.. kernel=.. avg_us=<per launch> per_layer=<launches per layer> scope=<which launches>"""
+    for fn, kv in profile_lines("DURATION"):
+        if kv.get("workload") != workload or kv.get("stage") != stage:
+            continue
+        if kv.get("kernel") != kernel:
+            return None, None, f"profiles/{fn} holds {kv.get('kernel')!r} for this stage, the kernel launched is {kernel!r}"
+        return float(kv["avg_us"]) * int(kv.get("per_layer", 1)), kv.get("scope", "in-model"), f"profiles/{fn}"
+    return None, None, "no DURATION line for this workload and stage"
 
 
 def stage_kernel(w, stage: str) -> str:
     """Label of the kernel(s) the library launches for `stage` at this call size (mirrors its dispatch)."""
     M = w.batch * w.q_len
     f_pairs = (w.ffn_per_rank + 31) // 32 * 32 // 16
+    two_chains = w.q_len > 1 and w.batch >= 2 and (w.batch // 2) * w.q_len >= 1024
     if stage == "gateup":
         if M > 512:
-            return "k_gemm_lds<EpiGU<true>,GemmBig,false>+k_gemm_lds<EpiGU<true>,GemmHalf,false>"
+            tiles = ((2 * f_pairs + 15) // 16) * (((M // 2 if two_chains else M) // 16 + 15) // 16)
+            one = "k_gemm_lds<EpiGU,GemmBig,false>"
+            if tiles > 256 and 0 < tiles % 256 <= 128:
+                one += "+k_gemm_lds<EpiGU,GemmHalf,false>"
+            return one + ("x2" if two_chains else "")          # x2: one launch per chain of a two-chain prefill
         if M > 16 and f_pairs >= 128:
-            return "k_mid<MT>+k_mid_finish<EpiGU<true>>"
+            return "k_mid<8>+k_mid_finish<EpiGU>"
         if M > 16:
-            return "k_skinny<8,MT,false,0,EpiGU<true>>"
+            return "k_skinny<8,MT,false,0,EpiGU>"
         if f_pairs >= 192 or (f_pairs >= 64 and f_pairs % 256 != 0):
-            return "k_gemv<16,2,true,0,EpiGU<false>>"            # 16-column tiles, or the decode-only copy with narrow groups
-        return "k_gemv<8,2,true,1,EpiGU<false>>+k_gemv_finish"
+            return "k_gemv<16,2,false,0,EpiGU>"            # 16-column tiles, or the decode-only copy with narrow groups
+        return "k_gemv<8,2,false,1,EpiGU>+k_gemv_finish<EpiGU>"
     return stage
 
 
@@ -171,9 +193,11 @@ class Runner:
 
     def stage_in_model(self, mask, stage, reps):
         """Mean duration of the stage's launches inside the full forward: the library brackets every launch of the
-        stage with a pair of HIP events on the launch stream (eager launches: events cannot be captured)."""
+        stage with a pair of HIP events on the launch stream (eager launches: events cannot be captured).
+        stage "empty": a bracket with nothing inside, i.e. what the pair of events itself adds."""
         torch, B = self.torch, self.B
-        timer = B.spd_stage_timer_create(B.STAGES[stage], (self.w.n_layers + 1) * reps)
+        sid = B.SPD_STAGE_EMPTY if stage == "empty" else B.STAGES[stage]
+        timer = B.spd_stage_timer_create(sid, 2 * (self.w.n_layers + 1) * reps)
         try:
             self.forward(mask)
             torch.cuda.synchronize()
@@ -280,32 +304,48 @@ def measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph=True, sync
     work = algorithmic_work(w)
     reps = 3 if prefill else 10
     train, inmodel = {}, {}
+    _, pair_us, _ = r.stage_in_model(w.mask, "empty", 2)           # an event pair with nothing between
     for st in ("gateup", "down", "qkv", "attn", "o", "prep"):
         train[st] = round(r.stage_train(w.mask, st, reps if st == "gateup" else max(1, reps // 2)), 2)
         n, mean_us, min_us = r.stage_in_model(w.mask, st, 2)
-        inmodel[st] = dict(mean_us=round(mean_us, 2), min_us=round(min_us, 2), launches=n)
+        inmodel[st] = dict(raw_mean_us=round(mean_us, 2), raw_min_us=round(min_us, 2), launches=n)
     log(f"  us per launch, stage following itself under a HIP graph: {train}")
-    log(f"  us per launch inside the full forward (eager, HIP events): { {k: v['mean_us'] for k, v in inmodel.items()} }")
+    log(f"  us per launch inside the full forward (eager, HIP events; an empty event pair alone reads {pair_us:.2f} us): "
+        f"{ {k: v['raw_mean_us'] for k, v in inmodel.items()} }")
 
-    # dominant kernel: the gate/up projection + SwiGLU (55 % of the weights, 55 % of the flops); its duration is the
-    # one measured inside the full forward
+    # dominant kernel: the gate/up projection + SwiGLU (55 % of the weights, 55 % of the flops).  Its mean launch
+    # duration is taken live with HIP events around a HIP graph of that kernel over every layer's weights (`mean_us`);
+    # beside it: the same kernel bracketed by events inside the full eager forward (raw, and what an empty bracket
+    # costs), and rocprofv3's in-model average from the committed kernel trace.
     g = inmodel["gateup"]
-    mean_us = g["mean_us"]
+    mean_us = train["gateup"]
     kernel = stage_kernel(w, "gateup")
+    per = work["gateup"]["flops"] / 1e12 if M > 512 else work["gateup"]["bytes"] / 1e9
     if M > 512:      # a dense contraction bound by the matrix cores
-        roof = dict(bound="mfma", achieved=work["gateup"]["flops"] / (mean_us * 1e-6) / 1e12, peak=MFMA_PEAK / 1e12,
-                    unit="TFLOP/s")
+        roof = dict(bound="mfma", achieved=per / (mean_us * 1e-6), peak=MFMA_PEAK / 1e12, unit="TFLOP/s")
     else:            # bound by streaming its weights once from HBM
-        roof = dict(bound="hbm", achieved=work["gateup"]["bytes"] / (mean_us * 1e-6) / 1e9, peak=HBM_PEAK / 1e9, unit="GB/s")
+        roof = dict(bound="hbm", achieved=per / (mean_us * 1e-6), peak=HBM_PEAK / 1e9, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
     traffic, src = measured_traffic(w.name, "gateup", kernel)
+    prof_us, prof_scope, prof_src = profiled_duration(w.name, "gateup", kernel)
+    per_layer = 2 if kernel.endswith("x2") else 1
     roof.update(traffic=traffic, traffic_source=src, kernel=kernel, stage="gate/up projection + SwiGLU",
-                launches_timed=g["launches"], mean_us=mean_us, min_us=g["min_us"], mean_us_train=train["gateup"],
-                timing="HIP events around every launch of the stage inside the full eager forward; mean_us_train: the "
-                       "stage following itself over all layers in a HIP graph",
-                algorithmic_bytes_per_launch=work["gateup"]["bytes"], algorithmic_flops_per_launch=work["gateup"]["flops"])
+                launches_per_layer=per_layer, layers_timed=reps * w.n_layers, mean_us=mean_us,
+                mean_us_in_model_events=g["raw_mean_us"], event_pair_us=round(pair_us, 2), launches_in_model=g["launches"],
+                mean_us_rocprofv3=prof_us, rocprofv3_scope=prof_scope, rocprofv3_source=prof_src,
+                frac_rocprofv3=(per / (prof_us * 1e-6) / roof["peak"]) if prof_us else None,
+                timing="mean_us, the figure `achieved` uses: per layer (all launches_per_layer launches of the stage: with "
+                       "two chains they run side by side on two streams), HIP events on the launch stream around replays "
+                       "of a HIP graph that launches this stage's kernel for every layer (distinct weights, no cache "
+                       "reuse). mean_us_in_model_events: per launch, HIP events around every launch of the stage inside the "
+                       "full eager forward (they include the bracket itself; event_pair_us is the same bracket with "
+                       "nothing inside). mean_us_rocprofv3: per layer, from the committed rocprofv3 kernel trace of this "
+                       "command (rocprofv3_scope says which launches)",
+                algorithmic_bytes_per_launch=work["gateup"]["bytes"] // per_layer,
+                algorithmic_flops_per_launch=work["gateup"]["flops"] // per_layer)
     res["roofline"] = roof
-    res["stage_us_in_model"] = {k: v["mean_us"] for k, v in inmodel.items()}
+    res["stage_us_in_model_events"] = {k: v["raw_mean_us"] for k, v in inmodel.items()}
+    res["event_pair_us"] = round(pair_us, 2)
     res["stage_us_train"] = train
     res["whole_layer"] = dict(hbm_GBps=work["bytes"] / (us_layer * 1e-6) / 1e9, hbm_frac=work["bytes"] / (us_layer * 1e-6) / HBM_PEAK,
                               mfma_TFLOPs=work["flops"] / (us_layer * 1e-6) / 1e12,
@@ -323,8 +363,10 @@ def measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph=True, sync
 def config_of(w, use_graph):
     return {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_len": w.q_len, "ctx": w.ctx,
             "tp_degree": w.tp, "rank": 0, "spd_layers": int(sum(w.mask)), "launch": "hip-graph" if use_graph else "eager",
-            "operands": "bf16 (MLP inputs as hi+lo pairs)" if w.batch * w.q_len <= 16
-                        else "fp16 activations and fp16-encoded bf16 weights, QKV input as hi+lo pair (act_split AUTO)"}
+            "operands": "fp16 activations (single planes) and fp16-encoded bf16 weights; attention on the bf16 cache"
+                        if w.batch * w.q_len <= 16 else
+                        "fp16 activations and fp16-encoded bf16 weights, QKV input as hi+lo pair (act_split AUTO); "
+                        "attention on the bf16 cache"}
 
 
 def main():
@@ -413,15 +455,15 @@ def main():
         pre["target"] = "north star: >= 50 % MFMA utilisation over the layer (whole_layer.mfma_frac), i.e. <= 1430 us/layer"
         extra["prefill"] = pre
 
-    M = w.batch * w.q_len
     line = {
         "metric": "us_per_layer_per_tp_rank_shard", "value": head["us_per_layer"], "unit": "us/layer", "n_gpus": 1,
         "steps": head["steps"], "warmup": head["warmup"], "ms_per_step": head["ms_per_step"], "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": ("bf16" if M <= 16 else "f16") if w.dtype == 1 else "f32", "data": "synthetic",
+        "dtype": "f16" if w.dtype == 1 else "f32", "data": "synthetic",
         "config": config_of(w, use_graph),
         "tokens_per_s": head["tokens_per_s"], "device_ms_per_step": head["device_ms_per_step"],
-        "whole_layer": head["whole_layer"], "stage_us": head["stage_us_in_model"], "stage_us_train": head["stage_us_train"],
+        "whole_layer": head["whole_layer"], "stage_us": head["stage_us_train"],
+        "stage_us_in_model_events": head["stage_us_in_model_events"], "event_pair_us": head["event_pair_us"],
         "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
         "paper_context": "paper reports ~20% end-to-end latency reduction at <1% accuracy loss for LLaMA2-70B on 8 GPUs "
                          "(other hardware; not comparable to a per-layer shard time)",

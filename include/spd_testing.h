@@ -26,11 +26,14 @@ extern "C" {
 #define SPD_STAGE_DOWN 5    /* down projection + partial-sum fold */
 #define SPD_N_STAGES 6
 #define SPD_ALL_STAGES ((1u << SPD_N_STAGES) - 1u)
+#define SPD_STAGE_EMPTY 6   /* timers only: a pair of events with nothing between them, once per block (what the
+                               bracket itself adds to a measured stage) */
 
 /* A timer for one stage: every launch of that stage inside a call it is handed to is bracketed by
  * a pair of HIP events on the call's stream (so that call must not be under stream capture).
  * Holds room for max_records launches; further launches go untimed.  One timer serves one call at
- * a time.  SPD_EINVAL: unknown stage, max_records <= 0, NULL; SPD_EHIP: event creation failed. */
+ * a time.  `stage` is one of the stages above or SPD_STAGE_EMPTY.  SPD_EINVAL: unknown stage,
+ * max_records <= 0, NULL; SPD_EHIP: event creation failed. */
 typedef struct spd_stage_timer spd_stage_timer;
 int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out);
 /* Waits for the recorded events, returns the number of launches timed and their mean and minimum

@@ -103,6 +103,7 @@ _PROTOS = {
 EXPORTS = tuple(_PROTOS)
 STAGES = {"prep": 0, "qkv": 1, "attn": 2, "o": 3, "gateup": 4, "down": 5}
 SPD_ALL_STAGES = (1 << len(STAGES)) - 1
+SPD_STAGE_EMPTY = len(STAGES)
 
 
 def lib():

@@ -427,7 +427,7 @@ void spd_stage_timer_destroy(spd_stage_timer *t) {
 }
 
 int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out) {
-    if (!out || stage < 0 || stage >= SPD_N_STAGES || max_records <= 0) return SPD_EINVAL;
+    if (!out || stage < 0 || stage > SPD_STAGE_EMPTY || max_records <= 0) return SPD_EINVAL;
     *out = nullptr;
     spd_stage_timer *t = new (std::nothrow) spd_stage_timer();
     if (!t) return SPD_EINVAL;

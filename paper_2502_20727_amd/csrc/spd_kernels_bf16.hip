@@ -2214,6 +2214,8 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         }
     }
 
+    spd_stage_begin(c, SPD_STAGE_EMPTY);      // (timers only) an empty bracket between two kernels of the block
+    spd_stage_end(c, SPD_STAGE_EMPTY);
     const int DT = D.d / 16;
     spd_stage_begin(c, SPD_STAGE_ATTN);
     if (!c.on(SPD_STAGE_ATTN)) {
