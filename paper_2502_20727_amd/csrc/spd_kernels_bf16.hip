@@ -1236,7 +1236,9 @@ __global__ void __launch_bounds__(256) k_qkv_gather(const float *__restrict__ pa
 // contraction elements, double buffered.  The operands already are sequences of 1 KiB MFMA fragments in global
 // memory, so a stage is filled with gfx950's direct global->LDS loads (one instruction per
 // fragment, no staging registers) and read back with conflict-free 16-byte LDS reads.  Each
-// wave owns 4 n-tiles x 8 m-tiles (128 accumulator registers).  One barrier per step.
+// wave owns 4 n-tiles x 8 m-tiles (128 accumulator registers).  One barrier per step.  In the steps of
+// two k-tiles the LDS reads of one k-tile and the copies of a later step are dealt between the MFMAs of
+// the other k-tile, so that neither the LDS nor the load unit is asked for a burst while the matrix cores wait.
 // ------------------------------------------------------------------------------------------
 // Tile shapes.  WN x WM waves, each TI n-tiles x TJ m-tiles; KPS k-tiles per step.
 struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per compute unit (128 KiB of LDS)
@@ -1317,57 +1319,117 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
             loff[i] = GL_BN * (KW * 1024) + (row - GL_BN) * (KX * 1024);
         }
     }
-    auto issue = [&](int stage, int ks) {
-#pragma unroll
-        for (int i = 0; i < GL_FPW; ++i) {
-            if (RAGGED && wave * GL_FPW + i >= GL_BN + GL_BM) continue;
-            const __bf16 *g = src[i] + (size_t)ks * ((XS ? 1 : KPS) * 512);
-            char *l = lds + stage * GL_STAGE + loff[i];
+    // copy number n of a stage (n < GL_NCP): tile row n / CPR of this wave's share, fragment n % CPR of that row
+    constexpr int CPR = XS ? 1 : KPS;
+    constexpr int GL_NCP = GL_FPW * CPR;
+    auto issue_one = [&](int stage, int ks, int n) {
+        const int i = n / CPR, f = n % CPR;
+        if (RAGGED && wave * GL_FPW + i >= GL_BN + GL_BM) return;
+        const __bf16 *g = src[i] + (size_t)ks * (CPR * 512);
+        char *l = lds + stage * GL_STAGE + loff[i];
+        if (f == 0)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                              (__attribute__((address_space(3))) void *)l, 16, 0, 0);
-            if constexpr (XS) {
-                if (isx[i]) {
-                    const __bf16 *g2 = src2[i] + (size_t)ks * 512;
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g2,
-                                                     (__attribute__((address_space(3))) void *)(l + 1024), 16, 0, 0);
-                }
-            } else if (KPS == 2) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                                 (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
+        else
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                             (__attribute__((address_space(3))) void *)l, 16, 1024, 0);
+        if constexpr (XS) {
+            if (isx[i]) {
+                const __bf16 *g2 = src2[i] + (size_t)ks * 512;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g2,
+                                                 (__attribute__((address_space(3))) void *)(l + 1024), 16, 0, 0);
             }
         }
     };
+    auto issue = [&](int stage, int ks) {
+#pragma unroll
+        for (int n = 0; n < GL_NCP; ++n) issue_one(stage, ks, n);
+    };
     const int nks = XS ? KT : KT / KPS;
-    issue(0, 0);
-    for (int ks = 0; ks < nks; ++ks) {
-        const int cur = ks & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's copies into `cur` have landed
-        __syncthreads();                                     // everybody's have, and nobody still reads the other stage
-        if (ks + 1 < nks) issue(cur ^ 1, ks + 1);
-        const char *st = lds + cur * GL_STAGE;
-        // all fragments of the step are requested first, then the MFMAs run in program order
-        // (the scheduling barriers keep the compiler from re-interleaving reads and MFMAs, which
-        // would make it wait for the whole LDS queue before every group of MFMAs)
-        bf16x8 a[KW][GL_TI], b[KX][GL_TJ];
-#pragma unroll
-        for (int kt = 0; kt < KX; ++kt) {
-#pragma unroll
-            for (int j = 0; j < GL_TJ; ++j)
-                b[kt][j] = *(const bf16x8 *)(st + GL_BN * KW * 1024 + ((wm * GL_TJ + j) * KX + kt) * 1024 + lane * 16);
-            if (kt < KW) {
-#pragma unroll
-                for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * KW + kt) * 1024 + lane * 16);
-            }
-        }
-#pragma unroll
-        for (int kt = 0; kt < KX; ++kt)
+    if constexpr (!XS && KPS == 2) {
+        // A step is two k-tiles; the fragments of one k-tile are read from LDS while the MFMAs of the other run.
+        // The barrier sits in the middle of a step: when a wave passes it, everybody has read both k-tiles of the
+        // current stage (so the copies of the step after next may overwrite it) and the next stage has landed (so
+        // its first k-tile can be read during the second half of this step).
+        bf16x8 a0[GL_TI], b0[GL_TJ], a1[GL_TI], b1[GL_TJ];
+        static_assert(2 * (GL_TI + GL_TJ) <= GL_TI * GL_TJ, "one fragment read per two MFMAs must cover a k-tile");
+        const int a_off = (wn * GL_TI * 2) * 1024 + lane * 16, b_off = GL_BN * 2048 + (wm * GL_TJ * 2) * 1024 + lane * 16;
+        // fragment r of k-tile kt of a stage: the wave's TJ activation fragments, then its TI weight fragments
+        auto rd1 = [&](const char *st, int kt, int r, bf16x8(&a)[GL_TI], bf16x8(&b)[GL_TJ]) {
+            if (r < GL_TJ) b[r] = *(const bf16x8 *)(st + b_off + (r * 2 + kt) * 1024);
+            else a[r - GL_TJ] = *(const bf16x8 *)(st + a_off + ((r - GL_TJ) * 2 + kt) * 1024);
+        };
+        // the MFMAs of one k-tile, with the fragment reads of the next one dealt between them (one per two MFMAs):
+        // the LDS works while the matrix cores do, and every fragment is there long before its first use
+        // The copies of a later step are dealt the same way (one instruction per CS MFMAs): a wave that issues
+        // them in one burst waits for the load unit to take them, at the rate the data moves, and multiplies nothing.
+        constexpr int CS = (GL_TI * GL_TJ) / GL_NCP;
+        static_assert(CS >= 1, "more copies per wave than MFMAs per k-tile");
+        auto mm = [&](const bf16x8(&a)[GL_TI], const bf16x8(&b)[GL_TJ], const char *st, int kt, bf16x8(&an)[GL_TI],
+                      bf16x8(&bn)[GL_TJ], bool copy, int cstage, int cks) {
 #pragma unroll
             for (int i = 0; i < GL_TI; ++i)
 #pragma unroll
                 for (int j = 0; j < GL_TJ; ++j) {
-                    acc[i][j] = MFMA16(a[XS ? 0 : kt][i], b[kt][j], acc[i][j]);
-                    if (KX == 2) __builtin_amdgcn_sched_barrier(0);
+                    const int n = i * GL_TJ + j;
+                    acc[i][j] = MFMA16(a[i], b[j], acc[i][j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (n % 2 == 0 && n / 2 < GL_TI + GL_TJ) {
+                        rd1(st, kt, n / 2, an, bn);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (n % CS == CS - 1 && n / CS < GL_NCP) {
+                        if (copy) issue_one(cstage, cks, n / CS);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
+        };
+        issue(0, 0);
+        if (nks > 1) issue(1, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < GL_TI + GL_TJ; ++r) rd1(lds, 0, r, a0, b0);
+        for (int ks = 0; ks < nks; ++ks) {
+            const int cur = ks & 1;
+            mm(a0, b0, lds + cur * GL_STAGE, 1, a1, b1, false, 0, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's copies of the next step have landed
+            __syncthreads();
+            // (in the last step: fragments read and never used)
+            mm(a1, b1, lds + (cur ^ 1) * GL_STAGE, 0, a0, b0, ks + 2 < nks, cur, ks + 2);
+        }
+    } else {
+        issue(0, 0);
+        for (int ks = 0; ks < nks; ++ks) {
+            const int cur = ks & 1;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's copies into `cur` have landed
+            __syncthreads();                                     // everybody's have, and nobody still reads the other stage
+            if (ks + 1 < nks) issue(cur ^ 1, ks + 1);
+            const char *st = lds + cur * GL_STAGE;
+            // all fragments of the step are requested first, then the MFMAs run in program order
+            // (the scheduling barriers keep the compiler from re-interleaving reads and MFMAs, which
+            // would make it wait for the whole LDS queue before every group of MFMAs)
+            bf16x8 a[KW][GL_TI], b[KX][GL_TJ];
+#pragma unroll
+            for (int kt = 0; kt < KX; ++kt) {
+#pragma unroll
+                for (int j = 0; j < GL_TJ; ++j)
+                    b[kt][j] = *(const bf16x8 *)(st + GL_BN * KW * 1024 + ((wm * GL_TJ + j) * KX + kt) * 1024 + lane * 16);
+                if (kt < KW) {
+#pragma unroll
+                    for (int i = 0; i < GL_TI; ++i) a[kt][i] = *(const bf16x8 *)(st + ((wn * GL_TI + i) * KW + kt) * 1024 + lane * 16);
+                }
+            }
+#pragma unroll
+            for (int kt = 0; kt < KX; ++kt)
+#pragma unroll
+                for (int i = 0; i < GL_TI; ++i)
+#pragma unroll
+                    for (int j = 0; j < GL_TJ; ++j) {
+                        acc[i][j] = MFMA16(a[XS ? 0 : kt][i], b[kt][j], acc[i][j]);
+                        if (KX == 2) __builtin_amdgcn_sched_barrier(0);
+                    }
+        }
     }
     // norm factors of all the wave's m-tiles first, so that their loads are in flight together
     float rs[GL_TJ];
