@@ -453,6 +453,15 @@ def main():
         pre["dtype"] = "f16"
         pre["config"] = config_of(wp, use_graph)
         pre["target"] = "north star: >= 50 % MFMA utilisation over the layer (whole_layer.mfma_frac), i.e. <= 1430 us/layer"
+        # context for the fraction of the nominal peak: what the matrix cores sustain with nothing else in the way
+        # (register-resident operands, full grid); on random data the chip lowers its clock
+        scratch = torch.empty(B.SPD_MFMA_PROBE_SCRATCH_BYTES, dtype=torch.uint8, device=dev)
+        tf_r, mhz_r = B.spd_mfma_probe(20000, True, scratch)
+        tf_1, mhz_1 = B.spd_mfma_probe(20000, False, scratch)
+        pre["mfma_probe"] = {"what": "register-resident 16x16x32 fp16 MFMAs, 256 workgroups of 8 waves, no LDS or memory traffic",
+                             "random_data": {"TFLOP/s": round(tf_r, 1), "shader_MHz": round(mhz_r)},
+                             "all_ones": {"TFLOP/s": round(tf_1, 1), "shader_MHz": round(mhz_1)}}
+        log(f"  MFMA probe: random data {tf_r:.0f} TFLOP/s at {mhz_r:.0f} MHz, all ones {tf_1:.0f} TFLOP/s at {mhz_1:.0f} MHz")
         extra["prefill"] = pre
 
     line = {

@@ -58,6 +58,18 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
                              void *stream, int64_t *n_rank_sums, uint32_t stage_mask,
                              spd_stage_timer *timer, float *layer_out);
 
+/* ---------------------------------------------------------------- what the matrix cores sustain
+ * A grid of one workgroup of 8 waves per compute unit (256 workgroups) in which every wave runs `iters`
+ * rounds of 32 independent 16x16x32 fp16 MFMAs on operands it holds in registers: no LDS, no memory
+ * traffic inside the loop.  With random_data != 0 the operands are pseudo-random values in (-2, 2), else
+ * all ones (the chip's clock under load depends on how many bits toggle).  Returns the rate over the
+ * whole launch (HIP events on `stream`) and the shader clock seen by one workgroup in the middle of the
+ * grid (its cycle counter against the 100 MHz real-time counter).  `scratch` is device memory of at least
+ * SPD_MFMA_PROBE_SCRATCH_BYTES that the kernel writes its sums to (so that the loop is not optimised
+ * away).  Synchronises the stream.  SPD_EINVAL: iters <= 0 or NULL pointers; SPD_EHIP as elsewhere. */
+#define SPD_MFMA_PROBE_SCRATCH_BYTES (256 * 512 * 4 + 16)
+int spd_mfma_probe(int32_t iters, int32_t random_data, void *scratch, void *stream, double *tflops, double *mhz);
+
 /* ---------------------------------------------------------------- launch order of the GEMM tiles
  * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
  * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number

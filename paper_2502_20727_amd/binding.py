@@ -97,6 +97,7 @@ _PROTOS = {
     "spd_stage_timer_create": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "spd_stage_timer_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_stage_timer_destroy": (None, [C.c_void_p]),
+    "spd_mfma_probe": (C.c_int, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_gemm_launch_size": (C.c_int, [C.c_int32]),
     "spd_gemm_tile_of": (C.c_int, [C.c_int32] * 7 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
 }
@@ -379,6 +380,19 @@ def spd_stage_timer_read(timer: int):
 
 def spd_stage_timer_destroy(timer: int) -> None:
     lib().spd_stage_timer_destroy(timer)
+
+
+SPD_MFMA_PROBE_SCRATCH_BYTES = 256 * 512 * 4 + 16
+
+
+def spd_mfma_probe(iters: int, random_data: bool, scratch, stream=None):
+    """(TFLOP/s, shader MHz) of register-resident 16x16x32 fp16 MFMAs over a full grid; `scratch` is a device
+    tensor of at least SPD_MFMA_PROBE_SCRATCH_BYTES."""
+    assert scratch.is_cuda and scratch.numel() * scratch.element_size() >= SPD_MFMA_PROBE_SCRATCH_BYTES
+    tf, mhz = C.c_double(), C.c_double()
+    _check(lib().spd_mfma_probe(iters, 1 if random_data else 0, scratch.data_ptr(), _stream_ptr(stream), C.byref(tf),
+                                C.byref(mhz)), "spd_mfma_probe")
+    return tf.value, mhz.value
 
 
 def spd_gemm_launch_size(n_tiles: int) -> int:

@@ -426,6 +426,13 @@ void spd_stage_timer_destroy(spd_stage_timer *t) {
     delete t;
 }
 
+int spd_mfma_probe(int32_t iters, int32_t random_data, void *scratch, void *stream, double *tflops, double *mhz) {
+    if (iters <= 0 || !scratch || !tflops || !mhz) return SPD_EINVAL;
+    clear_stale_hip_error();
+    SPD_HIP(spd_bf16::mfma_probe(iters, random_data, scratch, (hipStream_t)stream, tflops, mhz));
+    return SPD_OK;
+}
+
 int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out) {
     if (!out || stage < 0 || stage > SPD_STAGE_EMPTY || max_records <= 0) return SPD_EINVAL;
     *out = nullptr;

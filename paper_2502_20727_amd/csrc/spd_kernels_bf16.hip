@@ -2479,3 +2479,89 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
 }
 
 }  // namespace spd_bf16
+
+// ------------------------------------------------------------------------------------------
+// Benchmark aid: the rate of the matrix cores on register-resident operands (see spd_testing.h)
+// ------------------------------------------------------------------------------------------
+namespace {
+__global__ void __launch_bounds__(512) k_mfma_probe(int iters, int random_data, float *__restrict__ out,
+                                                    unsigned long long *__restrict__ clk) {
+    // operands: a counter-based hash of (thread, fragment, element) mapped to fp16 values in (-2, 2), or ones
+    bf16x8 a[4], b[8];
+    auto fill = [&](int f) {
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            unsigned h = (threadIdx.x * 12u + f) * 8u + e;
+            h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+            const float x = random_data ? ((float)(h & 0xffffu) - 32767.5f) * (2.0f / 32768.0f) : 1.0f;
+            const _Float16 hf = (_Float16)x;
+            v[e] = __builtin_bit_cast(__bf16, hf);
+        }
+        return v;
+    };
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = fill(i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[j] = fill(4 + j);
+    f32x4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const bool stamp = blockIdx.x == gridDim.x / 2 && threadIdx.x == 0;
+    unsigned long long c0 = 0, w0 = 0;
+    if (stamp) {
+        c0 = clock64();
+        w0 = wall_clock64();
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = MFMA16(a[i], b[j], acc[i][j]);
+    }
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[i][j];
+    if (stamp) {
+        clk[0] = clock64() - c0;
+        clk[1] = wall_clock64() - w0;
+    }
+    out[blockIdx.x * 512 + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
+}  // namespace
+
+namespace spd_bf16 {
+hipError_t mfma_probe(int iters, int random_data, void *scratch, hipStream_t s, double *tflops, double *mhz) {
+    constexpr int kGrid = 256;
+    float *out = (float *)scratch;
+    unsigned long long *clk = (unsigned long long *)((char *)scratch + (size_t)kGrid * 512 * 4);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_mfma_probe, dim3(kGrid), dim3(512), 0, s, 16, random_data, out, clk);      // warm-up
+        e = hipEventRecord(e0, s);
+    }
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_mfma_probe, dim3(kGrid), dim3(512), 0, s, iters, random_data, out, clk);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    unsigned long long hc[2] = {0, 0};
+    if (e == hipSuccess) e = hipMemcpy(hc, clk, sizeof(hc), hipMemcpyDeviceToHost);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return e;
+    const double flops = (double)kGrid * 8 * (double)iters * 32 * 2.0 * 16 * 16 * 32;
+    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    *mhz = hc[1] ? 100.0 * (double)hc[0] / (double)hc[1] : 0.0;      // the real-time counter runs at 100 MHz
+    return hipSuccess;
+}
+}  // namespace spd_bf16

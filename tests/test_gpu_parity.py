@@ -639,3 +639,14 @@ def test_bf16_two_chain_prefill(gpu):
         worst = max(worst, assert_close(got[l], want, w, f"two-chain block {l}"))
     say(f"  worst block max err {worst:.2e}")
     case.close()
+
+
+@pytest.mark.gpu
+def test_mfma_probe_reports_a_plausible_rate():
+    """The benchmark aid runs and lands between a tenth of and the whole nominal fp16 MFMA peak, at a clock the chip has."""
+    import torch
+    scratch = torch.empty(B.SPD_MFMA_PROBE_SCRATCH_BYTES, dtype=torch.uint8, device="cuda:0")
+    for random_data in (True, False):
+        tf, mhz = B.spd_mfma_probe(2000, random_data, scratch)
+        assert 250.0 < tf < 2600.0, (random_data, tf)
+        assert 500.0 < mhz < 2600.0, (random_data, mhz)

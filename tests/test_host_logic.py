@@ -54,6 +54,14 @@ def test_static_entry_point_refuses_a_workspace_that_does_not_fit():
     B.spd_destroy(ctx)
 
 
+def test_mfma_probe_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    tf, mhz = C.c_double(), C.c_double()
+    assert lib.spd_mfma_probe(0, 1, C.c_void_p(8), None, C.byref(tf), C.byref(mhz)) == B.SPD_EINVAL
+    assert lib.spd_mfma_probe(10, 1, None, None, C.byref(tf), C.byref(mhz)) == B.SPD_EINVAL
+    assert lib.spd_mfma_probe(10, 1, C.c_void_p(8), None, None, C.byref(mhz)) == B.SPD_EINVAL
+
+
 def test_strerror():
     assert B.strerror(0) == "ok"
     for code in (B.SPD_EINVAL, B.SPD_EUNSUPPORTED, B.SPD_EHIP, -99):
