@@ -550,6 +550,18 @@ def test_full_depth_model_forward(gpu, name, n_syncs):
     assert syncs == B.spd_sync_count(dev.ctx, w.mask) == n_syncs
     got = taps.cpu().numpy()
     assert np.array_equal(got[-1], out.cpu().numpy())
+    # the launch configuration the bench times: the same call replayed from a HIP graph (twice, into another
+    # output buffer) gives the eager result bit for bit
+    out_g = torch.empty_like(x)
+    slots_g = torch.from_numpy(peers).to(gpu)
+    graph = _capture(torch, lambda: B.spd_model_forward(dev.ctx, w.mask, 0, dev.weights, dev.kv, positions, w.batch, 1, x,
+                                                        slots_g, out_g, dev.workspace))
+    for rep in range(2):
+        out_g.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out_g.cpu().numpy(), got[-1]), f"graph replay {rep} differs from the eager forward"
+    del graph
     dev.close()
     del dev, taps
     torch.cuda.empty_cache()
@@ -638,6 +650,68 @@ def test_bf16_two_chain_prefill(gpu):
                                    rank, o_slots)
         worst = max(worst, assert_close(got[l], want, w, f"two-chain block {l}"))
     say(f"  worst block max err {worst:.2e}")
+    case.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# the launch configuration bench.py times: the whole-model forward replayed from a HIP graph
+# ------------------------------------------------------------------------------------------------
+def _capture(torch, fn):
+    """fn() captured into a graph on a side stream, the way bench.py does it."""
+    stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        fn()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fn()
+    stream.wait_stream(side)
+    torch.cuda.synchronize()
+    return graph
+
+
+@pytest.mark.parametrize("kind", ["decode", "two-chain-prefill"])
+def test_graph_replays_equal_the_eager_forward(gpu, kind):
+    """spd_model_forward captured into a HIP graph and replayed three times, each time on new hidden states written
+    into the same buffers, with the library's own eager forward between the replays: every replay must equal the
+    eager result on the same inputs bit for bit (the path is deterministic).  The two-chain prefill records
+    its second chain on the library's helper stream into the same graph."""
+    import torch
+    if kind == "decode":
+        w, rank, batch, q_len = MID, 3, 2, 1
+        positions = [100, 37]
+        case = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=256, max_tokens=48)
+    else:
+        w, rank, batch, q_len = TWO_CHAIN, 1, TWO_CHAIN.batch, TWO_CHAIN.q_len
+        positions = [0, 5, 0]
+        case = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=w.ctx, max_tokens=batch * q_len)
+    M = batch * q_len
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    x = case.to_dev(X)
+    slots, slots_e = case.to_dev(peers), case.to_dev(peers)
+    out, out_e = torch.empty_like(x), torch.empty_like(x)
+
+    def run(o, sl):
+        return B.spd_model_forward(case.dev.ctx, w.mask, rank, case.dev.weights, case.dev.kv, positions, batch, q_len, x, sl, o,
+                                   case.dev.workspace)
+
+    graph = _capture(torch, lambda: run(out, slots))
+    for rep in range(3):
+        say(f"graph replay {rep} ({kind})")
+        x.copy_(torch.from_numpy(X * (1.0 + 0.25 * rep)).to(gpu))         # new inputs in the captured buffers
+        out.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_slot = out.cpu().numpy().copy(), slots[rank].cpu().numpy().copy()
+        out_e.fill_(-2.0)
+        run(out_e, slots_e)                                                # eager, same inputs, other output buffers
+        torch.cuda.synchronize()
+        assert np.isfinite(got).all()
+        assert np.array_equal(got, out_e.cpu().numpy()), f"replay {rep} differs from the eager forward"
+        assert np.array_equal(got_slot, slots_e[rank].cpu().numpy())
     case.close()
 
 
