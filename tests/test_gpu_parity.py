@@ -512,6 +512,23 @@ def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
     say("  largest per-row max err:", " ".join(f"{rows[i]}:{worst[i]:.1e}" for i in np.argsort(worst)[-6:]))
     err = assert_close(got, want, w, f"prefill rows flag={flag} split={split}")
     say(f"  {len(rows)} sampled rows: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}, rms {rms:.2f}")
+    if split == B.SPD_SPLIT_AUTO:
+        # what the bench launches: spd_model_forward (two chains of 2 x 2048 tokens on two streams) replayed from a
+        # HIP graph; the same sampled rows against the same oracle rows
+        x = case.to_dev(X)
+        slots_g = case.to_dev(peers)
+        out_g = torch.empty_like(x)
+        graph = _capture(torch, lambda: B.spd_model_forward(case.dev.ctx, w.mask, 0, case.dev.weights, case.dev.kv,
+                                                            [0] * full.batch, full.batch, full.q_len, x, slots_g, out_g,
+                                                            case.dev.workspace))
+        out_g.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got_g = out_g[torch.from_numpy(rows).to(gpu)].cpu().numpy()
+        err_g = assert_close(got_g, want, w, f"prefill rows, two chains under a graph, flag={flag}")
+        say(f"  two chains replayed from a graph: max err {err_g:.2e}; against the one-chain block call {np.max(np.abs(got_g - got)):.2e}")
+        assert bool(torch.isfinite(out_g).all())
+        del graph, x, out_g, slots_g
     # properties that hold at any size: peers' slots untouched; finite everywhere
     assert np.array_equal(slots[5][:64].cpu().numpy(), peers[5][:64])
     assert bool(torch.isfinite(slots[0]).all())
