@@ -279,7 +279,13 @@ int spd_block_forward_static(const spd_ctx *ctx, int32_t layer, int32_t spd_flag
  *   slots          one [tp_degree][tokens, hidden] buffer reused by every layer
  *   n_rank_sums    NULL or host int64 receiving the number of rank-sums enqueued
  * x_out may alias x_in.  The rank-sum that ends block l is fused with the first norm's
- * elementwise work of block l+1. */
+ * elementwise work of block l+1.
+ * A bf16 prefill (q_len > 1) of at least two sequences whose halves have 1024 tokens or more, for one rank,
+ * in a context sized for it, is enqueued as two chains of launches, one half of the sequences each: one on
+ * `stream`, one on a stream the library keeps per device (default priority, created on first use), forked
+ * from and joined back to `stream` with events, so that `stream` sees one ordered call and the call can be
+ * captured into a HIP graph.  Calls of this kind from several threads on one device enqueue one after the
+ * other. */
 int spd_model_forward(const spd_ctx *ctx, const uint8_t *spd_mask, int32_t rank,
                       const void *const *layer_weights, void *const *layer_kv,
                       const int32_t *positions, int32_t batch, int32_t q_len,

@@ -137,21 +137,33 @@ int block_core(const spd_ctx *ctx, spd_call &c, int spd, int32_t rank, const cha
 }
 
 // The helper stream of the two-chain model forward and the events that fork to it and join from it: one
-// set per process, created on first use (default priority, non-blocking), never destroyed.
+// set per device, created on first use with that device current (default priority, non-blocking), never
+// destroyed.
 struct TwoStreams {
     std::mutex mu;
     hipStream_t helper = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
-    bool ok = false;
+    bool tried = false, ok = false;
 };
 TwoStreams *two_streams() {
-    static TwoStreams ts;
-    static std::once_flag once;
-    std::call_once(once, [] {
-        ts.ok = hipStreamCreateWithFlags(&ts.helper, hipStreamNonBlocking) == hipSuccess &&
-                hipEventCreateWithFlags(&ts.fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&ts.join, hipEventDisableTiming) == hipSuccess;
-    });
+    constexpr int kMaxDevices = 64;
+    static TwoStreams per_device[kMaxDevices];
+    static std::mutex create_mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        std::snprintf(g_hip_msg, sizeof(g_hip_msg), "no current device for the helper stream of the two-chain model forward");
+        return nullptr;
+    }
+    TwoStreams &ts = per_device[dev];
+    {
+        std::lock_guard<std::mutex> lock(create_mu);
+        if (!ts.tried) {
+            ts.tried = true;
+            ts.ok = hipStreamCreateWithFlags(&ts.helper, hipStreamNonBlocking) == hipSuccess &&
+                    hipEventCreateWithFlags(&ts.fork, hipEventDisableTiming) == hipSuccess &&
+                    hipEventCreateWithFlags(&ts.join, hipEventDisableTiming) == hipSuccess;
+        }
+    }
     if (!ts.ok) {
         std::snprintf(g_hip_msg, sizeof(g_hip_msg), "could not create the helper stream of the two-chain model forward");
         return nullptr;
