@@ -241,13 +241,13 @@ hipError_t mlp_half(const spd_call &c, const char *w, const float *r_in, const f
 namespace spd_bf16 {
 // benchmark aid (spd_testing.h): rate of register-resident MFMAs over a full grid
 hipError_t mfma_probe(int iters, int random_data, void *scratch, hipStream_t s, double *tflops, double *mhz);
-// out = base + sum slots (optional), xhat = bf16(out * g) packed (optional), partial sums of squares
+// out = base + sum slots (optional), xhat = fp16(out * g) packed (optional), partial sums of squares
 // which = 0: the block's first norm (xhat, ss1); which = 1: its second norm (xhat2, ss2)
 // bias (may be NULL): [h], added to `out` after the sum
 hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_slots, float *out,
                 const float *gain, bool want_xhat, int which, const float *bias = nullptr);
 // QKV + rotary + cache append + attention + O projection.
-//   spd = 1: ybuf <- Y_r, xhat2 <- bf16((X + Y_r) g2) and its partial sums of squares
+//   spd = 1: ybuf <- Y_r, xhat2 <- fp16((X + Y_r) g2) and its partial sums of squares
 //   spd = 0: slot <- Y_r
 // With `mid` (TP block, one rank, calls of at most 512 tokens) the O projection's epilogue also performs
 // the kept attention sync point: R = X + sum of the slots (+ bias) -> mid->rbuf, second norm prepared;

@@ -103,7 +103,7 @@ __device__ __forceinline__ float row_rsqrt(const float *__restrict__ ss, int nch
 }
 
 // ------------------------------------------------------------------------------------------
-// prep: out = base + (slot0 + slot1 + ...), xhat = bf16(out * gain) in packed layout (plus its
+// prep: out = base + (slot0 + slot1 + ...), xhat = fp16(out * gain) in packed layout (plus its
 // lo plane), and the partial sums of squares of `out` per (k-chunk, token).  One wave per
 // (m-tile, chunk of `tpw` k-tiles); lane l handles token l%16 and 8 consecutive features.
 // ------------------------------------------------------------------------------------------
