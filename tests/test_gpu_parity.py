@@ -538,6 +538,48 @@ def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
 
 
 # ------------------------------------------------------------------------------------------------
+# the prefill call the bench makes, several blocks deep: two chains, each block's closing sync point
+# preparing the next block's first norm
+# ------------------------------------------------------------------------------------------------
+def test_full_size_prefill_model_forward_three_blocks(gpu):
+    """LLaMA2-70B shard, 4 x 2048 tokens through spd_model_forward (two chains of 2 x 2048 on two streams) over
+    three blocks with mask (1, 0, 1): every block's output on sampled rows against the oracle's block fed the
+    input the library's block had (all rows of it: the keys and values of every token matter), 2e-2 each."""
+    import torch
+    full = workloads.LLAMA70B_PREFILL
+    w = full.with_layers(3).with_mask((1, 0, 1))
+    batch, q_len = full.batch, full.q_len
+    M = batch * q_len
+    positions = [0] * batch
+    rows = np.unique(np.concatenate([np.array([0, 15, 16, 2047, 2048, 4095, 4096, 6144, 8191]),
+                                     np.random.default_rng(11).choice(M, size=40, replace=False)]))
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    say(f"full-size prefill, model forward over {w.n_layers} blocks, mask {w.mask}")
+    case = Case(w, gpu, ranks=[0], positions=positions)
+    x, slots = case.to_dev(X), case.to_dev(peers)
+    out = torch.empty_like(x)
+    taps = torch.zeros((w.n_layers, M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward_staged(case.dev.ctx, w.mask, 0, case.dev.weights, case.dev.kv, positions, batch, q_len, x,
+                                       slots, out, case.dev.workspace, layer_out=taps)
+    torch.cuda.synchronize()
+    assert syncs == B.spd_sync_count(case.dev.ctx, w.mask) == 4
+    assert bool(torch.equal(taps[-1], out))
+    sel = torch.from_numpy(rows).to(gpu)
+    worst = 0.0
+    for l in range(w.n_layers):
+        x_in = X if l == 0 else taps[l - 1].cpu().numpy()
+        want = O.block_single_rank(case.sh, x_in, case.shards[l][0], case.caches[l][0], positions, batch, q_len,
+                                   int(w.mask[l]), 0, peers.astype(np.float64), rows=rows)
+        err = assert_close(taps[l][sel].cpu().numpy(), want, w, f"prefill model forward block {l} (mask {w.mask[l]})")
+        say(f"  block {l}: max err {err:.2e} on {len(rows)} sampled rows")
+        worst = max(worst, err)
+    del taps, x, out, slots
+    case.close()
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------------------
 # the call the bench makes: spd_model_forward at full depth with the workload's own mask
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name,n_syncs", [("7b-decode", 32), ("13b-decode", 50), ("70b-decode", 96)])
