@@ -148,7 +148,15 @@ WIDE_MID = Workload(name="wide-ffn-mid", hidden=1184, n_q_heads=4, n_kv_heads=2,
                     tp=2, dtype=BF16, seed=17, batch=2, q_len=1, ctx=64, mask=(1,))
 
 
-@pytest.mark.parametrize("w", [SMALL, SMALL_MHA, NARROW_GU, WIDE_MID], ids=lambda w: w.name)
+# head sizes other than LLaMA2's 128 and the small shapes' 64: 96 (six 16-wide slices per head, three rotary tile
+# pairs) and 32 (two slices), with grouped KV heads
+SMALL_D96 = Workload(name="small-bf16-d96", hidden=256, n_q_heads=8, n_kv_heads=4, head_dim=96, ffn=512, n_layers=1,
+                     tp=2, dtype=BF16, seed=21, batch=3, q_len=1, ctx=64, mask=(1,))
+SMALL_D32 = Workload(name="small-bf16-d32", hidden=128, n_q_heads=8, n_kv_heads=2, head_dim=32, ffn=256, n_layers=1,
+                     tp=2, dtype=BF16, seed=22, batch=3, q_len=1, ctx=64, mask=(1,))
+
+
+@pytest.mark.parametrize("w", [SMALL, SMALL_MHA, NARROW_GU, WIDE_MID, SMALL_D96, SMALL_D32], ids=lambda w: w.name)
 @pytest.mark.parametrize("batch,q_len,positions", [
     (3, 1, [0, 17, 40]),          # decode, ragged contexts, one sequence with a single key
     (2, 7, [0, 5]),               # 14 tokens: a partial m-tile
@@ -202,7 +210,7 @@ SMALL_H512 = Workload(name="small-bf16-h512", hidden=512, n_q_heads=8, n_kv_head
                       tp=4, dtype=BF16, seed=18, batch=3, q_len=1, ctx=64, mask=(1,))
 
 
-@pytest.mark.parametrize("w", [SMALL, SMALL_H512, SMALL_MHA], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL, SMALL_H512, SMALL_MHA, SMALL_D96, SMALL_D32], ids=lambda w: w.name)
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 @pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS, B.SPD_SPLIT_NEVER], ids=["default", "all-split", "no-split"])
 def test_bf16_long_call_small_shape(gpu, w, flag, split):
@@ -238,8 +246,8 @@ SMALL_BIAS = Workload(name="small-bf16-bias", hidden=256, n_q_heads=8, n_kv_head
 
 
 @pytest.mark.parametrize("w", [TOY_BIAS, SMALL_BIAS], ids=lambda w: w.name)
-@pytest.mark.parametrize("batch,q_len,positions", [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8])],
-                         ids=["decode", "chunk20", "chunk80"])
+@pytest.mark.parametrize("batch,q_len,positions", [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8]), (3, 181, [0, 3, 0])],
+                         ids=["decode", "chunk20", "chunk80", "chunk543"])
 @pytest.mark.parametrize("mode", ["all-ranks", "one-rank"])
 def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
     """Three blocks (SPD, TP, SPD) with a bias of the size of the activations on the output projection:
@@ -247,7 +255,8 @@ def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
     import torch
     M = batch * q_len
     ranks = list(range(w.tp)) if mode == "all-ranks" else [1]
-    case = Case(w, gpu, ranks=ranks, positions=positions, max_ctx=64, max_tokens=max(48, M), bias_std=1.0)
+    case = Case(w, gpu, ranks=ranks, positions=positions, max_ctx=max(64, (max(positions) + q_len + 31) // 32 * 32), max_tokens=max(48, M),
+                bias_std=1.0)
     X = inputs.hidden_states(w, M)
     say(f"case {w.name} {mode} batch={batch} q_len={q_len}")
     peers = inputs.peer_slots(w, M) if mode == "one-rank" else np.zeros((w.tp, M, w.hidden), np.float32)
