@@ -343,6 +343,19 @@ def measure(torch, B, inputs, shard, w, dev, steps, warmup, use_graph=True, sync
                        "command (rocprofv3_scope says which launches)",
                 algorithmic_bytes_per_launch=work["gateup"]["bytes"] // per_layer,
                 algorithmic_flops_per_launch=work["gateup"]["flops"] // per_layer)
+    if M <= 16:
+        # context for the fraction of the nominal peak: what a kernel that only reads the same number of bytes takes
+        # (same grid and wave-contiguous access as the decode projections; 24 distinct buffers, no cache reuse)
+        chunk = work["gateup"]["bytes"] // (4 << 20) * (4 << 20)
+        if chunk > 0:
+            buf = torch.zeros(24 * chunk, dtype=torch.uint8, device=dev)
+            sink = torch.zeros(4, dtype=torch.float32, device=dev)
+            us_read = B.spd_read_probe(buf, chunk, 24, 96, sink)
+            roof["read_probe"] = {"what": "a kernel that only reads as many bytes (256 workgroups of 16 waves, wave-contiguous, "
+                                          "non-temporal; launches following each other on the stream)",
+                                  "bytes": chunk, "us": round(us_read, 2), "GB/s": round(chunk / (us_read * 1e-6) / 1e9, 1)}
+            log(f"  read probe: {chunk / 1e6:.1f} MB in {us_read:.2f} us = {chunk / (us_read * 1e-6) / 1e12:.2f} TB/s")
+            del buf, sink
     res["roofline"] = roof
     res["stage_us_in_model_events"] = {k: v["raw_mean_us"] for k, v in inmodel.items()}
     res["event_pair_us"] = round(pair_us, 2)

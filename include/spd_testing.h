@@ -70,6 +70,18 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
 #define SPD_MFMA_PROBE_SCRATCH_BYTES (256 * 512 * 4 + 16)
 int spd_mfma_probe(int32_t iters, int32_t random_data, void *scratch, void *stream, double *tflops, double *mhz);
 
+/* ---------------------------------------------------------------- what a plain read sustains
+ * `reps` launches of a kernel that only reads: launch i reads the `chunk_bytes` bytes at buf + (i % n_chunks) *
+ * chunk_bytes (so that with n_chunks * chunk_bytes well above the 256 MB Infinity Cache every launch reads from
+ * HBM), 256 workgroups of 16 waves, every wave a contiguous share with four 1 KiB non-temporal loads in flight:
+ * the access pattern of the decode projections without their arithmetic, activations, reduction and epilogue.
+ * Returns the mean time per launch in microseconds (HIP events on `stream` around all launches, which follow each
+ * other on the stream).  `sink` is device memory of at least 4 bytes (never written unless the data read is a
+ * particular pattern; it keeps the loads alive).  Synchronises the stream.
+ * SPD_EINVAL: NULL pointers, chunk_bytes not a multiple of 4 MiB, n_chunks or reps <= 0. */
+int spd_read_probe(const void *buf, size_t chunk_bytes, int32_t n_chunks, int32_t reps, void *sink, void *stream,
+                   double *us_per_launch);
+
 /* ---------------------------------------------------------------- launch order of the GEMM tiles
  * The LDS-tiled GEMM of a long call runs its TN x TM tiles (of rn x rm rows) in an order that keeps the tiles
  * an XCD has in flight close together.  For a launch of n_tiles tiles of that order starting at tile number

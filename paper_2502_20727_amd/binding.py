@@ -98,6 +98,7 @@ _PROTOS = {
     "spd_stage_timer_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "spd_stage_timer_destroy": (None, [C.c_void_p]),
     "spd_mfma_probe": (C.c_int, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "spd_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]),
     "spd_gemm_launch_size": (C.c_int, [C.c_int32]),
     "spd_gemm_tile_of": (C.c_int, [C.c_int32] * 7 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
 }
@@ -393,6 +394,15 @@ def spd_mfma_probe(iters: int, random_data: bool, scratch, stream=None):
     _check(lib().spd_mfma_probe(iters, 1 if random_data else 0, scratch.data_ptr(), _stream_ptr(stream), C.byref(tf),
                                 C.byref(mhz)), "spd_mfma_probe")
     return tf.value, mhz.value
+
+
+def spd_read_probe(buf, chunk_bytes: int, n_chunks: int, reps: int, sink, stream=None) -> float:
+    """Mean microseconds per launch of a kernel that only reads chunk_bytes (device tensors `buf`, `sink`)."""
+    assert buf.is_cuda and buf.numel() * buf.element_size() >= chunk_bytes * n_chunks and sink.is_cuda
+    us = C.c_double()
+    _check(lib().spd_read_probe(buf.data_ptr(), chunk_bytes, n_chunks, reps, sink.data_ptr(), _stream_ptr(stream), C.byref(us)),
+           "spd_read_probe")
+    return us.value
 
 
 def spd_gemm_launch_size(n_tiles: int) -> int:

@@ -445,6 +445,15 @@ int spd_mfma_probe(int32_t iters, int32_t random_data, void *scratch, void *stre
     return SPD_OK;
 }
 
+int spd_read_probe(const void *buf, size_t chunk_bytes, int32_t n_chunks, int32_t reps, void *sink, void *stream,
+                   double *us_per_launch) {
+    if (!buf || !sink || !us_per_launch || n_chunks <= 0 || reps <= 0) return SPD_EINVAL;
+    if (chunk_bytes == 0 || chunk_bytes % ((size_t)4 << 20) != 0) return SPD_EINVAL;
+    clear_stale_hip_error();
+    SPD_HIP(spd_bf16::read_probe(buf, chunk_bytes, n_chunks, reps, sink, (hipStream_t)stream, us_per_launch));
+    return SPD_OK;
+}
+
 int spd_stage_timer_create(int32_t stage, int32_t max_records, spd_stage_timer **out) {
     if (!out || stage < 0 || stage > SPD_STAGE_EMPTY || max_records <= 0) return SPD_EINVAL;
     *out = nullptr;

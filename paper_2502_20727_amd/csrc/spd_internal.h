@@ -241,6 +241,8 @@ hipError_t mlp_half(const spd_call &c, const char *w, const float *r_in, const f
 namespace spd_bf16 {
 // benchmark aid (spd_testing.h): rate of register-resident MFMAs over a full grid
 hipError_t mfma_probe(int iters, int random_data, void *scratch, hipStream_t s, double *tflops, double *mhz);
+// benchmark aid (spd_testing.h): mean time of launches that only read chunk_bytes each
+hipError_t read_probe(const void *buf, size_t chunk_bytes, int n_chunks, int reps, void *sink, hipStream_t s, double *us);
 // out = base + sum slots (optional), xhat = fp16(out * g) packed (optional), partial sums of squares
 // which = 0: the block's first norm (xhat, ss1); which = 1: its second norm (xhat2, ss2)
 // bias (may be NULL): [h], added to `out` after the sum

@@ -2534,6 +2534,54 @@ __global__ void __launch_bounds__(512) k_mfma_probe(int iters, int random_data, 
 }
 }  // namespace
 
+namespace {
+// benchmark aid: every wave reads a contiguous share of `per_wave` KiB, four 1 KiB non-temporal loads in flight
+__global__ void __launch_bounds__(1024) k_read_probe(const f32x4 *__restrict__ p, size_t per_wave, float *__restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * 16 + (threadIdx.x >> 6);
+    const f32x4 *q = p + wave * per_wave * 64 + lane;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (size_t i = 0; i + 4 <= per_wave; i += 4) {
+        f32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(q + (i + u) * 64);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += v[u];
+    }
+    if (acc[0] == 1234.5f && acc[1] == -77.25f) sink[0] = acc[2];      // keeps the loads alive
+}
+}  // namespace
+
+namespace spd_bf16 {
+hipError_t read_probe(const void *buf, size_t chunk_bytes, int n_chunks, int reps, void *sink, hipStream_t s, double *us) {
+    const size_t per_wave = chunk_bytes / (256 * 16 * 1024);        // KiB per wave (chunk_bytes is a multiple of 4 MiB)
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    auto launch = [&](int i) {
+        const char *src = (const char *)buf + (size_t)(i % n_chunks) * chunk_bytes;
+        hipLaunchKernelGGL(k_read_probe, dim3(256), dim3(1024), 0, s, (const f32x4 *)src, per_wave, (float *)sink);
+    };
+    if (e == hipSuccess) {
+        for (int i = 0; i < 3; ++i) launch(i);                         // warm-up
+        e = hipEventRecord(e0, s);
+    }
+    if (e == hipSuccess) {
+        for (int i = 0; i < reps; ++i) launch(3 + i);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return e;
+    *us = (double)ms * 1000.0 / reps;
+    return hipSuccess;
+}
+}  // namespace spd_bf16
+
 namespace spd_bf16 {
 hipError_t mfma_probe(int iters, int random_data, void *scratch, hipStream_t s, double *tflops, double *mhz) {
     constexpr int kGrid = 256;

@@ -792,3 +792,16 @@ def test_mfma_probe_reports_a_plausible_rate():
         tf, mhz = B.spd_mfma_probe(2000, random_data, scratch)
         assert 250.0 < tf < 2600.0, (random_data, tf)
         assert 500.0 < mhz < 2600.0, (random_data, mhz)
+
+
+def test_read_probe_reports_a_plausible_rate(gpu):
+    """The benchmark aid runs: 64 MiB per launch from 8 distinct buffers, between 1 and 8 TB/s."""
+    import torch
+    chunk = 64 << 20
+    buf = torch.zeros(8 * chunk, dtype=torch.uint8, device=gpu)
+    sink = torch.zeros(4, dtype=torch.float32, device=gpu)
+    us = B.spd_read_probe(buf, chunk, 8, 16, sink)
+    rate = chunk / (us * 1e-6) / 1e12
+    say(f"read probe: {us:.2f} us per 64 MiB = {rate:.2f} TB/s")
+    assert 1.0 < rate < 8.0
+    assert float(sink.sum()) == 0.0

@@ -62,6 +62,17 @@ def test_mfma_probe_rejects_bad_arguments_before_any_launch():
     assert lib.spd_mfma_probe(10, 1, C.c_void_p(8), None, None, C.byref(mhz)) == B.SPD_EINVAL
 
 
+def test_read_probe_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    us = C.c_double()
+    ok = C.c_void_p(8)
+    assert lib.spd_read_probe(None, 4 << 20, 1, 1, ok, None, C.byref(us)) == B.SPD_EINVAL
+    assert lib.spd_read_probe(ok, (4 << 20) + 1024, 1, 1, ok, None, C.byref(us)) == B.SPD_EINVAL
+    assert lib.spd_read_probe(ok, 4 << 20, 0, 1, ok, None, C.byref(us)) == B.SPD_EINVAL
+    assert lib.spd_read_probe(ok, 4 << 20, 1, 1, None, None, C.byref(us)) == B.SPD_EINVAL
+    assert lib.spd_read_probe(ok, 4 << 20, 1, 1, ok, None, None) == B.SPD_EINVAL
+
+
 def test_strerror():
     assert B.strerror(0) == "ok"
     for code in (B.SPD_EINVAL, B.SPD_EUNSUPPORTED, B.SPD_EHIP, -99):
