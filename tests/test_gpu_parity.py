@@ -430,6 +430,30 @@ def test_edge_cases(gpu):
     c64.close()
 
 
+def test_long_context_decode(gpu):
+    """Decode steps against caches of 16383, 9000 and 31 positions in one call (capacity 16384): the attention
+    kernel cuts the context into as many splits as it may and merges them; one rank of four."""
+    import torch
+    w, rank = SMALL, 2
+    positions = [16383, 9000, 31]
+    case = Case(w, gpu, ranks=[rank], positions=positions, max_ctx=16384, max_tokens=16)
+    X = inputs.hidden_states(w, 3)
+    peers = inputs.peer_slots(w, 3)
+    slots = case.to_dev(peers)
+    out = torch.empty((3, w.hidden), dtype=torch.float32, device=gpu)
+    say("long-context decode, positions", positions)
+    for l, flag in enumerate(w.mask):
+        x_in = X if l == 0 else out.cpu().numpy()
+        B.spd_block_forward(case.dev.ctx, l, flag, rank, case.dev.weights[l], case.dev.kv[l], positions, 3, 1,
+                            case.to_dev(x_in), slots, out, case.dev.workspace)
+        torch.cuda.synchronize()
+        want = O.block_single_rank(case.sh, x_in, case.shards[l][0], case.caches[l][0], positions, 3, 1, flag, rank,
+                                   peers.astype(np.float64))
+        err = assert_close(out.cpu().numpy(), want, w, f"long context block {l}")
+        say(f"  block {l}: max err {err:.2e}")
+    case.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # full-size shapes through spd_block_forward (2 layers each: the first as an SPD block, the last as a TP block);
 # the call the bench makes, spd_model_forward at full depth, is checked at the end of this file
