@@ -1033,18 +1033,21 @@ __global__ void __launch_bounds__(W * 64) k_skinny(const __bf16 *__restrict__ Wp
 // ------------------------------------------------------------------------------------------
 constexpr int MID_KB = 2;        // k-tiles per stage
 constexpr int MID_PAIRS = 8;     // pairs of n-tiles per workgroup (one per wave)
-template <int MT>
+template <int MT, bool XS>
 struct MidSet {
-    bf16x8 wa[MID_KB], wb[MID_KB], x[MT >= 4 ? MT / 4 : 1];
+    bf16x8 wa[MID_KB], wb[MID_KB], x[MT >= 4 ? MT / 4 : 1], xl[XS ? (MT >= 4 ? MT / 4 : 1) : 1];
 };
 
-template <int MT>
-__global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp, int KT,
-                                                        int KS, int n_pairs, int n_mtiles, f32x4 *__restrict__ kpart) {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * MT * MID_KB * 1024];
+// XS: the activations are hi + lo pairs (second plane at Xlo); both planes go through LDS and every weight
+// fragment meets both.
+template <int MT, bool XS>
+__global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
+                                                        const __bf16 *__restrict__ Xlo, int KT, int KS, int n_pairs,
+                                                        int n_mtiles, f32x4 *__restrict__ kpart) {
     // activation fragments of a stage fetched by one wave (with 2 m-tiles there are only 4 fragments: waves
     // 4 .. 7 fetch and store the same ones again, which keeps the loop free of branches)
-    constexpr int XPW = MT >= 4 ? MT / 4 : 1, NFRAG = MT * MID_KB;
+    constexpr int XPW = MT >= 4 ? MT / 4 : 1, NFRAG = MT * MID_KB, PLANES = XS ? 2 : 1;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * PLANES * NFRAG * 1024];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int pair = blockIdx.x * MID_PAIRS + wave;
     const bool live = pair < n_pairs;
@@ -1061,22 +1064,24 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
     };
     const bf16x8 *wa = (const bf16x8 *)(Wp + spd_frag_index(2 * pair, 0, KT)) + lane;
     const bf16x8 *wb = (const bf16x8 *)(Wp + spd_frag_index(2 * pair + 1, 0, KT)) + lane;
-    const bf16x8 *xsrc[XPW];
+    size_t xoff[XPW];
 #pragma unroll
     for (int i = 0; i < XPW; ++i) {
         const int mt = mt0 + ((wave * XPW + i) % NFRAG) / MID_KB;
-        xsrc[i] = (const bf16x8 *)(Xp + spd_frag_index(mt < n_mtiles ? mt : n_mtiles - 1, 0, KT)) + lane;
+        xoff[i] = spd_frag_index(mt < n_mtiles ? mt : n_mtiles - 1, 0, KT) + (size_t)lane * 8;
     }
     f32x4 acc[MT][2];
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[m][0] = acc[m][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    auto load = [&](MidSet<MT> &S, int st) {
+    auto load = [&](MidSet<MT, XS> &S, int st) {
         const int kt0 = stage_of(st) * MID_KB;
 #pragma unroll
         for (int i = 0; i < XPW; ++i) {
             const int kt = kt0 + ((wave * XPW + i) % NFRAG) % MID_KB;
-            S.x[i] = xsrc[i][(size_t)(kt < KT ? kt : KT - 1) * 64];
+            const size_t o = xoff[i] + (size_t)(kt < KT ? kt : KT - 1) * 512;
+            S.x[i] = *(const bf16x8 *)(Xp + o);
+            if (XS) S.xl[i] = *(const bf16x8 *)(Xlo + o);
         }
 #pragma unroll
         for (int kb = 0; kb < MID_KB; ++kb) {
@@ -1085,25 +1090,35 @@ __global__ void __launch_bounds__(MID_PAIRS * 64) k_mid(const __bf16 *__restrict
             S.wb[kb] = __builtin_nontemporal_load(wb + (size_t)kt * 64);
         }
     };
-    auto put = [&](const MidSet<MT> &S, int buf) {
+    auto put = [&](const MidSet<MT, XS> &S, int buf) {
 #pragma unroll
-        for (int i = 0; i < XPW; ++i) *(bf16x8 *)(lds + (buf * NFRAG + (wave * XPW + i) % NFRAG) * 1024 + lane * 16) = S.x[i];
+        for (int i = 0; i < XPW; ++i) {
+            char *dst = lds + ((buf * PLANES) * NFRAG + (wave * XPW + i) % NFRAG) * 1024 + lane * 16;
+            *(bf16x8 *)dst = S.x[i];
+            if (XS) *(bf16x8 *)(dst + NFRAG * 1024) = S.xl[i];
+        }
     };
-    auto compute = [&](const MidSet<MT> &S, int buf, int st) {
+    auto compute = [&](const MidSet<MT, XS> &S, int buf, int st) {
         const int kt0 = stage_of(st) * MID_KB;
 #pragma unroll
         for (int kb = 0; kb < MID_KB; ++kb) {
             if (kb > 0 && kt0 + kb >= KT) break;                 // odd number of k-tiles: the last stage holds one
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                const bf16x8 x = *(const bf16x8 *)(lds + (buf * MT * MID_KB + m * MID_KB + kb) * 1024 + lane * 16);
+                const char *src = lds + ((buf * PLANES) * NFRAG + m * MID_KB + kb) * 1024 + lane * 16;
+                const bf16x8 x = *(const bf16x8 *)src;
                 acc[m][0] = MFMA16(S.wa[kb], x, acc[m][0]);
                 acc[m][1] = MFMA16(S.wb[kb], x, acc[m][1]);
+                if (XS) {
+                    const bf16x8 xl = *(const bf16x8 *)(src + NFRAG * 1024);
+                    acc[m][0] = MFMA16(S.wa[kb], xl, acc[m][0]);
+                    acc[m][1] = MFMA16(S.wb[kb], xl, acc[m][1]);
+                }
             }
         }
     };
     // stage t lives in set t % 4, its activations in LDS buffer t % 2
-    MidSet<MT> st[4];
+    MidSet<MT, XS> st[4];
     load(st[0], 0);
     load(st[1], 1);
     load(st[2], 2);
@@ -2099,26 +2114,39 @@ hipError_t launch_skinny(const spd_call &c, bool split, const __bf16 *Wp, const 
 // Returns false in *done when the shape is not its kind (the caller then takes the skinny kernel).
 constexpr int SKINNY_MAX_MTILES = 32;      // beyond 512 tokens the LDS-tiled GEMM re-reads the weights less often
 constexpr int MID_MIN_PAIRS = 128;
+constexpr int MID_OTHERS_FROM = 10;    // m-tiles from which the QKV and down projections take the mid kernel too
+// K slices the mid kernel would use for this shape, 0 when the shape is not its kind
+inline int mid_slices(const spd_call &c, int n_pairs, int KT, int min_pairs = MID_MIN_PAIRS, int min_stages = 4) {
+    const spd_dims &D = *c.D;
+    const int n_mtiles = (c.M + 15) / 16;
+    if (n_mtiles <= 1 || n_mtiles > SKINNY_MAX_MTILES || n_pairs < min_pairs) return 0;
+    const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS, nst = (KT + MID_KB - 1) / MID_KB;
+    const int MT = n_mtiles <= 2 ? 2 : (n_mtiles <= 4 ? 4 : 8), zg = (n_mtiles + MT - 1) / MT;
+    // one round of workgroups (one fits a compute unit), at least min_stages stages per slice
+    int KS = 256 / (groups * zg);
+    if (KS > nst / min_stages) KS = nst / min_stages;
+    while (KS > 1 && (size_t)n_pairs * KS * n_mtiles > D.kpart_tiles) --KS;
+    return KS < 2 ? 0 : KS;
+}
 template <class Epi>
-hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, int n_pairs, int KT, const Epi &epi, bool *done) {
+hipError_t launch_mid(const spd_call &c, const __bf16 *Wp, const __bf16 *Xhi, const __bf16 *Xlo, int n_pairs, int KT, const Epi &epi,
+                      bool *done, int min_pairs = MID_MIN_PAIRS, int min_stages = 4) {
     const spd_dims &D = *c.D;
     const int n_mtiles = (c.M + 15) / 16;
     *done = false;
-    if (n_mtiles <= 1 || n_mtiles > SKINNY_MAX_MTILES || n_pairs < MID_MIN_PAIRS) return hipSuccess;
-    const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS, nst = (KT + MID_KB - 1) / MID_KB;
+    const int KS = mid_slices(c, n_pairs, KT, min_pairs, min_stages);
+    if (KS == 0) return hipSuccess;
+    const int groups = (n_pairs + MID_PAIRS - 1) / MID_PAIRS;
     const int MT = n_mtiles <= 2 ? 2 : (n_mtiles <= 4 ? 4 : 8), zg = (n_mtiles + MT - 1) / MT;
-    // one round of workgroups (one fits a compute unit), at least 4 stages per slice
-    int KS = 254 / (groups * zg);
-    if (KS > nst / 4) KS = nst / 4;
-    while (KS > 1 && (size_t)n_pairs * KS * n_mtiles > D.kpart_tiles) --KS;
-    if (KS < 2) return hipSuccess;
     f32x4 *kpart = (f32x4 *)(c.ws + D.ws_kpart);
-    if (MT == 2)
-        hipLaunchKernelGGL((k_mid<2>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
-    else if (MT == 4)
-        hipLaunchKernelGGL((k_mid<4>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
-    else
-        hipLaunchKernelGGL((k_mid<8>), dim3(groups, KS, zg), dim3(MID_PAIRS * 64), 0, c.s, Wp, Xhi, KT, KS, n_pairs, n_mtiles, kpart);
+    const dim3 grid(groups, KS, zg), wg(MID_PAIRS * 64);
+#define SPD_MID(MTV)                                                                                                          \
+    if (Xlo) hipLaunchKernelGGL((k_mid<MTV, true>), grid, wg, 0, c.s, Wp, Xhi, Xlo, KT, KS, n_pairs, n_mtiles, kpart);        \
+    else hipLaunchKernelGGL((k_mid<MTV, false>), grid, wg, 0, c.s, Wp, Xhi, Xlo, KT, KS, n_pairs, n_mtiles, kpart)
+    if (MT == 2) { SPD_MID(2); }
+    else if (MT == 4) { SPD_MID(4); }
+    else { SPD_MID(8); }
+#undef SPD_MID
     SPD_TRY(hipGetLastError());
     hipLaunchKernelGGL((k_mid_finish<Epi>), dim3(groups, n_mtiles), dim3(MID_PAIRS * 64), 0, c.s, kpart, KS, n_pairs, n_mtiles, epi);
     *done = true;
@@ -2240,7 +2268,28 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
         if (!fused_q && !gather_q) qkv_slices = 1;
     }
     float *qkvp = (float *)(c.ws + D.ws_kpart);
-    if (fused_q || gather_q) {
+    auto full_epilogue = [&]() {
+        EpiQKV e1;
+        e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
+        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
+        e1.ss = (const float *)(c.ws + D.ws_ss1);
+        e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.wsc = wqkv.wsc;
+        e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
+        return e1;
+    };
+    // MID_OTHERS_FROM .. 32 m-tiles: the mid kernel (activation fragments shared by 8 pairs of n-tiles through LDS)
+    // where its slices fit; the skinny kernel pulls every activation through the L2 once per pair, which from about
+    // 200 tokens on costs more than the slice partials the mid kernel writes and reads back
+    if (!fused_q && n_mtiles >= MID_OTHERS_FROM && n_mtiles <= SKINNY_MAX_MTILES &&
+        mid_slices(c, qkv_pairs, D.h / 32, MID_PAIRS, 8) > 0) {
+        if (c.on(SPD_STAGE_QKV)) {
+            spd_stage_scope prof(c, SPD_STAGE_QKV);
+            bool done = false;
+            SPD_TRY(launch_mid(c, wqkv.w, xhat, c.sp_x ? xhat + D.pl_x : (const __bf16 *)nullptr, qkv_pairs, D.h / 32,
+                               full_epilogue(), &done, MID_PAIRS, 8));
+        }
+    } else if (fused_q || gather_q) {
         EpiQKVPart e1;
         e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
         e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.part_rows = 16 * n_mtiles; e1.eps = D.eps;
@@ -2262,13 +2311,7 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
             }
         }
     } else {
-        EpiQKV e1;
-        e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.max_ctx = D.max_ctx;
-        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.eps = D.eps;
-        e1.ss = (const float *)(c.ws + D.ws_ss1);
-        e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
-        e1.wsc = wqkv.wsc;
-        e1.qbuf = qbuf; e1.qlo = qlo; e1.kc = kc; e1.vc = vc; e1.P = c.pos;
+        const EpiQKV e1 = full_epilogue();
         if (c.on(SPD_STAGE_QKV)) {
             spd_stage_scope prof(c, SPD_STAGE_QKV);
             SPD_TRY(launch_proj(c, c.sp_x, wqkv.w, xhat, D.pl_x, D.nqkv / 32, D.h / 32, e1,
@@ -2427,7 +2470,7 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             }
         } else {
             bool mid = false;
-            if (!c.sp_m) SPD_TRY(launch_mid(c, wgu.w, xhat, D.f_pad / 16, D.h / 32, e1, &mid));
+            if (!c.sp_m) SPD_TRY(launch_mid(c, wgu.w, xhat, (const __bf16 *)nullptr, D.f_pad / 16, D.h / 32, e1, &mid));
             if (!mid) SPD_TRY(launch_proj(c, c.sp_m, wgu.w, xhat, D.pl_x, D.f_pad / 16, D.h / 32, e1));
         }
     }
@@ -2461,8 +2504,14 @@ hipError_t mlp_half(const spd_call &c, const char *w, int spd, float *slot, cons
             if (M <= 16)
                 SPD_TRY(c.sp_m ? launch_gemv<true>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2)
                                : launch_gemv<false>(c, wdn.w, uhat, uhat + D.pl_u, D.h / 32, D.f_pad / 32, e2));
-            else
-                SPD_TRY(launch_skinny<0>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
+            else {
+                // (up to MID_OTHERS_FROM m-tiles the finishing kernel, which carries the closing sync point, costs more
+                // than the activation traffic the mid kernel saves)
+                bool mid = false;
+                if (!c.sp_m && (int)cdiv(M, 16) >= MID_OTHERS_FROM)
+                    SPD_TRY(launch_mid(c, wdn.w, uhat, (const __bf16 *)nullptr, D.h / 32, D.f_pad / 32, e2, &mid));
+                if (!mid) SPD_TRY(launch_skinny<0>(c, c.sp_m, wdn.w, uhat, D.pl_u, D.h / 32, D.f_pad / 32, 1, 16, e2));
+            }
         } else {
             EpiDownT<false> e2;
             fill(e2);

@@ -486,19 +486,24 @@ def test_full_size_decode_shapes(gpu, name):
     case.close()
 
 
-def test_full_size_short_prefill(gpu):
+@pytest.mark.parametrize("q_len", [128, 200, 500])
+def test_full_size_short_prefill(gpu, q_len):
     """LLaMA2-70B shard, one sequence of 128 tokens (the shape of the paper's latency breakdown,
     Fig. 2), an SPD block then a TP block, every output row checked at the 2e-2 bound as it
-    stands, in the default configuration (the one the bench times)."""
+    stands, in the default configuration (the one the bench times).  200 and 500 tokens: from 145
+    tokens on the QKV and down projections take the kernel that shares the activations through LDS
+    (the QKV one on its hi + lo input pair), with ragged last m-tiles."""
     import torch
+    from dataclasses import replace
     full = workloads.get("70b-prefill-128")
+    full = replace(full, q_len=q_len, ctx=(q_len + 31) // 32 * 32)
     w = full.with_layers(2).with_mask((1, 0))
     M = full.q_len
     case = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, full.n_layers - 1])
     X = inputs.hidden_states(w, M)
     peers = inputs.peer_slots(w, M)
     x, slots = case.to_dev(X), case.to_dev(peers)
-    say("full-size short prefill: 1 x 128 tokens")
+    say(f"full-size short prefill: 1 x {M} tokens")
     for l in range(2):
         x_host = x.cpu().numpy()
         out = torch.empty_like(x)
@@ -510,6 +515,23 @@ def test_full_size_short_prefill(gpu):
         err = assert_close(out.cpu().numpy(), want, w, f"short prefill layer {l}")
         say(f"  flag {w.mask[l]}: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
         x = out
+    # the same two blocks through spd_model_forward (the call the bench makes: the down projection's epilogue then
+    # carries the closing sync point and the next block's norm preparation), block by block against the oracle
+    case2 = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, full.n_layers - 1])
+    taps = torch.zeros((2, M, w.hidden), dtype=torch.float32, device=gpu)
+    out2 = torch.empty((M, w.hidden), dtype=torch.float32, device=gpu)
+    syncs = B.spd_model_forward_staged(case2.dev.ctx, w.mask, 0, case2.dev.weights, case2.dev.kv, [0], 1, M, case2.to_dev(X),
+                                       case2.to_dev(peers), out2, case2.dev.workspace, layer_out=taps)
+    torch.cuda.synchronize()
+    assert syncs == 3
+    got = taps.cpu().numpy()
+    for l in range(2):
+        x_in = X if l == 0 else got[l - 1]
+        want = O.block_single_rank(case2.sh, x_in, case2.shards[l][0], case2.caches[l][0], [0], 1, M, w.mask[l], 0,
+                                   peers.astype(np.float64))
+        err = assert_close(got[l], want, w, f"short prefill, model forward, layer {l}")
+        say(f"  model forward, flag {w.mask[l]}: max err {err:.2e}")
+    case2.close()
     case.close()
 
 
