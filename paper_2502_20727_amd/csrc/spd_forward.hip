@@ -45,6 +45,7 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
     c->slot_stride = (size_t)c->M * D.h;
     c->ws = (char *)workspace;
     c->taps = nullptr;
+    c->chained = false;
     c->stages = SPD_ALL_STAGES;
     c->timer = nullptr;
     c->max_pos_end = 0;
@@ -290,6 +291,7 @@ int spd_model_forward_staged(const spd_ctx *ctx, const uint8_t *spd_mask, int32_
             Chain &h = ch[k];
             const int bb = k ? b1 : b0, first = k ? b0 : 0;
             h.c = c;
+            h.c.chained = true;
             h.c.batch = bb;
             h.c.M = bb * q_len;
             std::memset(&h.c.pos, 0, sizeof(h.c.pos));

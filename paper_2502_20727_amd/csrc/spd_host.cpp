@@ -157,6 +157,9 @@ void compute_dims(const spd_config &c, spd_dims &D) {
         D.ws_uhat = o; o = spd_align256(o + 2 * M * f * 2);
         // partial tiles of the K-sliced launches: the decode sizes always, the 17 .. 128 token kind when calls can be that long
         D.kpart_tiles = D.max_tokens > 16 ? (size_t)SPD_MID_KPART : (size_t)SPD_MAX_KPART;
+        // ... and, when calls can be longer than 512 tokens, the slice partials of a K-sliced QKV GEMM: up to
+        // 8192 (slice, token) rows of fp32
+        if (D.max_tokens > 512) D.kpart_tiles = std::max(D.kpart_tiles, (size_t)8192 * D.nqkv / 512 + 1);
         D.ws_kpart = o; o = spd_align256(o + D.kpart_tiles * 512 * 4);
         D.ws_apart = o;
         o = spd_align256(o + (size_t)D.max_batch * D.kv * SPD_MAX_SPLITS * 16 * (D.d + 2) * 4);

@@ -201,6 +201,7 @@ struct spd_call {
     int nch1;                 // number of sum-of-squares partials per token waiting in ss1
     char *ws;                 // workspace
     const spd_taps *taps;
+    bool chained;             // one of the two chains of a long prefill: its kernels share the chip with the other chain's
     uint32_t stages;          // bit s set: the kernels of stage s are launched (all set in an ordinary call)
     spd_stage_timer *timer;   // NULL, or the timer that brackets the launches of its stage
     bool on(int stage) const { return (stages >> stage) & 1u; }

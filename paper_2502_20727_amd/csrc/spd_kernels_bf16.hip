@@ -361,6 +361,7 @@ const float4 tb##j = *(const float4 *)(slots + (size_t)min(s0 + j, last) * slot_
 // computes from the partial sums of squares ss[nch][m_pad].
 struct EpiQKV {
     static constexpr bool kNeedsRs = true;
+    static constexpr bool kSliced = false;
     int M, q_len, q, kv, d, h, max_ctx, nch, m_pad;
     float eps;
     const float *ss, *cosT, *sinT;
@@ -433,8 +434,10 @@ struct EpiQKV {
 // the slices in ascending order, rounds, and appends the new key and value to the cache.
 struct EpiQKVPart {
     static constexpr bool kNeedsRs = true;
+    static constexpr bool kSliced = true;      // a kernel whose workgroups own one K slice each sets `ks` and calls operator()
     int M, q_len, q, kv, d, h, nqkv, nch, m_pad;
     int part_rows;             // token rows per slice of `part`
+    int ks = 0;
     float eps;
     const float *ss, *cosT, *sinT;
     const float *wsc;
@@ -477,11 +480,15 @@ struct EpiQKVPart {
         *(float4 *)(dst + ca) = lo;
         *(float4 *)(dst + cb) = hi;
     }
+    __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
+        slice(pair, ks, mt, a, b, lane, rs, p);
+    }
 };
 
 template <bool MID>      // MID: the epilogue can also perform the kept attention sync point (spd = 2)
 struct EpiOT {
     static constexpr bool kNeedsRs = false;
+    static constexpr bool kSliced = false;
     int M, h, spd, m_pad;
     const float *x, *g2;
     const float *bo = nullptr; // bias of the output projection or NULL: part of the SPD block's MLP input (Sec. 4.1.2)
@@ -582,6 +589,7 @@ struct EpiOT {
 
 struct EpiGU {
     static constexpr bool kNeedsRs = true;
+    static constexpr bool kSliced = false;
     int M, h, f_pad, nch, m_pad;
     int cols = 16;             // FFN columns per group: 16, or fewer for the decode-only narrow groups
     float eps;
@@ -628,6 +636,7 @@ struct EpiGU {
 template <bool FUSED>
 struct EpiDownT {
     static constexpr bool kNeedsRs = false;
+    static constexpr bool kSliced = false;
     int M, h, spd;
     const float *ybuf;
     float *slot;
@@ -1278,7 +1287,7 @@ template <class Epi, class G, bool XS>
 __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const __bf16 *__restrict__ Wp, const __bf16 *__restrict__ Xp,
                                                                    const __bf16 *__restrict__ Xlo, int KT, int n_ntiles,
                                                                    int n_mtiles, spd_tile_order ord, int tile0, int n_tiles,
-                                                                   int msub, Epi epi) {
+                                                                   int msub, int kslices, int wgs_per_slice, Epi epi_in) {
     constexpr int GL_WN = G::WN, GL_WM = G::WM, GL_TI = G::TI, GL_TJ = G::TJ, KPS = G::KPS;
     constexpr int GL_BN = GL_WN * GL_TI, GL_BM = GL_WM * GL_TJ;          // tiles per workgroup
     constexpr int KW = XS ? 1 : KPS;                                     // weight fragments per tile row and step
@@ -1292,15 +1301,25 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
     const int wn = wave % GL_WN, wm = wave / GL_WN;
     // A launch covers `n_tiles` tiles of the order from `tile0` on, each cut into `msub` workgroup tiles along M
     // (1, or 2 for the launch that finishes a ragged last round with half tiles; `ord` counts the uncut tiles).
+    // kslices > 1 (epilogues that are linear in the accumulators only): the launch is kslices copies of the
+    // tile grid, copy s contracting the s-th part of K and handing its slice number to the epilogue
+    int bid = (int)blockIdx.x, kslice = 0;
+    if (kslices > 1) {
+        kslice = bid / wgs_per_slice;
+        bid -= kslice * wgs_per_slice;
+    }
+    Epi epi = epi_in;
+    if constexpr (Epi::kSliced) epi.ks = kslice;
+    const int kt_first = (int)(((long)kslice * KT) / kslices), kt_end = (int)(((long)(kslice + 1) * KT) / kslices);
     int tn, tm, sub = 0;
     {
         int idx;
         if (msub == 1) {
-            idx = spd_tile_deal((int)blockIdx.x, n_tiles);
+            idx = spd_tile_deal(bid, n_tiles);
             if (idx < 0) return;                 // spare workgroup of a ragged share (whole workgroup, before any barrier)
         } else {
-            idx = (int)blockIdx.x / msub;
-            sub = (int)blockIdx.x % msub;
+            idx = bid / msub;
+            sub = bid % msub;
         }
         spd_tile_at(ord, tile0 + idx, tn, tm);
     }
@@ -1324,13 +1343,13 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
         if (!isx[i]) {
             int t = nt0 + row;
             if (t >= n_ntiles) t = n_ntiles - 1;
-            src[i] = src2[i] = Wp + spd_frag_index(t, 0, KT) + lane * 8;
+            src[i] = src2[i] = Wp + spd_frag_index(t, kt_first, KT) + lane * 8;
             loff[i] = row * (KW * 1024);
         } else {
             int t = mt0 + row - GL_BN;
             if (t >= n_mtiles) t = n_mtiles - 1;
-            src[i] = Xp + spd_frag_index(t, 0, KT) + lane * 8;
-            src2[i] = XS ? Xlo + spd_frag_index(t, 0, KT) + lane * 8 : src[i];
+            src[i] = Xp + spd_frag_index(t, kt_first, KT) + lane * 8;
+            src2[i] = XS ? Xlo + spd_frag_index(t, kt_first, KT) + lane * 8 : src[i];
             loff[i] = GL_BN * (KW * 1024) + (row - GL_BN) * (KX * 1024);
         }
     }
@@ -1360,7 +1379,7 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
 #pragma unroll
         for (int n = 0; n < GL_NCP; ++n) issue_one(stage, ks, n);
     };
-    const int nks = XS ? KT : KT / KPS;
+    const int nks = XS ? kt_end - kt_first : (kt_end - kt_first) / KPS;      // (the launcher keeps a slice a whole number of steps)
     if constexpr (!XS && KPS == 2) {
         // A step is two k-tiles; the fragments of one k-tile are read from LDS while the MFMAs of the other run.
         // The barrier sits in the middle of a step: when a wave passes it, everybody has read both k-tiles of the
@@ -1488,7 +1507,7 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
 
 template <class G, bool XS, class Epi>
 hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, const __bf16 *Xlo, int n_pairs, int KT,
-                               const Epi &epi, int tile0 = 0, int msub = 1, int n_tiles = -1) {
+                               const Epi &epi, int tile0 = 0, int msub = 1, int n_tiles = -1, int kslices = 1) {
     // with msub = 2 the tiles are counted in the shape of twice G's height (GemmHalf finishing a GemmBig launch)
     constexpr int BN = G::WN * G::TI;
     constexpr int STAGE = (BN * (XS ? 1 : G::KPS) + G::WM * G::TJ * (XS ? 2 : G::KPS)) * 1024;
@@ -1509,18 +1528,28 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     if (n_tiles < 0) n_tiles = ord.TN * ord.TM - tile0;
     // msub = 1: whole rounds of 256, then eight equal shares (the spare workgroups of a ragged share exit at once)
     const int n_wgs = msub == 1 ? spd_tile_launch_size(n_tiles) : n_tiles * msub;
-    hipLaunchKernelGGL((k_gemm_lds<Epi, G, XS>), dim3(n_wgs), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, Xlo, KT, n_ntiles,
-                       n_mtiles, ord, tile0, n_tiles, msub, epi);
+    hipLaunchKernelGGL((k_gemm_lds<Epi, G, XS>), dim3(n_wgs * kslices), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, Xlo, KT,
+                       n_ntiles, n_mtiles, ord, tile0, n_tiles, msub, kslices, n_wgs, epi);
     return hipGetLastError();
 }
 
+// Number of workgroup tiles of the shape launch_gemm_lds() picks (below 256: one launch)
+inline int gemm_tile_count(bool xs, int n_pairs, int n_mtiles) {
+    const int big = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 15) / 16), tall = ((2 * n_pairs + 7) / 8) * ((n_mtiles + 23) / 24);
+    const int wide = ((2 * n_pairs + 9) / 10) * ((n_mtiles + 15) / 16);
+    if (xs && big < 224 && wide <= 256 && wide > tall && 160 * ((wide + 255) / 256) < 192 * ((tall + 255) / 256)) return wide;
+    if (big < 224 && tall <= 256 && tall > big) return tall;
+    return big;
+}
+
+// kslices > 1: K is cut into that many parts, each part a copy of the tile grid in the same launch (sliced epilogues only)
 template <bool XS, class Epi>
 hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp, const __bf16 *Xlo, int n_pairs, int KT,
-                           const Epi &epi) {
+                           const Epi &epi, int kslices = 1) {
     // both shapes measure the same on the 70B shard (the big one is ahead by 1-3 % on QKV and down);
     // the mid one also takes an odd number of k-tiles (a step of the split kind is one k-tile anyway)
     if constexpr (!XS) {
-        if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid, false>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+        if ((KT % 2) != 0) return launch_gemm_lds_cfg<GemmMid, false>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
     }
     // fewer 256 x 256 tiles than compute units (the QKV projection of a shard): 128 x 384 tiles when they
     // fill one round better
@@ -1531,18 +1560,18 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
         // per tile than the other shapes (the QKV projection of the 70B shard: 8 x 32 = 256 tiles)
         const int wide = ((2 * n_pairs + 9) / 10) * ((n_mtiles + 15) / 16);
         if (big < 224 && wide <= 256 && wide > tall && 160 * ((wide + 255) / 256) < 192 * ((tall + 255) / 256))
-            return launch_gemm_lds_cfg<GemmWide, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+            return launch_gemm_lds_cfg<GemmWide, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
     }
-    if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+    if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
     // a last round that would occupy at most half of the compute units runs as twice as many half tiles
     // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)
     const int rem = big % 256;
-    if (big > 256 && rem > 0 && rem <= 128) {
+    if (big > 256 && rem > 0 && rem <= 128 && kslices == 1) {
         const hipError_t e = launch_gemm_lds_cfg<GemmBig, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, big - rem);
         if (e != hipSuccess) return e;
         return launch_gemm_lds_cfg<GemmHalf, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, big - rem, 2, rem);
     }
-    return launch_gemm_lds_cfg<GemmBig, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi);
+    return launch_gemm_lds_cfg<GemmBig, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2232,6 +2261,24 @@ inline ProjW proj_weights(const spd_call &c, const char *w, int i) {
 }
 }  // namespace
 
+namespace {
+// K slices for the QKV GEMM of a long call (0 or 1: none): only where the GEMM would leave most compute
+// units idle, the call is not one of two chains (whose QKV GEMMs fill the chip together), every slice keeps
+// at least 16 k-tiles in whole steps, and the slices' partial rows fit the workspace
+inline int qkv_gemm_slices(const spd_call &c, int n_pairs, int KT, int n_mtiles) {
+    const spd_dims &D = *c.D;
+    if (n_mtiles <= SKINNY_MAX_MTILES || c.chained) return 0;
+    const int tiles = gemm_tile_count(c.sp_x, n_pairs, n_mtiles);
+    if (tiles > 128) return 0;
+    int s = 256 / tiles;
+    if (s > SPD_MAX_QKV_SLICES) s = SPD_MAX_QKV_SLICES;
+    while (s > 1 && (KT % (2 * s) != 0 || KT / s < 16 ||
+                     (size_t)s * 16 * n_mtiles * D.nqkv > D.kpart_tiles * 512))
+        --s;
+    return s;
+}
+}  // namespace
+
 hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const float *x, int spd, float *slot,
                           const spd_mid_sync *mid, bool *mid_done) {
     const spd_dims &D = *c.D;
@@ -2309,6 +2356,25 @@ hipError_t attention_half(const spd_call &c, const char *w, char *kvc, const flo
                                    16 * n_mtiles, M, c.q_len, D.q, D.kv, D.d, D.max_ctx, c.pos, qbuf, qlo, kc, vc);
                 SPD_TRY(hipGetLastError());
             }
+        }
+    } else if (const int gs = qkv_gemm_slices(c, qkv_pairs, D.h / 32, n_mtiles); gs > 1) {
+        // a long call of one chain whose QKV GEMM has far fewer tiles than there are compute units: K is cut
+        // into slices that run side by side, each applying the (linear) epilogue to its partial sums; the gather
+        // kernel adds the slices
+        EpiQKVPart e1;
+        e1.M = M; e1.q_len = c.q_len; e1.q = D.q; e1.kv = D.kv; e1.d = D.d; e1.h = D.h; e1.nqkv = D.nqkv;
+        e1.nch = c.nch1; e1.m_pad = D.m_pad; e1.part_rows = 16 * n_mtiles; e1.eps = D.eps;
+        e1.ss = (const float *)(c.ws + D.ws_ss1);
+        e1.cosT = (const float *)(c.ws + D.ws_cos); e1.sinT = (const float *)(c.ws + D.ws_sin);
+        e1.wsc = wqkv.wsc;
+        e1.part = qkvp; e1.P = c.pos;
+        if (c.on(SPD_STAGE_QKV)) {
+            spd_stage_scope prof(c, SPD_STAGE_QKV);
+            SPD_TRY(c.sp_x ? launch_gemm_lds<true>(c, wqkv.w, xhat, xhat + D.pl_x, qkv_pairs, D.h / 32, e1, gs)
+                           : launch_gemm_lds<false>(c, wqkv.w, xhat, xhat + D.pl_x, qkv_pairs, D.h / 32, e1, gs));
+            hipLaunchKernelGGL(k_qkv_gather, dim3(cdiv((int64_t)M * (D.nqkv / 4), 256)), dim3(256), 0, c.s, qkvp, gs,
+                               16 * n_mtiles, M, c.q_len, D.q, D.kv, D.d, D.max_ctx, c.pos, qbuf, qlo, kc, vc);
+            SPD_TRY(hipGetLastError());
         }
     } else {
         const EpiQKV e1 = full_epilogue();

@@ -535,6 +535,45 @@ def test_full_size_short_prefill(gpu, q_len):
     case.close()
 
 
+@pytest.mark.parametrize("q_len", [1100, 2048])
+def test_full_size_single_sequence_prefill(gpu, q_len):
+    """LLaMA2-70B shard, one sequence of 1100 / 2048 tokens: a single chain, whose QKV GEMM (40 or 64 tiles for 256
+    compute units) runs in 4 K slices side by side, the slices' partial rows added by the gather kernel.  An SPD
+    block and a TP block, sampled output rows against the oracle at 2e-2."""
+    import torch
+    from dataclasses import replace
+    full = replace(workloads.LLAMA70B_PREFILL, batch=1, q_len=q_len, ctx=(q_len + 31) // 32 * 32)
+    w = full.with_layers(2).with_mask((1, 0))
+    M = q_len
+    rows = np.unique(np.concatenate([np.array([0, 1, 15, 16, 255, 256, 1023, 1024, M - 17, M - 1]),
+                                     np.random.default_rng(5).choice(M, size=54, replace=False)]))
+    X = inputs.hidden_states(w, M)
+    peers = inputs.peer_slots(w, M)
+    say(f"full-size single-sequence prefill: 1 x {M} tokens")
+    case = Case(w, gpu, ranks=[0], positions=[0], layer_ids=[0, workloads.LLAMA70B_PREFILL.n_layers - 1])
+    x, slots = case.to_dev(X), case.to_dev(peers)
+    sel = torch.from_numpy(rows).to(gpu)
+    for l in range(2):
+        x_host = x.cpu().numpy()
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, l, w.mask[l], 0, case.dev.weights[l], case.dev.kv[l], [0], 1, M, x, slots, out,
+                            case.dev.workspace)
+        torch.cuda.synchronize()
+        want = O.block_single_rank(case.sh, x_host, case.shards[l][0], case.caches[l][0], [0], 1, M, w.mask[l], 0,
+                                   peers.astype(np.float64), rows=rows)
+        err = assert_close(out[sel].cpu().numpy(), want, w, f"single-sequence prefill layer {l}")
+        say(f"  flag {w.mask[l]}: max err {err:.2e} on {len(rows)} sampled rows")
+        assert bool(torch.isfinite(out).all())
+        x = out
+    # the appended keys and values of the first block, all positions: bf16 copies of the oracle's
+    k, v = case.dev.read_kv(0, 0, 1, M)
+    ko, vo = case.caches[0][0].k[0, :, :M], case.caches[0][0].v[0, :, :M]
+    assert np.max(np.abs(k[0] - ko)) <= 2.0 ** -7 * np.max(np.abs(ko)) + 1e-3
+    assert np.max(np.abs(v[0] - vo)) <= 2.0 ** -7 * np.max(np.abs(vo)) + 1e-3
+    case.close()
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("flag", [1, 0], ids=["spd", "tp"])
 @pytest.mark.parametrize("split", [B.SPD_SPLIT_AUTO, B.SPD_SPLIT_ALWAYS], ids=["default", "all-split"])
 def test_full_size_prefill_shape_sampled_rows(gpu, flag, split):
