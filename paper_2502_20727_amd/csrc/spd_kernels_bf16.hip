@@ -1562,6 +1562,14 @@ hipError_t launch_gemm_lds(const spd_call &c, const __bf16 *Wp, const __bf16 *Xp
         if (big < 224 && wide <= 256 && wide > tall && 160 * ((wide + 255) / 256) < 192 * ((tall + 255) / 256))
             return launch_gemm_lds_cfg<GemmWide, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
     }
+    {
+        // at most half a round of 256 x 256 tiles: 256 x 128 half tiles when they occupy more compute units than
+        // the other shapes
+        const int halves = ((2 * n_pairs + 15) / 16) * ((n_mtiles + 7) / 8);
+        const int other = (big < 224 && tall <= 256 && tall > big) ? tall : big;
+        if (kslices == 1 && big <= 128 && halves <= 256 && halves > other)
+            return launch_gemm_lds_cfg<GemmHalf, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 2, big);
+    }
     if (big < 224 && tall <= 256 && tall > big) return launch_gemm_lds_cfg<GemmTall, XS>(c, Wp, Xp, Xlo, n_pairs, KT, epi, 0, 1, -1, kslices);
     // a last round that would occupy at most half of the compute units runs as twice as many half tiles
     // in a second launch (gate/up of the 70B shard: 896 tiles = 3.5 rounds of 256)

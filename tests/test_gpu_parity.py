@@ -535,17 +535,18 @@ def test_full_size_short_prefill(gpu, q_len):
     case.close()
 
 
-@pytest.mark.parametrize("q_len", [1100, 2048])
+@pytest.mark.parametrize("q_len", [700, 1100, 2048])
 def test_full_size_single_sequence_prefill(gpu, q_len):
-    """LLaMA2-70B shard, one sequence of 1100 / 2048 tokens: a single chain, whose QKV GEMM (40 or 64 tiles for 256
-    compute units) runs in 4 K slices side by side, the slices' partial rows added by the gather kernel.  An SPD
+    """LLaMA2-70B shard, one sequence of 700 / 1100 / 2048 tokens: a single chain, whose QKV GEMM (24, 40 or 64 tiles
+    for 256 compute units) runs in 8 or 4 K slices side by side, the slices' partial rows added by the gather kernel;
+    at 700 tokens the other projections run as 256 x 128 half tiles throughout (a ragged last one).  An SPD
     block and a TP block, sampled output rows against the oracle at 2e-2."""
     import torch
     from dataclasses import replace
     full = replace(workloads.LLAMA70B_PREFILL, batch=1, q_len=q_len, ctx=(q_len + 31) // 32 * 32)
     w = full.with_layers(2).with_mask((1, 0))
     M = q_len
-    rows = np.unique(np.concatenate([np.array([0, 1, 15, 16, 255, 256, 1023, 1024, M - 17, M - 1]),
+    rows = np.unique(np.concatenate([np.array([0, 1, 15, 16, 255, 256, 511, 512, 640, M - 17, M - 1]),
                                      np.random.default_rng(5).choice(M, size=54, replace=False)]))
     X = inputs.hidden_states(w, M)
     peers = inputs.peer_slots(w, M)
