@@ -204,9 +204,7 @@ __device__ __forceinline__ float4 ldnt4(const float *p) {
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
-// The launch is a fixed, small number of workgroups that walk the (chunk, m-tile) items with a stride: a
-// workgroup with 16 KiB of LDS and one wave per SIMD fits beside a workgroup of the LDS-tiled GEMM on the same
-// compute unit, so that in a two-chain prefill this memory-bound kernel and the other chain's GEMM share the chip.
+// The launch is a fixed number of workgroups (two per compute unit) that walk the (chunk, m-tile) items with a stride.
 template <int NP>     // NP pieces of 256 features per workgroup and token (1 or 2): NP KiB contiguous per token row
 __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ base, const float *__restrict__ slots, int n_slots,
                                                    size_t slot_stride, float *__restrict__ out,
@@ -308,6 +306,107 @@ __global__ void __launch_bounds__(256) k_prep_rows(const float *__restrict__ bas
     }
     __syncthreads();      // the tile is free for the next item
   }
+}
+
+// The same preparation for a chain of a two-chain prefill, where it shares the chip with the other chain's GEMM:
+// a few workgroups that each fill a whole compute unit (16 waves) and keep the next item's loads in flight
+// while the current item is summed, stored and turned into fragments, so that a fraction of the compute units
+// draws the HBM's full rate and the rest stay with the GEMM.  An item is (chunk of 256 features, m-tile); wave w
+// takes token w of the m-tile, lane l features 4l .. 4l+3 of the chunk (1 KiB per wave, slot and row).  Sums in
+// the order of k_prep_rows (slots ascending, then the base, then the bias).  At most 8 slots.
+template <int NS, bool XH, bool BIAS>     // slots; fragments of the normalised values wanted; bias joins the sum
+__global__ void __launch_bounds__(1024) k_prep_cu(const float *__restrict__ base, const float *__restrict__ slots,
+                                                  size_t slot_stride, float *__restrict__ out,
+                                                  const float *__restrict__ gain, __bf16 *__restrict__ xhat,
+                                                  __bf16 *__restrict__ xlo, float *__restrict__ ss, int M, int h,
+                                                  int m_pad, const float *__restrict__ bias, int n_chunks, int n_items) {
+    __shared__ __attribute__((aligned(16))) __bf16 tile[2][2][16][256];      // [buffer][plane][token][feature]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int KT = h >> 5;
+    int item = blockIdx.x;
+    if (item >= n_items) return;
+    // everything an item reads, issued as one group without branches (the wait for the current group can then
+    // leave the next group's loads in flight)
+    struct Loads {
+        float4 p[NS], b, gn, bs;
+        size_t off;
+        bool valid;
+    };
+    auto issue = [&](int it, Loads &L) {
+        const int chunk = it % n_chunks, mt = it / n_chunks;
+        const int m = mt * 16 + wave;
+        const int col = chunk * 256 + lane * 4;
+        L.valid = m < M;
+        L.off = (size_t)(L.valid ? m : M - 1) * h + col;
+#pragma unroll
+        for (int j = 0; j < NS; ++j) L.p[j] = ldnt4(slots + (size_t)j * slot_stride + L.off);
+        L.b = ldnt4(base + L.off);
+        if constexpr (XH) L.gn = *(const float4 *)(gain + col);
+        if constexpr (BIAS) L.bs = *(const float4 *)(bias + col);
+    };
+    int buf = 0;
+    // one item: the next item's loads go out first, into the other register set (the two sets swap roles from item
+    // to item, so that nothing is copied and nothing waits for loads it does not use yet)
+    auto step = [&](Loads &cur, Loads &nxt, int it) {
+        const int ni = it + gridDim.x;
+        // (past the end: the last item's addresses once more, so that the group stays branch-free; never used)
+        issue(ni < n_items ? ni : it, nxt);
+        const int chunk = it % n_chunks, mt = it / n_chunks;
+        float4 v = cur.p[0];
+#pragma unroll
+        for (int j = 1; j < NS; ++j) { v.x += cur.p[j].x; v.y += cur.p[j].y; v.z += cur.p[j].z; v.w += cur.p[j].w; }
+        v.x = cur.b.x + v.x; v.y = cur.b.y + v.y; v.z = cur.b.z + v.z; v.w = cur.b.w + v.w;
+        if constexpr (BIAS) { v.x += cur.bs.x; v.y += cur.bs.y; v.z += cur.bs.z; v.w += cur.bs.w; }
+        if (!cur.valid) v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (cur.valid) *(float4 *)(out + cur.off) = v;
+        float sq = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) sq += shfl_xor_f(sq, o);
+        if constexpr (XH) {
+            if (lane == 0) ss[(size_t)chunk * m_pad + mt * 16 + wave] = sq;
+            const float q0 = v.x * cur.gn.x, q1 = v.y * cur.gn.y, q2 = v.z * cur.gn.z, q3 = v.w * cur.gn.w;
+            const bf16x4 hi = cvt4h(q0, q1, q2, q3);
+            *(bf16x4 *)&tile[buf][0][wave][lane * 4] = hi;
+            if (xlo) *(bf16x4 *)&tile[buf][1][wave][lane * 4] = cvt4h_lo(q0, q1, q2, q3, hi);
+            // the barrier orders LDS traffic only: the loads of the next item stay in flight across it.  One
+            // barrier per item is enough with two tile buffers: whoever writes buffer b for item i + 2 has passed
+            // the barrier of item i + 1, which every wave reaches after its reads of item i
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            // wave w writes k-tile w % 8 of plane w / 8: 1 KiB, lane = (row, group of 8 features)
+            const int plane = wave >> 3, kt = wave & 7, r = lane & 15, g = lane >> 4;
+            const size_t fo = spd_frag_index(mt, chunk * 8 + kt, KT) + lane * 8;
+            const bf16x8 f = *(const bf16x8 *)&tile[buf][plane][r][kt * 32 + g * 8];
+            if (plane == 0) *(bf16x8 *)(xhat + fo) = f;
+            else if (xlo) *(bf16x8 *)(xlo + fo) = f;
+            buf ^= 1;
+        }
+    };
+    Loads A, B;
+    issue(item, A);
+    for (;;) {
+        step(A, B, item);
+        item += gridDim.x;
+        if (item >= n_items) break;
+        step(B, A, item);
+        item += gridDim.x;
+        if (item >= n_items) break;
+    }
+}
+
+template <int NS>
+hipError_t launch_prep_cu(hipStream_t s, int n_wgs, const float *base, const float *slots, size_t slot_stride, float *out,
+                          const float *gain, __bf16 *xhat, __bf16 *xlo, float *ss, int M, int h, int m_pad, const float *bias) {
+    const int n_chunks = h / 256, n_items = n_chunks * ((M + 15) / 16);
+    const dim3 grid(n_items < n_wgs ? n_items : n_wgs), block(1024);
+#define SPD_PREP_CU_GO(XH, BIAS)                                                                                         \
+    hipLaunchKernelGGL((k_prep_cu<NS, XH, BIAS>), grid, block, 0, s, base, slots, slot_stride, out, gain, xhat, xlo, ss, M, h, \
+                       m_pad, bias, n_chunks, n_items)
+    if (xhat) { if (bias) SPD_PREP_CU_GO(true, true); else SPD_PREP_CU_GO(true, false); }
+    else { if (bias) SPD_PREP_CU_GO(false, true); else SPD_PREP_CU_GO(false, false); }
+#undef SPD_PREP_CU_GO
+    return hipGetLastError();
 }
 
 // The sum over the ranks at a sync point, for one rank whose own partial is still in registers:
@@ -2221,6 +2320,10 @@ hipError_t launch_proj(const spd_call &c, bool split, const __bf16 *Wp, const __
 // chunking of the sum-of-squares partials written by prep()
 // k-tiles per wave of k_prep: enough waves to occupy the chip at every call size
 constexpr int PREP_ROWS_WGS = 512;       // workgroups of the row-wise preparation kernel (two per compute unit)
+// workgroups (one compute unit each) of a chain's rank-sum in a two-chain prefill.  70B shard, 4 x 2048 tokens, us per
+// layer with all sync points dropped / all kept: 64: 2459 / 2790, 96: 2408 / 2702, 112: 2374 / 2699, 128: 2367 / 2552,
+// 144: 2442 / 2712, 192: 2426 / 2718; k_prep_rows: 2454 / 2690
+constexpr int PREP_CU_WGS = 128;       // workgroups of the row-wise preparation kernel (two per compute unit)
 inline int prep_tpw(int M) { return M <= 64 ? 1 : (M <= 512 ? 2 : 8); }
 inline int prep_nch(int h, int M) { return (int)cdiv(h / 32, prep_tpw(M)); }
 
@@ -2239,6 +2342,13 @@ hipError_t prep(const spd_call &c, const float *base, const float *slots, int n_
     if (!c.on(SPD_STAGE_PREP)) return hipSuccess;
     spd_stage_scope prof(c, SPD_STAGE_PREP);
     // (two adjacent chunks per workgroup, 2 KiB per row, measured slower: 547 against 505 us on the 70B prefill shape)
+    // a chain of a two-chain prefill summing the slots of a sync point: few workgroups, a compute unit each
+    if (tpw == 8 && D.h % 256 == 0 && c.chained && base && out && (n_slots == 8 || n_slots == 4)) {
+        return n_slots == 8 ? launch_prep_cu<8>(c.s, PREP_CU_WGS, base, slots, c.slot_stride, out, gain, xhat, xlo, ss, c.M, D.h,
+                                                D.m_pad, bias)
+                            : launch_prep_cu<4>(c.s, PREP_CU_WGS, base, slots, c.slot_stride, out, gain, xhat, xlo, ss, c.M, D.h,
+                                                D.m_pad, bias);
+    }
     if (tpw == 8 && D.h % 256 == 0)
     {
         const int n_chunks = D.h / 256, n_items = n_chunks * (int)cdiv(c.M, 16);

@@ -246,12 +246,14 @@ SMALL_BIAS = Workload(name="small-bf16-bias", hidden=256, n_q_heads=8, n_kv_head
 
 
 @pytest.mark.parametrize("w", [TOY_BIAS, SMALL_BIAS], ids=lambda w: w.name)
-@pytest.mark.parametrize("batch,q_len,positions", [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8]), (3, 181, [0, 3, 0])],
-                         ids=["decode", "chunk20", "chunk80", "chunk543"])
+@pytest.mark.parametrize("batch,q_len,positions",
+                         [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8]), (3, 181, [0, 3, 0]), (2, 1030, [0, 8])],
+                         ids=["decode", "chunk20", "chunk80", "chunk543", "chunk2060"])
 @pytest.mark.parametrize("mode", ["all-ranks", "one-rank"])
 def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
     """Three blocks (SPD, TP, SPD) with a bias of the size of the activations on the output projection:
-    model forward against the oracle, with every rank emulated and from one rank's point of view."""
+    model forward against the oracle, with every rank emulated and from one rank's point of view (whose bf16 call
+    of 2 x 1030 tokens runs as two chains, the bias joining the rank-sums of their preparation kernel)."""
     import torch
     M = batch * q_len
     ranks = list(range(w.tp)) if mode == "all-ranks" else [1]
