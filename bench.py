@@ -377,7 +377,7 @@ def config_of(w, use_graph):
     return {"workload": w.name, "layers": w.n_layers, "batch": w.batch, "q_len": w.q_len, "ctx": w.ctx,
             "tp_degree": w.tp, "rank": 0, "spd_layers": int(sum(w.mask)), "launch": "hip-graph" if use_graph else "eager",
             "operands": "fp16 activations (single planes) and fp16-encoded bf16 weights; attention on the bf16 cache"
-                        if w.batch * w.q_len <= 16 else
+                        if w.batch * w.q_len <= 16 or w.q_len == 1 else
                         "fp16 activations and fp16-encoded bf16 weights, QKV input as hi+lo pair (act_split AUTO); "
                         "attention on the bf16 cache"}
 

@@ -88,8 +88,8 @@ typedef struct spd_config {
  * activation is kept as a pair hi + lo of fp16 values (lo = the rounding error of hi) and the contraction
  * runs over both, which removes that rounding from the result at the price of a second pass over the
  * matrix cores.  AUTO splits the one input whose rounding shows at the block output: the QKV
- * projection's in calls of more than 16 tokens (a prefill attends to keys it produces itself; the softmax
- * amplifies errors of q and k).  ALWAYS splits every projection input, NEVER none. */
+ * projection's in calls of more than 16 tokens with q_len > 1 (a prefill attends to keys it produces itself; the
+ * softmax amplifies errors of q and k; a decode step of any batch size keeps the single plane).  ALWAYS splits every projection input, NEVER none. */
 #define SPD_SPLIT_AUTO 0
 #define SPD_SPLIT_ALWAYS 1
 #define SPD_SPLIT_NEVER 2

@@ -53,8 +53,9 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
         const bool bf = D.dtype == SPD_BF16;
         const bool always = bf && ctx->cfg.act_split == SPD_SPLIT_ALWAYS, automatic = bf && ctx->cfg.act_split == SPD_SPLIT_AUTO;
         // AUTO: fp16 activations are precise enough everywhere except the QKV projection's input in calls that
-        // attend to keys they produce themselves (prefill), where the softmax amplifies its rounding
-        c->sp_x = always || (automatic && c->M > SPD_AUTO_SPLIT_TOKENS);
+        // attend to keys they produce themselves (prefill), where the softmax amplifies its rounding; a decode
+        // step of any batch size attends to one new key per sequence and keeps the single plane
+        c->sp_x = always || (automatic && c->M > SPD_AUTO_SPLIT_TOKENS && q_len > 1);
         c->sp_a = always;
         c->sp_m = always;
     }

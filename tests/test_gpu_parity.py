@@ -488,6 +488,37 @@ def test_full_size_decode_shapes(gpu, name):
     case.close()
 
 
+@pytest.mark.parametrize("batch", [24, 48, 64])
+def test_full_size_large_batch_decode(gpu, batch):
+    """LLaMA2-70B shard, one decode step of 24 / 48 / 64 sequences at ragged positions of a 1024-position cache: the
+    projections take the kernels for 17 to 512 tokens, the QKV one on a single activation plane (a decode step
+    attends to one new key per sequence).  An SPD block and a TP block, every row at the 2e-2 bound."""
+    import torch
+    from dataclasses import replace
+    full = replace(workloads.get("70b-decode"), batch=batch, ctx=1024)
+    w = full.with_layers(2).with_mask((1, 0))
+    positions = [int(p) for p in np.random.default_rng(batch).integers(0, full.ctx, size=batch)]
+    positions[0], positions[-1] = full.ctx - 1, 0
+    say(f"full-size decode, batch {batch}")
+    case = Case(w, gpu, ranks=[0], positions=positions, layer_ids=[0, workloads.get("70b-decode").n_layers - 1])
+    X = inputs.hidden_states(w, batch)
+    peers = inputs.peer_slots(w, batch)
+    x, slots = case.to_dev(X), case.to_dev(peers)
+    for l in range(2):
+        x_host = x.cpu().numpy()
+        out = torch.empty_like(x)
+        B.spd_block_forward(case.dev.ctx, l, w.mask[l], 0, case.dev.weights[l], case.dev.kv[l], positions, batch, 1, x,
+                            slots, out, case.dev.workspace)
+        torch.cuda.synchronize()
+        want = O.block_single_rank(case.sh, x_host, case.shards[l][0], case.caches[l][0], positions, batch, 1, w.mask[l],
+                                   0, peers.astype(np.float64))
+        err = assert_close(out.cpu().numpy(), want, w, f"decode batch {batch} flag {w.mask[l]}")
+        say(f"  flag {w.mask[l]}: max err {err:.2e}, max |oracle| {np.max(np.abs(want)):.2f}")
+        x = out
+    case.close()
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("q_len", [128, 200, 500])
 def test_full_size_short_prefill(gpu, q_len):
     """LLaMA2-70B shard, one sequence of 128 tokens (the shape of the paper's latency breakdown,
