@@ -533,10 +533,9 @@ struct EpiQKV {
 // the slices in ascending order, rounds, and appends the new key and value to the cache.
 struct EpiQKVPart {
     static constexpr bool kNeedsRs = true;
-    static constexpr bool kSliced = true;      // a kernel whose workgroups own one K slice each sets `ks` and calls operator()
+    static constexpr bool kSliced = true;      // a kernel whose workgroups own one K slice each calls slice() with its slice number
     int M, q_len, q, kv, d, h, nqkv, nch, m_pad;
     int part_rows;             // token rows per slice of `part`
-    int ks = 0;
     float eps;
     const float *ss, *cosT, *sinT;
     const float *wsc;
@@ -580,7 +579,7 @@ struct EpiQKVPart {
         *(float4 *)(dst + cb) = hi;
     }
     __device__ __forceinline__ void operator()(int pair, int mt, f32x4 a, f32x4 b, int lane, float rs, const Pre &p) const {
-        slice(pair, ks, mt, a, b, lane, rs, p);
+        slice(pair, 0, mt, a, b, lane, rs, p);
     }
 };
 
@@ -1407,8 +1406,7 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
         kslice = bid / wgs_per_slice;
         bid -= kslice * wgs_per_slice;
     }
-    Epi epi = epi_in;
-    if constexpr (Epi::kSliced) epi.ks = kslice;
+    const Epi &epi = epi_in;      // (used where the launch put it: a copy of an epilogue with a table of positions would live in scratch memory)
     const int kt_first = (int)(((long)kslice * KT) / kslices), kt_end = (int)(((long)(kslice + 1) * KT) / kslices);
     int tn, tm, sub = 0;
     {
@@ -1599,7 +1597,8 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
         for (int i = 0; i < GL_TI; i += 2) {
             const int nt = nt0 + wn * GL_TI + i;
             if (nt >= n_ntiles) continue;
-            epi(nt >> 1, mt, acc[i][j], acc[i + 1][j], lane, rs[j], pre[i / 2]);
+            if constexpr (Epi::kSliced) epi.slice(nt >> 1, kslice, mt, acc[i][j], acc[i + 1][j], lane, rs[j], pre[i / 2]);
+            else epi(nt >> 1, mt, acc[i][j], acc[i + 1][j], lane, rs[j], pre[i / 2]);
         }
     }
 }
