@@ -1364,19 +1364,22 @@ __global__ void __launch_bounds__(256) k_qkv_gather(const float *__restrict__ pa
 // ------------------------------------------------------------------------------------------
 // Tile shapes.  WN x WM waves, each TI n-tiles x TJ m-tiles; KPS k-tiles per step.
 struct GemmBig {      // 8 waves, 256 x 256, steps of 64: one workgroup per compute unit (128 KiB of LDS)
-    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 8, KPS = 2, MINB = 1;
+    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 8, KPS = 2, MINB = 1, NST = 2;
 };
 struct GemmMid {      // 4 waves, 256 x 128, steps of 32: 48 KiB of LDS, two or three workgroups per compute unit
-    static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2;
+    static constexpr int WN = 2, WM = 2, TI = 8, TJ = 4, KPS = 1, MINB = 2, NST = 2;
 };
-struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile (96 KiB of LDS: still one workgroup per compute unit)
-    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 4, KPS = 2, MINB = 1;
+#ifndef SPD_HALF_NST
+#define SPD_HALF_NST 3
+#endif
+struct GemmHalf {     // 8 waves, 256 x 128, steps of 64: half of a GemmBig tile, three stages of 48 KiB (one workgroup per compute unit)
+    static constexpr int WN = 4, WM = 2, TI = 4, TJ = 4, KPS = 2, MINB = 1, NST = SPD_HALF_NST;
 };
 struct GemmTall {     // 8 waves, 128 x 384, steps of 64: for few n-tiles, where 256 x 256 tiles leave compute units idle
-    static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1;
+    static constexpr int WN = 2, WM = 4, TI = 4, TJ = 6, KPS = 2, MINB = 1, NST = 2;
 };
 struct GemmWide {     // 8 waves, 160 x 256, every wave all 10 n-tiles of 2 m-tiles: for split activations and few n-tiles
-    static constexpr int WN = 1, WM = 8, TI = 10, TJ = 2, KPS = 2, MINB = 1;      // (80 n-tiles x 512 m-tiles = exactly 256 tiles)
+    static constexpr int WN = 1, WM = 8, TI = 10, TJ = 2, KPS = 2, MINB = 1, NST = 2;      // (80 n-tiles x 512 m-tiles = exactly 256 tiles)
 };
 // XS: the activations are hi + lo pairs (second plane at Xlo).  A step then covers ONE k-tile: its weight
 // fragments and, per m-tile, the hi and the lo fragment of that k-tile, so the copies and the fragment
@@ -1515,19 +1518,29 @@ __global__ void __launch_bounds__(G::WN * G::WM * 64, G::MINB) k_gemm_lds(const 
                     }
                 }
         };
-        issue(0, 0);
-        if (nks > 1) issue(1, 1);
+        // NST stages: the copies of step ks + NST go into the stage that step ks frees at its barrier.  With three
+        // stages (tiles whose step is too short for a copy to arrive within one step) a wave has the copies of two
+        // steps in flight at the barrier and waits for the older ones only.
+        constexpr int NST = G::NST;
+        static_assert(NST == 2 || (NST == 3 && !RAGGED), "three stages: every wave issues the same number of copies");
+#pragma unroll
+        for (int s0 = 0; s0 < NST; ++s0)
+            if (s0 < nks) issue(s0, s0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < GL_TI + GL_TJ; ++r) rd1(lds, 0, r, a0, b0);
+        int cur = 0;
         for (int ks = 0; ks < nks; ++ks) {
-            const int cur = ks & 1;
+            const int nxt = cur + 1 == NST ? 0 : cur + 1;
             mm(a0, b0, lds + cur * GL_STAGE, 1, a1, b1, false, 0, 0);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's copies of the next step have landed
+            // this wave's copies of the next step have landed
+            if (NST == 3 && ks + 2 < nks) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GL_NCP) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             // (in the last step: fragments read and never used)
-            mm(a1, b1, lds + (cur ^ 1) * GL_STAGE, 0, a0, b0, ks + 2 < nks, cur, ks + 2);
+            mm(a1, b1, lds + nxt * GL_STAGE, 0, a0, b0, ks + NST < nks, cur, ks + NST);
+            cur = nxt;
         }
     } else {
         issue(0, 0);
@@ -1609,13 +1622,14 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     // with msub = 2 the tiles are counted in the shape of twice G's height (GemmHalf finishing a GemmBig launch)
     constexpr int BN = G::WN * G::TI;
     constexpr int STAGE = (BN * (XS ? 1 : G::KPS) + G::WM * G::TJ * (XS ? 2 : G::KPS)) * 1024;
-    static_assert(2 * STAGE <= 160 * 1024, "two stages must fit the LDS of a compute unit");
+    constexpr int NST = (!XS && G::KPS == 2) ? G::NST : 2;       // (only the loop with steps of two k-tiles knows three stages)
+    static_assert(NST * STAGE <= 160 * 1024, "the stages must fit the LDS of a compute unit");
     const int BM = G::WM * G::TJ * msub;
     // the attribute is per kernel instantiation: set once, whichever thread comes first
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G, XS>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+        attr_err = hipFuncSetAttribute((const void *)k_gemm_lds<Epi, G, XS>, hipFuncAttributeMaxDynamicSharedMemorySize, NST * STAGE);
     });
     if (attr_err != hipSuccess) return attr_err;
     const int n_ntiles = 2 * n_pairs, n_mtiles = (c.M + 15) / 16;
@@ -1626,7 +1640,7 @@ hipError_t launch_gemm_lds_cfg(const spd_call &c, const __bf16 *Wp, const __bf16
     if (n_tiles < 0) n_tiles = ord.TN * ord.TM - tile0;
     // msub = 1: whole rounds of 256, then eight equal shares (the spare workgroups of a ragged share exit at once)
     const int n_wgs = msub == 1 ? spd_tile_launch_size(n_tiles) : n_tiles * msub;
-    hipLaunchKernelGGL((k_gemm_lds<Epi, G, XS>), dim3(n_wgs * kslices), dim3(G::WN * G::WM * 64), 2 * STAGE, c.s, Wp, Xp, Xlo, KT,
+    hipLaunchKernelGGL((k_gemm_lds<Epi, G, XS>), dim3(n_wgs * kslices), dim3(G::WN * G::WM * 64), NST * STAGE, c.s, Wp, Xp, Xlo, KT,
                        n_ntiles, n_mtiles, ord, tile0, n_tiles, msub, kslices, n_wgs, epi);
     return hipGetLastError();
 }
