@@ -245,7 +245,11 @@ SMALL_BIAS = Workload(name="small-bf16-bias", hidden=256, n_q_heads=8, n_kv_head
                       tp=4, dtype=BF16, seed=16, batch=3, q_len=1, ctx=64, mask=(1, 0, 1))
 
 
-@pytest.mark.parametrize("w", [TOY_BIAS, SMALL_BIAS], ids=lambda w: w.name)
+SMALL_BIAS8 = Workload(name="small-bf16-bias-tp8", hidden=256, n_q_heads=16, n_kv_heads=8, head_dim=32, ffn=1024, n_layers=3,
+                       tp=8, dtype=BF16, seed=17, batch=3, q_len=1, ctx=64, mask=(1, 0, 1))
+
+
+@pytest.mark.parametrize("w", [TOY_BIAS, SMALL_BIAS, SMALL_BIAS8], ids=lambda w: w.name)
 @pytest.mark.parametrize("batch,q_len,positions",
                          [(3, 1, [0, 9, 30]), (2, 10, [0, 4]), (2, 40, [0, 8]), (3, 181, [0, 3, 0]), (2, 1030, [0, 8])],
                          ids=["decode", "chunk20", "chunk80", "chunk543", "chunk2060"])
@@ -253,7 +257,8 @@ SMALL_BIAS = Workload(name="small-bf16-bias", hidden=256, n_q_heads=8, n_kv_head
 def test_block_with_bias(gpu, w, batch, q_len, positions, mode):
     """Three blocks (SPD, TP, SPD) with a bias of the size of the activations on the output projection:
     model forward against the oracle, with every rank emulated and from one rank's point of view (whose bf16 call
-    of 2 x 1030 tokens runs as two chains, the bias joining the rank-sums of their preparation kernel)."""
+    of 2 x 1030 tokens runs as two chains, the bias joining the rank-sums of their preparation kernel: four slots in
+    the 4-way shard, eight in the 8-way one)."""
     import torch
     M = batch * q_len
     ranks = list(range(w.tp)) if mode == "all-ranks" else [1]
