@@ -71,7 +71,7 @@ int check_call(const spd_ctx *ctx, int32_t rank, const int32_t *positions, int32
 
 // The part of a block between its input and the rank-sum that ends it.  On return the
 // slots hold the partial sums of the final sync point and *base_out is what they are added
-// to: X for an SPD block ("X is added after the sync operation"), R = X + sum Y for a TP
+// to: X for an SPD block (Sec. 4.1.1: the block input joins after the remaining sync point), R = X + sum Y for a TP
 // block.  *syncs is incremented by the number of kept attention sync points (0 or 1).
 // With end_sync_out (one rank, bf16 path, at most 16 tokens) the last kernel of the block also
 // performs that final rank-sum into x_out (and the next block's first-norm preparation when
