@@ -92,7 +92,7 @@ def test_spd_changes_only_what_each_mlp_sees(sh):
         # the MLP partial of device r is the MLP applied to X + Y_r (SPD) or X + sum Y (TP)
         np.testing.assert_allclose(ds["Z"][r], O.mlp_partial(sh, X + ds["Y"][r], shards[r]), rtol=1e-12)
         np.testing.assert_allclose(dt["Z"][r], O.mlp_partial(sh, X + sum(dt["Y"]), shards[r]), rtol=1e-12)
-    # "complete form of output": X + sum Y_i + sum Z_i
+    # Sec. 4.1.1: the whole output of the block is X + sum Y_i + sum Z_i
     np.testing.assert_allclose(spd, X + sum(ds["Y"]) + sum(ds["Z"]), rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(spd - tp, sum(ds["Z"]) - sum(dt["Z"]), rtol=1e-9, atol=1e-11)
     assert np.max(np.abs(spd - tp)) > 1e-3                          # a different function
