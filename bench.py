@@ -92,10 +92,17 @@ def stage_kernel(w, stage: str) -> str:
     two_chains = w.q_len > 1 and w.batch >= 2 and (w.batch // 2) * w.q_len >= 1024
     if stage == "gateup":
         if M > 512:
-            tiles = ((2 * f_pairs + 15) // 16) * (((M // 2 if two_chains else M) // 16 + 15) // 16)
-            one = "k_gemm_lds<EpiGU,GemmBig,false>"
-            if tiles > 256 and 0 < tiles % 256 <= 128:
-                one += "+k_gemm_lds<EpiGU,GemmHalf,false>"
+            n16, mt = (2 * f_pairs + 15) // 16, ((M // 2 if two_chains else M) + 15) // 16
+            tiles, halves, tall = n16 * ((mt + 15) // 16), n16 * ((mt + 7) // 8), ((2 * f_pairs + 7) // 8) * ((mt + 23) // 24)
+            use_tall = tiles < 224 and tall <= 256 and tall > tiles
+            if tiles <= 128 and halves <= 256 and halves > (tall if use_tall else tiles):
+                one = "k_gemm_lds<EpiGU,GemmHalf,false>"
+            elif use_tall:
+                one = "k_gemm_lds<EpiGU,GemmTall,false>"
+            else:
+                one = "k_gemm_lds<EpiGU,GemmBig,false>"
+                if tiles > 256 and 0 < tiles % 256 <= 128:
+                    one += "+k_gemm_lds<EpiGU,GemmHalf,false>"
             return one + ("x2" if two_chains else "")          # x2: one launch per chain of a two-chain prefill
         if M > 16 and f_pairs >= 128:
             return "k_mid<8>+k_mid_finish<EpiGU>"
@@ -390,6 +397,7 @@ def main():
     ap.add_argument("--workload", default=None, help="one workload only (default: 70B decode headline + 70B prefill)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers than the workload names")
     ap.add_argument("--batch", type=int, default=None, help="exploration: another number of sequences than the workload names")
+    ap.add_argument("--q-len", type=int, default=None, help="exploration: another number of tokens per sequence than the workload names")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-synced", action="store_true", help="skip the all-sync-points-kept run")
@@ -434,6 +442,11 @@ def main():
         if args.batch:
             from dataclasses import replace
             w = replace(w, batch=args.batch, name=f"{w.name}+batch{args.batch}")
+        if args.q_len:
+            from dataclasses import replace
+            # (a prefill from an empty cache: the context is the call itself, rounded up to whole key blocks)
+            w = replace(w, q_len=args.q_len, ctx=max(w.ctx if w.q_len == 1 else 0, (args.q_len + 31) // 32 * 32),
+                        name=f"{w.name}+qlen{args.q_len}")
         return w
 
     def steps_of(w):
