@@ -1728,7 +1728,7 @@ __device__ __forceinline__ void load_kv(KVFrags<DT> &f, const __bf16 *__restrict
 
 // one 32-key block: keys [vb*32, vb*32+32) of one (sequence, KV head); n_keys_col = number of
 // keys column lane%16 may attend (causal), 0 for a padding column
-template <int DT, bool LAZY = false>      // LAZY: the running output is rescaled only when some column's maximum moved
+template <int DT, bool LAZY = false>      // LAZY (prefill): the running output is rescaled only when some column's maximum moved; probabilities on one plane
 __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__restrict__ qf, const KVFrags<DT> &f, int vb,
                                            int n_keys_col, float scale, int lane) {
     // qf[0 .. DT/2) are the hi halves of the query fragments, qf[DT/2 .. DT) the lo halves
@@ -1764,13 +1764,19 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
     ps = quad_sum(ps);
     st.l = st.l * alpha + ps;
     st.m = m_new;
-    bf16x8 pb, pl;      // probabilities as hi + lo pairs
+    // probabilities: hi + lo pairs in a decode step (bound by the cache stream, the second pass is free); one bf16
+    // plane in a prefill, which is bound by this vector work: a probability's rounding error (2^-9 relative) reaches
+    // the block output through a sum over keys and the O projection, and measured 7.0e-3 -> 7.6e-3 there
+    constexpr bool PLO = !LAZY;
+    bf16x8 pb, pl;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         pb[i] = (__bf16)p0[i];
         pb[4 + i] = (__bf16)p1[i];
-        pl[i] = (__bf16)(p0[i] - (float)pb[i]);
-        pl[4 + i] = (__bf16)(p1[i] - (float)pb[4 + i]);
+        if (PLO) {
+            pl[i] = (__bf16)(p0[i] - (float)pb[i]);
+            pl[4 + i] = (__bf16)(p1[i] - (float)pb[4 + i]);
+        }
     }
     // (a factor of exactly 1 changes nothing: skipping the multiplication when no column of the wave needs it
     // gives the same bits; in a causal prefill the maxima settle after the first blocks)
@@ -1781,7 +1787,7 @@ __device__ __forceinline__ void attn_block(AttnState<DT> &st, const bf16x8 *__re
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
         st.o[dt] = MFMA(f.v[dt], pb, st.o[dt]);
-        st.o[dt] = MFMA(f.v[dt], pl, st.o[dt]);
+        if (PLO) st.o[dt] = MFMA(f.v[dt], pl, st.o[dt]);
     }
 }
 
